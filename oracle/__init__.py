@@ -1,0 +1,13 @@
+"""CPU fp64 oracle for the DiT attention hot path -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the GPU library never does.  See dit_oracle.c for what is computed and why.
+"""
+from .dit_oracle import (  # noqa: F401
+    build,
+    cross_attn,
+    num_threads,
+    rope3d,
+    self_attn,
+    token_positions,
+)

@@ -1,0 +1,146 @@
+"""ctypes binding of oracle/dit_oracle.c (test infrastructure, fp64, CPU only).
+
+Arrays go in as numpy: uint16 (bf16 bit patterns), float32 or float64, dense
+[B, L, H, D].  Results come back as float64.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dit_oracle.c")
+_LIB = os.path.join(_HERE, "libdit_oracle.so")
+_lib = None
+
+_I32x3 = ctypes.c_int32 * 3
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = ctypes.c_int
+        for name in ("oracle_self_attn", "oracle_cross_attn", "oracle_rope3d",
+                     "oracle_token_positions"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def _dtype_code(a):
+    if a.dtype == np.uint16:
+        return 0
+    if a.dtype == np.float32:
+        return 1
+    if a.dtype == np.float64:
+        return 2
+    raise TypeError("oracle inputs must be uint16 (bf16 bits), float32 or float64, got %s" % a.dtype)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def token_positions(grid, origin=(0, 0, 0), n_tokens=None):
+    n = int(np.prod(grid)) if n_tokens is None else int(n_tokens)
+    out = np.empty((n, 3), dtype=np.int64)
+    rc = _load().oracle_token_positions(_I32x3(*grid), _I32x3(*origin), ctypes.c_int64(n), _ptr(out))
+    assert rc == 0
+    return out
+
+
+def rope3d(x, pos, split, base=10000.0):
+    """Rotate x[L, D] (float64) at integer positions pos[L, 3]."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    pos = np.ascontiguousarray(pos, dtype=np.int64)
+    L, D = x.shape
+    assert pos.shape == (L, 3)
+    y = np.empty_like(x)
+    rc = _load().oracle_rope3d(_ptr(x), _ptr(y), ctypes.c_int64(L), ctypes.c_int32(D), _ptr(pos),
+                               _I32x3(*split), ctypes.c_double(base))
+    if rc != 0:
+        raise ValueError("oracle_rope3d rejected its arguments (rc=%d)" % rc)
+    return y
+
+
+def self_attn(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, scale=0.0, rows=None,
+              want_lse=False, probs_of=None):
+    """Self-attention with 3-axis RoPE.  q, k, v: [B, L, H, D].
+
+    rows: token indices to compute (default: all).  Returns out [B, n_rows, H, D] float64,
+    plus lse [B, H, n_rows] if want_lse, plus probs [n_rows, L] of (b, h) = probs_of.
+    """
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    dt = _dtype_code(q)
+    assert k.dtype == q.dtype and v.dtype == q.dtype and q.shape == k.shape == v.shape
+    B, L, H, D = q.shape
+    assert L == int(np.prod(grid)), "L must equal T*Hg*Wg"
+    rows = np.arange(L, dtype=np.int64) if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    n_rows = rows.shape[0]
+    out = np.empty((B, n_rows, H, D), dtype=np.float64)
+    lse = np.empty((B, H, n_rows), dtype=np.float64) if want_lse else None
+    probs = np.empty((n_rows, L), dtype=np.float64) if probs_of is not None else None
+    pb, ph = probs_of if probs_of is not None else (0, 0)
+    rc = _load().oracle_self_attn(
+        _ptr(q), _ptr(k), _ptr(v), ctypes.c_int32(dt), ctypes.c_int32(B), ctypes.c_int32(H),
+        ctypes.c_int32(D), _I32x3(*grid), _I32x3(*origin), _I32x3(*split), ctypes.c_double(base),
+        ctypes.c_double(scale), _ptr(rows), ctypes.c_int64(n_rows), _ptr(out), _ptr(lse),
+        _ptr(probs), ctypes.c_int32(pb), ctypes.c_int32(ph))
+    if rc != 0:
+        raise ValueError("oracle_self_attn rejected its arguments (rc=%d)" % rc)
+    res = (out,)
+    if want_lse:
+        res += (lse,)
+    if probs_of is not None:
+        res += (probs,)
+    return res[0] if len(res) == 1 else res
+
+
+def cross_attn(q, k, v, kv_valid=None, scale=0.0, rows=None, want_lse=False, probs_of=None):
+    """Cross-attention, joint softmax over Lk keys with a key-padding mask.
+
+    q: [B, Lq, H, D]; k, v: [B, Lk, H, D]; kv_valid: [B, Lk] uint8 (1 = attend) or None.
+    """
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    dt = _dtype_code(q)
+    assert k.dtype == q.dtype and v.dtype == q.dtype and k.shape == v.shape
+    B, Lq, H, D = q.shape
+    Lk = k.shape[1]
+    assert k.shape == (B, Lk, H, D)
+    if kv_valid is not None:
+        kv_valid = np.ascontiguousarray(kv_valid, dtype=np.uint8)
+        assert kv_valid.shape == (B, Lk)
+    rows = np.arange(Lq, dtype=np.int64) if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    n_rows = rows.shape[0]
+    out = np.empty((B, n_rows, H, D), dtype=np.float64)
+    lse = np.empty((B, H, n_rows), dtype=np.float64) if want_lse else None
+    probs = np.empty((n_rows, Lk), dtype=np.float64) if probs_of is not None else None
+    pb, ph = probs_of if probs_of is not None else (0, 0)
+    rc = _load().oracle_cross_attn(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(kv_valid), ctypes.c_int32(dt), ctypes.c_int32(B),
+        ctypes.c_int32(H), ctypes.c_int32(D), ctypes.c_int64(Lq), ctypes.c_int64(Lk),
+        ctypes.c_double(scale), _ptr(rows), ctypes.c_int64(n_rows), _ptr(out), _ptr(lse),
+        _ptr(probs), ctypes.c_int32(pb), ctypes.c_int32(ph))
+    if rc != 0:
+        raise ValueError("oracle_cross_attn rejected its arguments (rc=%d)" % rc)
+    res = (out,)
+    if want_lse:
+        res += (lse,)
+    if probs_of is not None:
+        res += (probs,)
+    return res[0] if len(res) == 1 else res

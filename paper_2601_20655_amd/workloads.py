@@ -1,0 +1,93 @@
+"""Seeded synthetic workloads for the DiT attention hot path.
+
+This module only *generates inputs* (shapes, N(0,1) values, bf16 bit patterns, key-padding
+masks, sampled row lists).  It holds none of the attention arithmetic, so both the GPU
+library's tests and the CPU oracle's tests can be fed from it.
+
+The tensors stand in for the activations of a Wan2.1-class video diffusion transformer
+(the Diffusion stage of the paper's image-to-video workflow, Sec. 2.4): same shapes, same
+dense (T,Hg,Wg) position lattice, unit-variance values.  No trained weights are involved.
+"""
+import numpy as np
+
+# name -> description of the five reference shapes
+CONFIGS = {
+    "tiny": dict(kind="self", B=1, grid=(4, 8, 8), H=4, D=64, split=(22, 20, 22), dtype="f32",
+                 seed=20655 + 1),
+    "dit_1p3b": dict(kind="self", B=1, grid=(21, 30, 52), H=12, D=128, split=(44, 42, 42),
+                     dtype="bf16", seed=20655 + 2),
+    "dit_14b": dict(kind="self", B=1, grid=(21, 30, 52), H=40, D=128, split=(44, 42, 42),
+                    dtype="bf16", seed=20655 + 3),
+    "dit_14b_hires": dict(kind="self", B=1, grid=(21, 45, 80), H=40, D=128, split=(44, 42, 42),
+                          dtype="bf16", seed=20655 + 4),
+    "cross_14b": dict(kind="cross", B=4, Lq=32760, n_text=512, n_image=257, H=40, D=128,
+                      dtype="bf16", min_text=16, seed=20655 + 5),
+    # mid-size shape for an all-rows comparison that spans several tiles and a ragged tail
+    "mid": dict(kind="self", B=1, grid=(4, 30, 52), H=4, D=128, split=(44, 42, 42),
+                dtype="bf16", seed=20655 + 6),
+}
+
+
+def f32_to_bf16_bits(x):
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return rounded.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b):
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def normal(shape, seed, stream, dtype="bf16", gain=1.0):
+    """iid N(0, gain^2) tensor; stream separates q/k/v.  bf16 -> uint16 bit patterns."""
+    rng = np.random.default_rng([int(seed), int(stream)])
+    x = rng.standard_normal(size=shape, dtype=np.float32)
+    if gain != 1.0:
+        x *= np.float32(gain)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    if dtype == "f32":
+        return x
+    raise ValueError(dtype)
+
+
+def self_attn_inputs(cfg, seed=None, gain=1.0, dtype=None):
+    """q, k, v of shape [B, L, H, D] for a self-attention config dict."""
+    T, Hg, Wg = cfg["grid"]
+    shape = (cfg["B"], T * Hg * Wg, cfg["H"], cfg["D"])
+    seed = cfg["seed"] if seed is None else seed
+    dtype = cfg["dtype"] if dtype is None else dtype
+    return tuple(normal(shape, seed, s, dtype, gain if s < 2 else 1.0) for s in range(3))
+
+
+def cross_attn_inputs(cfg, seed=None, dtype=None):
+    """q [B,Lq,H,D], k, v [B,Lk,H,D], kv_valid [B,Lk] uint8, text_len [B].
+
+    Keys [0, n_text) are text tokens of which the first text_len[b] are valid
+    (text_len ~ U{min_text..n_text}); keys [n_text, n_text+n_image) are image tokens,
+    always valid.
+    """
+    seed = cfg["seed"] if seed is None else seed
+    dtype = cfg["dtype"] if dtype is None else dtype
+    B, H, D = cfg["B"], cfg["H"], cfg["D"]
+    Lk = cfg["n_text"] + cfg["n_image"]
+    q = normal((B, cfg["Lq"], H, D), seed, 0, dtype)
+    k = normal((B, Lk, H, D), seed, 1, dtype)
+    v = normal((B, Lk, H, D), seed, 2, dtype)
+    rng = np.random.default_rng([int(seed), 3])
+    text_len = rng.integers(cfg["min_text"], cfg["n_text"] + 1, size=B)
+    valid = np.zeros((B, Lk), dtype=np.uint8)
+    for b in range(B):
+        valid[b, : text_len[b]] = 1
+        valid[b, cfg["n_text"]:] = 1
+    return q, k, v, valid, text_len
+
+
+def sample_rows(L, seed, edge=64, n_random=128):
+    """First `edge` rows, last `edge` rows and n_random seeded rows in between (sorted, unique)."""
+    if L <= 2 * edge + n_random:
+        return np.arange(L, dtype=np.int64)
+    rng = np.random.default_rng([int(seed), 7])
+    mid = rng.choice(np.arange(edge, L - edge), size=n_random, replace=False)
+    return np.unique(np.concatenate([np.arange(edge), np.arange(L - edge, L), mid])).astype(np.int64)

@@ -1,0 +1,328 @@
+"""Pins for the CPU fp64 oracle: facts fixed by mathematics, not by the oracle itself.
+
+Each test would fail for a plausible mistake somewhere in oracle/dit_oracle.c (a dropped
+term, wrong sign, wrong index, transposed operand, wrong section order, mask leak).
+The brute-force comparator below is an independent formulation: positions by nested
+loops, rotation by complex multiplication, scores as Re<zq, conj zk>, softmax by an
+explicit normalised-exponential loop in Python floats / numpy longdouble.
+"""
+import cmath
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+
+SPLITS = {4: (2, 2, 0), 6: (2, 2, 2), 8: (4, 2, 2), 64: (22, 20, 22)}
+
+
+def brute_self_attn(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, scale=None):
+    """q, k, v: float arrays [L, D] of ONE head. Returns out [L, D], lse [L], probs [L, L]."""
+    L, D = q.shape
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    pos = [(origin[0] + t, origin[1] + h, origin[2] + w)
+           for t in range(grid[0]) for h in range(grid[1]) for w in range(grid[2])]
+    assert len(pos) == L
+
+    def to_complex(x, p):
+        z, o = [], 0
+        for a in range(3):
+            for i in range(split[a] // 2):
+                w = base ** (-2.0 * i / split[a])
+                z.append(complex(x[o + 2 * i], x[o + 2 * i + 1]) * cmath.exp(1j * p[a] * w))
+            o += split[a]
+        return z
+
+    zq = [to_complex(q[n], pos[n]) for n in range(L)]
+    zk = [to_complex(k[n], pos[n]) for n in range(L)]
+    out = np.zeros((L, D))
+    lse = np.zeros(L)
+    probs = np.zeros((L, L))
+    for n in range(L):
+        s = [scale * sum((a * b.conjugate()).real for a, b in zip(zq[n], zk[m])) for m in range(L)]
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        z = math.fsum(e)
+        for m in range(L):
+            probs[n, m] = e[m] / z
+            out[n] += (e[m] / z) * v[m]
+        lse[n] = mx + math.log(z)
+    return out, lse, probs
+
+
+@pytest.mark.parametrize("grid,D", [((1, 1, 1), 4), ((1, 1, 2), 6), ((2, 2, 2), 8), ((2, 3, 4), 8),
+                                    ((2, 3, 4), 64), ((3, 2, 2), 6)])
+def test_p1_brute_force_tiny_grids(grid, D, rng):
+    L, H = int(np.prod(grid)), 2
+    q, k, v = (rng.standard_normal((1, L, H, D)) for _ in range(3))
+    split = SPLITS[D]
+    out, lse = oracle.self_attn(q, k, v, grid, split, want_lse=True)
+    for h in range(H):
+        bo, bl, _ = brute_self_attn(q[0, :, h], k[0, :, h], v[0, :, h], grid, split)
+        np.testing.assert_allclose(out[0, :, h], bo, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse[0, h], bl, rtol=0, atol=1e-12)
+
+
+def test_p1_brute_force_origin_scale_base(rng):
+    grid, D, split = (2, 2, 3), 8, (2, 4, 2)
+    L = 12
+    q, k, v = (rng.standard_normal((1, L, 1, D)) for _ in range(3))
+    out = oracle.self_attn(q, k, v, grid, split, origin=(3, -2, 5), base=100.0, scale=0.37)
+    bo, _, _ = brute_self_attn(q[0, :, 0], k[0, :, 0], v[0, :, 0], grid, split, origin=(3, -2, 5),
+                               base=100.0, scale=0.37)
+    np.testing.assert_allclose(out[0, :, 0], bo, rtol=0, atol=1e-12)
+
+
+def test_closed_form_two_tokens():
+    """L=2, D=2, one axis: scores are 1/sqrt(2) * [cos(0), cos(1 rad)] for row 0 by hand."""
+    q = np.zeros((1, 2, 1, 2)); k = np.zeros((1, 2, 1, 2)); v = np.zeros((1, 2, 1, 2))
+    q[0, :, 0] = [[1.0, 0.0], [0.0, 2.0]]
+    k[0, :, 0] = [[1.0, 0.0], [1.0, 0.0]]
+    v[0, :, 0] = [[1.0, 10.0], [3.0, -10.0]]
+    out, lse = oracle.self_attn(q, k, v, (2, 1, 1), (2, 0, 0), want_lse=True)
+    sc = 1.0 / math.sqrt(2.0)
+    # row 0: q at angle 0; key 0 at angle 0, key 1 rotated by +1 rad -> dot = cos(1)
+    s0 = np.array([sc * 1.0, sc * math.cos(1.0)])
+    # row 1: q = 2j rotated by +1 rad; key0 = 1 -> Re(2j e^{j} * 1) = -2 sin 1; key1 = e^{j} -> Re(2j) = 0
+    s1 = np.array([sc * (-2.0 * math.sin(1.0)), 0.0])
+    for n, s in enumerate((s0, s1)):
+        p = np.exp(s) / np.exp(s).sum()
+        np.testing.assert_allclose(out[0, n, 0], p[0] * v[0, 0, 0] + p[1] * v[0, 1, 0], atol=1e-14)
+        assert abs(lse[0, 0, n] - math.log(np.exp(s).sum())) < 1e-14
+
+
+def test_p2_softmax_rows_sum_to_one(rng):
+    grid, D = (3, 4, 5), 8
+    L = 60
+    q, k, v = (rng.standard_normal((2, L, 3, D)) * 3 for _ in range(3))
+    _, probs = oracle.self_attn(q, k, v, grid, SPLITS[8], probs_of=(1, 2))
+    assert probs.shape == (L, L)
+    assert np.all(probs >= 0)
+    assert np.max(np.abs(probs.sum(axis=1) - 1.0)) < 1e-14
+    qc, kc, vc = rng.standard_normal((2, 7, 2, 8)), rng.standard_normal((2, 9, 2, 8)), rng.standard_normal((2, 9, 2, 8))
+    valid = np.array([[1, 0, 1, 1, 0, 0, 1, 1, 1], [0, 0, 0, 0, 1, 0, 0, 0, 0]], dtype=np.uint8)
+    _, pc = oracle.cross_attn(qc, kc, vc, valid, probs_of=(0, 1))
+    assert np.max(np.abs(pc.sum(axis=1) - 1.0)) < 1e-14
+    assert np.all(pc[:, valid[0] == 0] == 0.0)
+
+
+def test_p3_constant_v(rng):
+    grid, D = (2, 3, 4), 8
+    L = 24
+    q, k = (rng.standard_normal((1, L, 2, D)) * 2 for _ in range(2))
+    c = rng.standard_normal(D)
+    v = np.broadcast_to(c, (1, L, 2, D)).copy()
+    out = oracle.self_attn(q, k, v, grid, SPLITS[8])
+    np.testing.assert_allclose(out, np.broadcast_to(c, out.shape), atol=1e-14)
+    valid = (rng.random((1, L)) < 0.5).astype(np.uint8)
+    valid[0, 3] = 1
+    outc = oracle.cross_attn(q, k, v, valid)
+    np.testing.assert_allclose(outc, np.broadcast_to(c, outc.shape), atol=1e-14)
+
+
+def test_p4_rope_shift_invariance(rng):
+    grid, D = (3, 4, 5), 64
+    L = 60
+    q, k, v = (rng.standard_normal((1, L, 2, D)) for _ in range(3))
+    a = oracle.self_attn(q, k, v, grid, SPLITS[64], origin=(0, 0, 0))
+    b = oracle.self_attn(q, k, v, grid, SPLITS[64], origin=(7, -3, 11))
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-10)
+    # but not invariant to a shift of the keys alone (positions matter): shift q/k differently
+    pos0 = oracle.token_positions(grid)
+    kr0 = oracle.rope3d(k[0, :, 0], pos0, SPLITS[64])
+    kr1 = oracle.rope3d(k[0, :, 0], pos0 + np.array([1, 0, 0]), SPLITS[64])
+    assert np.max(np.abs(kr0 - kr1)) > 1e-3
+
+
+def test_p5_single_key(rng):
+    q, k, v = (rng.standard_normal((1, 1, 3, 8)) for _ in range(3))
+    out, lse = oracle.self_attn(q, k, v, (1, 1, 1), SPLITS[8], want_lse=True)
+    np.testing.assert_allclose(out, v, atol=0)
+    # lse = the single score; position 0 means no rotation
+    s = (q * k).sum(-1)[0, 0] / math.sqrt(8)
+    np.testing.assert_allclose(lse[0, :, 0], s, atol=1e-14)
+
+
+def test_p6_zero_query_gives_mean_of_valid_values(rng):
+    grid, D = (2, 2, 5), 8
+    L = 20
+    k, v = (rng.standard_normal((1, L, 2, D)) for _ in range(2))
+    q = np.zeros_like(k)
+    out, lse = oracle.self_attn(q, k, v, grid, SPLITS[8], want_lse=True)
+    np.testing.assert_allclose(out, np.broadcast_to(v.mean(axis=1, keepdims=True), out.shape), atol=1e-14)
+    np.testing.assert_allclose(lse, math.log(L), atol=1e-14)
+    valid = np.zeros((1, L), dtype=np.uint8)
+    valid[0, [1, 4, 5, 17]] = 1
+    outc, lsec = oracle.cross_attn(q, k, v, valid, want_lse=True)
+    want = v[:, [1, 4, 5, 17]].mean(axis=1, keepdims=True)
+    np.testing.assert_allclose(outc, np.broadcast_to(want, outc.shape), atol=1e-14)
+    np.testing.assert_allclose(lsec, math.log(4), atol=1e-14)
+
+
+def test_p7_dominant_key(rng):
+    Lq, Lk, D = 5, 11, 8
+    q = rng.standard_normal((1, Lq, 1, D))
+    k = rng.standard_normal((1, Lk, 1, D)) * 0.01
+    v = rng.standard_normal((1, Lk, 1, D))
+    for n in range(Lq):
+        m = (3 * n + 1) % Lk
+        kk = k.copy()
+        kk[0, m, 0] = 200.0 * q[0, n, 0]  # aligned with +q: must win (a sign error would pick the opposite)
+        out = oracle.cross_attn(q, kk, v, rows=[n])
+        np.testing.assert_allclose(out[0, 0, 0], v[0, m, 0], atol=1e-9)
+        kk[0, m, 0] = -200.0 * q[0, n, 0]
+        out = oracle.cross_attn(q, kk, v, rows=[n])
+        assert np.max(np.abs(out[0, 0, 0] - v[0, m, 0])) > 1e-3
+
+
+def test_p8_rope_isometry_and_identity(rng):
+    D, split = 64, SPLITS[64]
+    x = rng.standard_normal((50, D))
+    pos = rng.integers(-40, 90, size=(50, 3))
+    y = oracle.rope3d(x, pos, split)
+    np.testing.assert_allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-13)
+    # every pair keeps its own norm (rotation acts pairwise on (2i, 2i+1))
+    np.testing.assert_allclose(np.hypot(y[:, 0::2], y[:, 1::2]), np.hypot(x[:, 0::2], x[:, 1::2]), rtol=1e-12)
+    z = oracle.rope3d(x, np.zeros((50, 3), dtype=np.int64), split)
+    assert np.array_equal(z, x)
+    # first pair of every section has omega = 1: rotating by position p is a rotation by p radians
+    p = np.array([[2, 0, 0]])
+    e = np.zeros((1, D)); e[0, 0] = 1.0
+    r = oracle.rope3d(e, p, split)
+    np.testing.assert_allclose(r[0, :2], [math.cos(2.0), math.sin(2.0)], atol=1e-15)
+    e = np.zeros((1, D)); e[0, 22] = 1.0  # first channel of the h section for split 22/20/22
+    r = oracle.rope3d(e, np.array([[5, 3, 9]]), split)
+    np.testing.assert_allclose(r[0, 22:24], [math.cos(3.0), math.sin(3.0)], atol=1e-15)
+    e = np.zeros((1, D)); e[0, 43] = 1.0  # second channel of the first w pair: j * e^{j 9}
+    r = oracle.rope3d(e, np.array([[5, 3, 9]]), split)
+    np.testing.assert_allclose(r[0, 42:44], [-math.sin(9.0), math.cos(9.0)], atol=1e-15)
+    # last pair of the t section: omega = base^(-2*10/22)
+    e = np.zeros((1, D)); e[0, 20] = 1.0
+    r = oracle.rope3d(e, np.array([[4, 0, 0]]), split)
+    phi = 4.0 * 10000.0 ** (-20.0 / 22.0)
+    np.testing.assert_allclose(r[0, 20:22], [math.cos(phi), math.sin(phi)], atol=1e-15)
+
+
+def test_p9_reduces_to_1d_rope_closed_form(rng):
+    """Split (D,0,0) on an (L,1,1) grid: score(n,m) = scale * Re sum_i q_i conj(k_i) e^{j (n-m) w_i}."""
+    L, D = 9, 8
+    q, k, v = (rng.standard_normal((1, L, 1, D)) for _ in range(3))
+    _, lse, probs = oracle.self_attn(q, k, v, (L, 1, 1), (D, 0, 0), want_lse=True, probs_of=(0, 0))
+    w = 10000.0 ** (-2.0 * np.arange(D // 2) / D)
+    zq = q[0, :, 0, 0::2] + 1j * q[0, :, 0, 1::2]
+    zk = k[0, :, 0, 0::2] + 1j * k[0, :, 0, 1::2]
+    n = np.arange(L)
+    phase = np.exp(1j * (n[:, None, None] - n[None, :, None]) * w[None, None, :])
+    s = (zq[:, None, :] * np.conj(zk)[None, :, :] * phase).real.sum(-1) / math.sqrt(D)
+    want = np.exp(s - s.max(1, keepdims=True))
+    want /= want.sum(1, keepdims=True)
+    np.testing.assert_allclose(probs, want, atol=1e-13)
+    np.testing.assert_allclose(lse[0, 0], np.log(np.exp(s).sum(1)), atol=1e-12)
+    # the same tokens laid along w with split (0,0,D) must give the same result
+    _, probs_w = oracle.self_attn(q, k, v, (1, 1, L), (0, 0, D), probs_of=(0, 0))
+    np.testing.assert_allclose(probs_w, probs, atol=1e-14)
+
+
+def test_p10_axis_separability_and_section_order(rng):
+    D, split = 8, (4, 2, 2)
+    x = rng.standard_normal((1, D))
+    base_pos = np.array([[3, 4, 5]])
+    y0 = oracle.rope3d(x, base_pos, split)
+    for axis, sl in enumerate((slice(0, 4), slice(4, 6), slice(6, 8))):
+        p = base_pos.copy(); p[0, axis] += 2
+        y1 = oracle.rope3d(x, p, split)
+        changed = np.abs(y1 - y0) > 1e-12
+        assert changed[0, sl].any()
+        mask = np.ones(D, bool); mask[sl] = False
+        assert not changed[0, mask].any()
+    # swapping the h and w axes of the grid together with their sections and the token order
+    grid = (2, 3, 4)
+    L = 24
+    q, k, v = (rng.standard_normal((1, L, 1, D)) for _ in range(3))
+    out = oracle.self_attn(q, k, v, grid, (4, 2, 2))
+    perm = np.arange(L).reshape(2, 3, 4).transpose(0, 2, 1).reshape(-1)  # new token order (t, w, h)
+    chan = np.array([0, 1, 2, 3, 6, 7, 4, 5])
+    q2, k2 = (a[:, perm][..., chan] for a in (q, k))
+    v2 = v[:, perm]
+    out2 = oracle.self_attn(q2, k2, v2, (2, 4, 3), (4, 2, 2))
+    np.testing.assert_allclose(out2, out[:, perm], atol=1e-13)
+
+
+def test_p11_permutation_properties_cross(rng):
+    B, Lq, Lk, H, D = 2, 6, 13, 2, 8
+    q = rng.standard_normal((B, Lq, H, D)); k = rng.standard_normal((B, Lk, H, D)); v = rng.standard_normal((B, Lk, H, D))
+    valid = (rng.random((B, Lk)) < 0.7).astype(np.uint8); valid[:, 0] = 1
+    out = oracle.cross_attn(q, k, v, valid)
+    pk = rng.permutation(Lk)
+    out_k = oracle.cross_attn(q, k[:, pk], v[:, pk], valid[:, pk])
+    np.testing.assert_allclose(out_k, out, atol=1e-14)
+    pq = rng.permutation(Lq)
+    out_q = oracle.cross_attn(q[:, pq], k, v, valid)
+    np.testing.assert_allclose(out_q, out[:, pq], atol=0)
+    # heads and batches are independent: swapping heads swaps outputs
+    out_h = oracle.cross_attn(q[:, :, ::-1], k[:, :, ::-1], v[:, :, ::-1], valid)
+    np.testing.assert_allclose(out_h, out[:, :, ::-1], atol=0)
+    # rows= selects exactly those rows
+    sel = oracle.cross_attn(q, k, v, valid, rows=[4, 1])
+    np.testing.assert_allclose(sel, out[:, [4, 1]], atol=0)
+
+
+def test_p12_mask_equals_compaction(rng):
+    B, Lq, Lk, H, D = 1, 5, 17, 2, 8
+    q = rng.standard_normal((B, Lq, H, D)); k = rng.standard_normal((B, Lk, H, D)); v = rng.standard_normal((B, Lk, H, D))
+    valid = np.zeros((B, Lk), dtype=np.uint8); idx = [0, 2, 3, 9, 16]; valid[0, idx] = 1
+    k2, v2 = k.copy(), v.copy()
+    k2[0, valid[0] == 0] = 1e30; v2[0, valid[0] == 0] = -1e30  # garbage under the mask must not leak
+    out, lse = oracle.cross_attn(q, k2, v2, valid, want_lse=True)
+    outc, lsec = oracle.cross_attn(q, k[:, idx], v[:, idx], None, want_lse=True)
+    np.testing.assert_allclose(out, outc, atol=1e-14)
+    np.testing.assert_allclose(lse, lsec, atol=1e-14)
+    # fully masked request: zeros and lse = -inf
+    valid0 = np.zeros((B, Lk), dtype=np.uint8)
+    out0, lse0 = oracle.cross_attn(q, k, v, valid0, want_lse=True)
+    assert np.all(out0 == 0.0) and np.all(np.isneginf(lse0))
+
+
+def test_p13_lse_and_merge(rng):
+    B, Lq, Lk, H, D = 1, 4, 12, 1, 8
+    q = rng.standard_normal((B, Lq, H, D)) * 2; k = rng.standard_normal((B, Lk, H, D)); v = rng.standard_normal((B, Lk, H, D))
+    out, lse = oracle.cross_attn(q, k, v, None, want_lse=True, scale=0.5)
+    s = 0.5 * np.einsum("nd,md->nm", q[0, :, 0].astype(np.longdouble), k[0, :, 0].astype(np.longdouble))
+    np.testing.assert_allclose(lse[0, 0], np.log(np.exp(s).sum(1)).astype(np.float64), atol=1e-14)
+    va = np.zeros((B, Lk), np.uint8); va[0, :5] = 1
+    vb = 1 - va
+    oa, la = oracle.cross_attn(q, k, v, va, want_lse=True, scale=0.5)
+    ob, lb = oracle.cross_attn(q, k, v, vb, want_lse=True, scale=0.5)
+    wa = np.exp(la - lse)[0, 0][None, :, None, None]; wb = np.exp(lb - lse)[0, 0][None, :, None, None]
+    np.testing.assert_allclose(wa * oa + wb * ob, out, atol=1e-14)
+
+
+def test_dtype_widening_is_exact(rng):
+    """bf16 bit patterns and float32 inputs are widened, never rounded."""
+    from paper_2601_20655_amd import workloads as wl
+
+    grid, D = (2, 2, 3), 8
+    L = 12
+    x = [rng.standard_normal((1, L, 2, D)).astype(np.float32) for _ in range(3)]
+    bits = [wl.f32_to_bf16_bits(a) for a in x]
+    wide = [wl.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
+    a = oracle.self_attn(*bits, grid, SPLITS[8])
+    b = oracle.self_attn(*wide, grid, SPLITS[8])
+    c = oracle.self_attn(*[w.astype(np.float32) for w in wide], grid, SPLITS[8])
+    assert np.array_equal(a, b) and np.array_equal(a, c)
+    # bf16 rounding helper: ties to even on known patterns
+    t = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.0e-39], dtype=np.float32)  # 1+2^-8 ties down, 1+3*2^-8 ties up
+    got = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(t))
+    np.testing.assert_array_equal(got[:4], np.array([1.0, 1.0, 1.015625, -2.5], dtype=np.float32))
+
+
+def test_bad_arguments_are_rejected(rng):
+    q = rng.standard_normal((1, 4, 1, 8))
+    with pytest.raises(ValueError):
+        oracle.self_attn(q, q, q, (2, 2, 1), (4, 2, 1))  # odd section / wrong sum
+    with pytest.raises(ValueError):
+        oracle.self_attn(q, q, q, (2, 2, 1), (4, 2, 2), rows=[4])
+    with pytest.raises(ValueError):
+        oracle.cross_attn(q, q, q, rows=[-1])
