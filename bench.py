@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the DiT attention hot path on one MI355X.
+
+One step = the attention of one DiT block for one request at the 14B-class shape: self-attention
+over the 32,760 tokens of a 21x30x52 latent grid (40 heads, head_dim 128, 3-axis RoPE 44/42/42)
+followed by cross-attention of the same 32,760 queries over 769 conditioning keys (512 text with a
+padding mask + 257 image).  Inputs are seeded synthetic bf16 N(0,1) tensors resident in HBM before
+the timed region.  Prints ONE JSON line: whole-step attention TFLOP/s (4*H*Lq*Lk*D flop per
+product pair, RoPE/softmax/mask not counted), a roofline object for the dominant kernel (the
+self-attention kernel, timed with HIP events on its stream) and the CPU fp64 oracle timed on a
+bounded row sample as a baseline.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs (ctypes on the HIP runtime) for the library's timing hook."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs:
+            assert self.hip.hipEventSynchronize(b) == 0
+            ms = ctypes.c_float()
+            assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--flags", type=int, default=0, help="DIT_FLAG_* bits for both calls (0 = library defaults)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all heads of one request on one MI355X, no "
+                 "collectives); --gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    from paper_2601_20655_amd import binding as B
+    from paper_2601_20655_amd import workloads as wl
+
+    B.lib()  # fail loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    cfg = wl.CONFIGS["dit_14b"]
+    ccfg = dict(wl.CONFIGS["cross_14b"], B=1)
+    q, k, v = wl.self_attn_inputs(cfg)
+    cq, ck, cv, cvalid, text_len = wl.cross_attn_inputs(ccfg)
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+
+    qd, kd, vd = dev(q), dev(k), dev(v)
+    ckd, cvd = dev(ck), dev(cv)
+    cvalid_d = torch.from_numpy(cvalid).cuda()
+    Bsz, L, H, D = qd.shape
+    Lk = ckd.shape[1]
+    out = torch.empty_like(qd)
+    cout = torch.empty_like(qd)
+    ps = B.self_attn_params(qd, kd, vd, out, cfg["grid"], cfg["split"], flags=args.flags)
+    pc = B.cross_attn_params(out, ckd, cvd, cout, flags=args.flags & ~(B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_KV_PREPACK))
+    ws = torch.empty(max(B.dit_attn_workspace_bytes(ps), B.dit_cross_attn_workspace_bytes(pc), 256),
+                     dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        # the cross-attention consumes the self-attention output as its queries, as in a DiT block
+        B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
+                           stream=stream)
+        B.dit_cross_attn_forward(out, ckd, cvd, cvalid_d, out=cout, flags=pc.flags, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ev = HipEvents(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        a, b = ev.pairs[i]
+        B.dit_attn_set_timing_events(a, b)
+        B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
+                           stream=stream)
+        B.dit_attn_set_timing_events(None, None)
+        B.dit_cross_attn_forward(out, ckd, cvd, cvalid_d, out=cout, flags=pc.flags, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern_ms = ev.elapsed_ms()
+    ev.close()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops_self = 4.0 * Bsz * H * L * L * D
+    flops_cross = 4.0 * Bsz * H * L * Lk * D  # dense count over all 769 keys
+    tflops = (flops_self + flops_cross) / (ms_per_step * 1e-3) / 1e12
+    kern_avg_ms = float(np.mean(kern_ms))
+    achieved = flops_self / (kern_avg_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "attention TFLOP/s + % bf16 MFMA peak at 32,760 tokens x 40 heads x d128",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16" if not (args.flags & B.DIT_FLAG_QK_BF16) else "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "dit_14b self-attention (B=1, grid 21x30x52 = 32,760 tokens, 40 heads, d128, RoPE 44/42/42) "
+                        "+ cross-attention of the same queries over 769 keys (512 text masked to %d, 257 image)"
+                        % int(text_len[0]),
+            "io": "bf16 in, bf16 out; 16-bit MFMA operands, fp32 accumulate",
+            "flags": args.flags,
+            "pct_of_16bit_mfma_peak": round(100.0 * tflops / PEAK_TFLOPS_16BIT_DENSE, 2),
+            "self_attn_kernel_ms": round(kern_avg_ms, 4),
+            "flops_per_step": flops_self + flops_cross,
+        },
+        "roofline": {
+            "kernel": "attn_fwd_kernel (self-attention, 32,760 x 32,760 x 40 heads)",
+            "bound": "mfma",
+            "achieved": round(achieved, 2),
+            "peak": PEAK_TFLOPS_16BIT_DENSE,
+            "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_TFLOPS_16BIT_DENSE, 4),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        rows = wl.sample_rows(L, cfg["seed"], edge=64, n_random=128)
+        t0 = time.perf_counter()
+        ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], rows=rows)
+        dt = time.perf_counter() - t0
+        got = out[:, torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        result["cpu_baseline"] = {
+            "value": round(4.0 * Bsz * H * len(rows) * L * D / dt / 1e12, 5),
+            "unit": "TFLOP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "%d query rows x %d heads x all %d keys of the same self-attention (fp64, %.1f s); "
+                      "extrapolated full problem %.0f s" % (len(rows), H, L, dt, dt * L / len(rows)),
+            "gpu_vs_oracle_max_err_over_rms": round(float(np.abs(got - ref).max() / rms), 5),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

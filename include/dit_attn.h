@@ -1,0 +1,155 @@
+/*
+ * dit_attn.h -- C ABI of the MI355X (gfx950) DiT attention library.
+ *
+ * The library computes the attention of the Diffusion stage of a Wan2.1-class video
+ * diffusion transformer -- the "core generative component" of the image-to-video workflow
+ * the OnePiece paper serves (Sec. 2.4, "The AIGC Workflow") -- as the user function a
+ * TaskWorker runs on tensors that already sit in GPU memory (Sec. 4.4, "TaskWorker").
+ * The paper names this workload but gives no mathematics for it; what is computed is
+ * defined here, and a CPU fp64 statement of the same definition lives in oracle/.
+ *
+ * Common rules for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *    allocates, frees or synchronises: kernels are enqueued on `stream` (a hipStream_t
+ *    passed as void*, NULL = the default stream) and the call returns at once.
+ *  - Tensors are addressed as  base + b*stride.batch + n*stride.token + h*stride.head + c
+ *    (strides in ELEMENTS, channel stride 1).  [B,L,H,D] and [B,H,L,D] both fit.
+ *    Every row start must be 16-byte aligned, else DIT_ERR_ALIGNMENT.
+ *  - `workspace` is caller-owned device scratch of at least *_workspace_bytes(params)
+ *    bytes, 256-byte aligned.  Its contents are overwritten by each call; two calls that
+ *    share one workspace must be ordered on one stream.
+ *  - Arguments are validated before anything is launched; a call that returns an error
+ *    has had no effect.  No exception crosses the ABI.
+ *  - Arithmetic: inputs bf16 (or fp32), q and k rotated and scaled in fp32, then rounded
+ *    once (nearest-even) to the 16-bit MFMA operand type chosen by `flags`; scores,
+ *    softmax statistics and the output accumulator are fp32; output bf16 or fp32.
+ */
+#ifndef DIT_ATTN_H
+#define DIT_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DIT_OK = 0,
+    DIT_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, bad RoPE split, bad enum */
+    DIT_ERR_UNSUPPORTED = -2, /* head_dim other than 64/128, or a flag combination not built */
+    DIT_ERR_ALIGNMENT = -3,   /* a base pointer or stride breaks 16-byte row alignment */
+    DIT_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or too small */
+    DIT_ERR_HIP = -5          /* a HIP runtime call failed; see dit_last_hip_error() */
+} dit_status;
+
+typedef enum { DIT_BF16 = 0, DIT_F32 = 1 } dit_dtype;
+
+/*
+ * flags: precision of the 16-bit MFMA operands and the K/V staging strategy.
+ * 0 selects the defaults: fp16 operands for both products, K/V pre-packed.
+ *
+ * fp16 operands (11 significant bits) keep max|err| near 2e-3 x output RMS against the
+ * fp64 definition at 32,760 tokens; bf16 operands (8 bits) give about 2e-2.  Both run at
+ * the same MFMA rate.  fp16 requires |scale*log2(e)*q'|, |k'| and |v| < 65504.
+ */
+enum {
+    DIT_FLAG_QK_BF16 = 1u << 0, /* round q', k' to bf16 */
+    DIT_FLAG_QK_F16 = 1u << 1,  /* round q', k' to fp16 (default) */
+    DIT_FLAG_PV_BF16 = 1u << 2, /* round P to bf16, V stays bf16 */
+    DIT_FLAG_PV_F16 = 1u << 3,  /* round P to fp16, V widened bf16 -> fp16 (default) */
+    /* K/V staging for dit_attn_forward:
+     *  PREPACK (default): one memory-bound pass rotates K and lays K', V^T out in workspace
+     *  as ready-to-copy LDS tile images; the attention kernel then only copies tiles.
+     *  FUSED: no K/V workspace; each K tile is rotated while it is staged into LDS and
+     *  each V tile is transposed in registers.  Requires bf16 inputs and PV_BF16. */
+    DIT_FLAG_KV_PREPACK = 1u << 4,
+    DIT_FLAG_KV_FUSED = 1u << 5,
+    /* 256 query rows per workgroup (64 per wavefront, one workgroup per CU) instead of
+     * 128 (32 per wavefront, two workgroups per CU). */
+    DIT_FLAG_WIDE_QTILE = 1u << 6
+};
+
+typedef struct {
+    int64_t batch, token, head; /* element strides; the channel stride is 1 */
+} dit_strides;
+
+/*
+ * Self-attention over the L = T*Hg*Wg tokens of a latent grid, no mask.
+ * Token n (row-major, w fastest) sits at integer position
+ *     (t, h, w) = (t0 + n / (Hg*Wg), h0 + (n / Wg) % Hg, w0 + n % Wg).
+ * 3-axis rotary embedding on q and k: the D channels are three contiguous sections
+ * (t, h, w) of sizes d_t, d_h, d_w (each even, 0 allowed, sum D).  In section a at
+ * channel offset o_a, pair i is channels (o_a+2i, o_a+2i+1); with
+ * phi = pos_a * rope_base^(-2i/d_a):
+ *     x'[2i] = x[2i] cos(phi) - x[2i+1] sin(phi),  x'[2i+1] = x[2i] sin(phi) + x[2i+1] cos(phi).
+ * out[n] = sum_m softmax_m(scale * <q'_n, k'_m>) v_m over all L keys.
+ */
+typedef struct {
+    int32_t B, H, D;       /* batch, heads, head_dim (64 or 128) */
+    int32_t T, Hg, Wg;     /* latent grid */
+    int32_t t0, h0, w0;    /* position origin */
+    int32_t d_t, d_h, d_w; /* RoPE split */
+    float rope_base;       /* e.g. 10000 */
+    float scale;           /* <= 0 selects 1/sqrt(D) */
+    int32_t in_dtype;      /* dit_dtype of q, k, v */
+    int32_t out_dtype;     /* dit_dtype of out */
+    uint32_t flags;        /* DIT_FLAG_* */
+    dit_strides sq, sk, sv, so;
+} dit_self_attn_params;
+
+/* Bytes of workspace dit_attn_forward needs for these params (0 on invalid params). */
+size_t dit_attn_workspace_bytes(const dit_self_attn_params *p);
+
+/*
+ * q, k, v: [B, L, H, D] by strides, in_dtype.  out: same logical shape, out_dtype.
+ * lse (nullable): fp32 [B, H, L] dense, natural-log sum of exp(scale * score) per row.
+ */
+dit_status dit_attn_forward(const void *q, const void *k, const void *v, void *out, float *lse,
+                            const dit_self_attn_params *p, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
+ * Cross-attention of Lq query tokens over Lk conditioning tokens (text then image
+ * embeddings, concatenated by the caller), no positional rotation, ONE joint softmax over
+ * the Lk keys.  kv_valid (nullable): uint8 [B, Lk] dense, 1 = key attends, 0 = padding.
+ * A request with no valid key yields out = 0 and lse = -inf.
+ * Flags: QK_* and PV_* and WIDE_QTILE apply; K/V are always pre-packed.
+ */
+typedef struct {
+    int32_t B, H, D;
+    int32_t Lq, Lk;
+    float scale;      /* <= 0 selects 1/sqrt(D) */
+    int32_t in_dtype; /* dit_dtype of q, k, v */
+    int32_t out_dtype;
+    uint32_t flags;
+    dit_strides sq, sk, sv, so;
+} dit_cross_attn_params;
+
+size_t dit_cross_attn_workspace_bytes(const dit_cross_attn_params *p);
+
+dit_status dit_cross_attn_forward(const void *q, const void *k, const void *v,
+                                  const uint8_t *kv_valid, void *out, float *lse,
+                                  const dit_cross_attn_params *p, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
+ * Timing hook for benchmarks and profilers (not part of the attention definition): while
+ * both handles are non-NULL, every forward call made by the calling thread records the
+ * hipEvent_t `before` on the stream just before the attention kernel and `after` just after
+ * it, so the dominant kernel can be timed apart from the table and pre-pack kernels.
+ * The events are the caller's; pass NULL, NULL to switch the hook off.
+ */
+void dit_attn_set_timing_events(void *before, void *after);
+
+/* Static strings; never NULL. */
+const char *dit_strerror(dit_status s);
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *dit_last_hip_error(void);
+/* major*10000 + minor*100 + patch */
+int dit_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIT_ATTN_H */

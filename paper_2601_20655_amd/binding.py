@@ -1,0 +1,237 @@
+"""ctypes binding of include/dit_attn.h: argument marshalling only.
+
+Every function here has the name of the C entry point it calls.  torch is used for device
+memory (tensors, workspace) and for the current HIP stream; all arithmetic happens in the
+library's kernels.  If libdit_attn.so has not been built, loading fails with an error --
+there is no fallback path.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdit_attn.so")
+
+DIT_OK = 0
+DIT_ERR_INVALID_ARG = -1
+DIT_ERR_UNSUPPORTED = -2
+DIT_ERR_ALIGNMENT = -3
+DIT_ERR_WORKSPACE = -4
+DIT_ERR_HIP = -5
+
+DIT_BF16 = 0
+DIT_F32 = 1
+
+DIT_FLAG_QK_BF16 = 1 << 0
+DIT_FLAG_QK_F16 = 1 << 1
+DIT_FLAG_PV_BF16 = 1 << 2
+DIT_FLAG_PV_F16 = 1 << 3
+DIT_FLAG_KV_PREPACK = 1 << 4
+DIT_FLAG_KV_FUSED = 1 << 5
+DIT_FLAG_WIDE_QTILE = 1 << 6
+
+EXPORTS = (
+    "dit_attn_workspace_bytes",
+    "dit_attn_forward",
+    "dit_cross_attn_workspace_bytes",
+    "dit_cross_attn_forward",
+    "dit_attn_set_timing_events",
+    "dit_strerror",
+    "dit_last_hip_error",
+    "dit_attn_version",
+)
+
+
+class dit_strides(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int64), ("token", ctypes.c_int64), ("head", ctypes.c_int64)]
+
+
+class dit_self_attn_params(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("T", ctypes.c_int32), ("Hg", ctypes.c_int32), ("Wg", ctypes.c_int32),
+        ("t0", ctypes.c_int32), ("h0", ctypes.c_int32), ("w0", ctypes.c_int32),
+        ("d_t", ctypes.c_int32), ("d_h", ctypes.c_int32), ("d_w", ctypes.c_int32),
+        ("rope_base", ctypes.c_float), ("scale", ctypes.c_float),
+        ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
+        ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
+    ]
+
+
+class dit_cross_attn_params(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("Lq", ctypes.c_int32), ("Lk", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
+        ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
+    ]
+
+
+class DitError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        super().__init__("%s failed: %s (status %d)%s" % (
+            what, dit_strerror(status), status,
+            (" -- " + dit_last_hip_error()) if status == DIT_ERR_HIP else ""))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libdit_attn.so is not built (run `python -m paper_2601_20655_amd.build`); "
+                "there is no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        L.dit_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.dit_attn_workspace_bytes.argtypes = [ctypes.POINTER(dit_self_attn_params)]
+        L.dit_cross_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.dit_cross_attn_workspace_bytes.argtypes = [ctypes.POINTER(dit_cross_attn_params)]
+        L.dit_attn_forward.restype = ctypes.c_int
+        L.dit_attn_forward.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(dit_self_attn_params), vp,
+                                       ctypes.c_size_t, vp]
+        L.dit_cross_attn_forward.restype = ctypes.c_int
+        L.dit_cross_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(dit_cross_attn_params),
+                                             vp, ctypes.c_size_t, vp]
+        L.dit_attn_set_timing_events.restype = None
+        L.dit_attn_set_timing_events.argtypes = [vp, vp]
+        L.dit_strerror.restype = ctypes.c_char_p
+        L.dit_strerror.argtypes = [ctypes.c_int]
+        L.dit_last_hip_error.restype = ctypes.c_char_p
+        L.dit_attn_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def dit_strerror(status):
+    return lib().dit_strerror(int(status)).decode()
+
+
+def dit_last_hip_error():
+    return lib().dit_last_hip_error().decode()
+
+
+def dit_attn_set_timing_events(before, after):
+    """before/after: raw hipEvent_t handles (ints) or None to switch the hook off."""
+    lib().dit_attn_set_timing_events(before, after)
+
+
+def dit_attn_version():
+    return int(lib().dit_attn_version())
+
+
+def _dtype_code(t):
+    import torch
+
+    if t.dtype == torch.bfloat16:
+        return DIT_BF16
+    if t.dtype == torch.float32:
+        return DIT_F32
+    raise TypeError("tensors must be bfloat16 or float32, got %s" % t.dtype)
+
+
+def _strides(t):
+    """[B, L, H, D] tensor (any permutation underneath) -> dit_strides; channel stride must be 1."""
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("expected a [B, L, H, D] tensor with contiguous channels")
+    return dit_strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def _stream_ptr(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def self_attn_params(q, k, v, out, grid, split, origin=(0, 0, 0), rope_base=10000.0, scale=0.0, flags=0):
+    B, L, H, D = q.shape
+    return dit_self_attn_params(
+        B, H, D, grid[0], grid[1], grid[2], origin[0], origin[1], origin[2], split[0], split[1], split[2],
+        rope_base, scale, _dtype_code(q), _dtype_code(out), flags,
+        _strides(q), _strides(k), _strides(v), _strides(out))
+
+
+def cross_attn_params(q, k, v, out, scale=0.0, flags=0):
+    B, Lq, H, D = q.shape
+    return dit_cross_attn_params(B, H, D, Lq, k.shape[1], scale, _dtype_code(q), _dtype_code(out), flags,
+                                 _strides(q), _strides(k), _strides(v), _strides(out))
+
+
+def dit_attn_workspace_bytes(params):
+    return int(lib().dit_attn_workspace_bytes(ctypes.byref(params)))
+
+
+def dit_cross_attn_workspace_bytes(params):
+    return int(lib().dit_cross_attn_workspace_bytes(ctypes.byref(params)))
+
+
+def _workspace(nbytes, device):
+    import torch
+
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0), rope_base=10000.0,
+                     scale=0.0, flags=0, out_dtype=None, workspace=None, stream=None, want_lse=False):
+    """Self-attention with 3-axis RoPE on device tensors q, k, v of shape [B, L, H, D].
+
+    Allocates `out` (and `lse`, `workspace`) with torch when not given; returns out, or
+    (out, lse) when an lse buffer is requested.  Asynchronous on the stream.
+    """
+    import torch
+
+    if not q.is_cuda:
+        raise ValueError("dit_attn_forward needs device tensors")
+    B, L, H, D = q.shape
+    if out is None:
+        out = torch.empty((B, L, H, D), dtype=out_dtype or q.dtype, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, H, L), dtype=torch.float32, device=q.device)
+    p = self_attn_params(q, k, v, out, grid, split, origin, rope_base, scale, flags)
+    need = dit_attn_workspace_bytes(p)
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    st = lib().dit_attn_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                lse.data_ptr() if lse is not None else None, ctypes.byref(p),
+                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_attn_forward")
+    return (out, lse) if lse is not None else out
+
+
+def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0, flags=0, out_dtype=None,
+                           workspace=None, stream=None, want_lse=False):
+    """Cross-attention: q [B, Lq, H, D]; k, v [B, Lk, H, D]; kv_valid uint8 [B, Lk] or None."""
+    import torch
+
+    if not q.is_cuda:
+        raise ValueError("dit_cross_attn_forward needs device tensors")
+    B, Lq, H, D = q.shape
+    if out is None:
+        out = torch.empty((B, Lq, H, D), dtype=out_dtype or q.dtype, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, H, Lq), dtype=torch.float32, device=q.device)
+    if kv_valid is not None:
+        if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, k.shape[1]):
+            raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
+    p = cross_attn_params(q, k, v, out, scale, flags)
+    need = dit_cross_attn_workspace_bytes(p)
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    st = lib().dit_cross_attn_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                      kv_valid.data_ptr() if kv_valid is not None else None,
+                                      out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                      ctypes.byref(p), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_cross_attn_forward")
+    return (out, lse) if lse is not None else out

@@ -1,0 +1,307 @@
+// C ABI of the library: argument validation, workspace carving, kernel sequencing.
+// Every check happens before the first launch, so a failing call has no effect.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/dit_attn.h"
+#include "dit_attn_internal.h"
+
+namespace dit {
+hipError_t launch_attn_d128_qb1(const AttnArgs&, int, int, bool, hipStream_t);
+hipError_t launch_attn_d128_qb2(const AttnArgs&, int, int, bool, hipStream_t);
+hipError_t launch_attn_d64_qb1(const AttnArgs&, int, int, bool, hipStream_t);
+hipError_t launch_attn_d64_qb2(const AttnArgs&, int, int, bool, hipStream_t);
+
+hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, bool fused, hipStream_t s) {
+    if (D == 128 && qb == 1) return launch_attn_d128_qb1(a, qk_op, pv_op, fused, s);
+    if (D == 128 && qb == 2) return launch_attn_d128_qb2(a, qk_op, pv_op, fused, s);
+    if (D == 64 && qb == 1) return launch_attn_d64_qb1(a, qk_op, pv_op, fused, s);
+    if (D == 64 && qb == 2) return launch_attn_d64_qb2(a, qk_op, pv_op, fused, s);
+    return hipErrorInvalidValue;
+}
+}  // namespace dit
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+thread_local hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
+
+dit_status hip_fail(hipError_t e, const char* where) {
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", where, hipGetErrorString(e));
+    return DIT_ERR_HIP;
+}
+
+constexpr size_t kAlign = 256;
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Flags {
+    int qk_op, pv_op, qb;
+    bool fused;
+};
+
+// Resolve flag bits into operand types and staging mode.
+dit_status parse_flags(uint32_t f, Flags* out) {
+    const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
+                           DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE;
+    if (f & ~known) return DIT_ERR_INVALID_ARG;
+    if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
+    if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
+    if ((f & DIT_FLAG_KV_PREPACK) && (f & DIT_FLAG_KV_FUSED)) return DIT_ERR_INVALID_ARG;
+    out->qk_op = (f & DIT_FLAG_QK_BF16) ? dit::OP_BF16 : dit::OP_F16;
+    out->pv_op = (f & DIT_FLAG_PV_BF16) ? dit::OP_BF16 : dit::OP_F16;
+    out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
+    out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
+    return DIT_OK;
+}
+
+// Attention kernel launch, bracketed by the caller's timing events when the hook is set.
+dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused, hipStream_t s) {
+    const bool timed = g_ev_before && g_ev_after;
+    hipError_t e;
+    if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    e = dit::launch_attn(aa, D, fl.qb, fl.qk_op, fl.pv_op, fused, s);
+    if (e != hipSuccess) return hip_fail(e, "attn_fwd_kernel");
+    if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    return DIT_OK;
+}
+
+bool dtype_ok(int32_t d) { return d == DIT_BF16 || d == DIT_F32; }
+
+// Rows must start on 16-byte boundaries: base pointer and every stride.
+bool aligned16(const void* p, const dit_strides& s, int32_t dtype) {
+    const int64_t per16 = dtype == DIT_F32 ? 4 : 8;
+    if (reinterpret_cast<uintptr_t>(p) & 15u) return false;
+    return s.batch % per16 == 0 && s.token % per16 == 0 && s.head % per16 == 0;
+}
+
+bool strides_ok(const dit_strides& s, int32_t B, int32_t H, int32_t D) {
+    if (s.token < 1 || s.head < 1) return false;
+    if (B > 1 && s.batch < 1) return false;
+    if (H > 1 && s.head < D && s.token < D) return false;
+    return s.batch >= 0;
+}
+
+struct SelfPlan {
+    Flags fl;
+    int64_t L;
+    int nKT, nQT;
+    int table_entries;
+    size_t tab_off, tiles_off, total;
+};
+
+dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
+    if (!p) return DIT_ERR_INVALID_ARG;
+    if (p->B < 1 || p->H < 1 || p->D < 1 || p->T < 1 || p->Hg < 1 || p->Wg < 1) return DIT_ERR_INVALID_ARG;
+    if (p->D != 64 && p->D != 128) return DIT_ERR_UNSUPPORTED;
+    if (p->d_t < 0 || p->d_h < 0 || p->d_w < 0 || ((p->d_t | p->d_h | p->d_w) & 1) ||
+        p->d_t + p->d_h + p->d_w != p->D)
+        return DIT_ERR_INVALID_ARG;
+    if (!(p->rope_base > 0.f) || !isfinite(p->rope_base) || !isfinite(p->scale)) return DIT_ERR_INVALID_ARG;
+    if (!dtype_ok(p->in_dtype) || !dtype_ok(p->out_dtype)) return DIT_ERR_INVALID_ARG;
+    dit_status st = parse_flags(p->flags, &pl->fl);
+    if (st != DIT_OK) return st;
+    const int64_t L = (int64_t)p->T * p->Hg * p->Wg;
+    if (L > (1 << 24)) return DIT_ERR_UNSUPPORTED;  // token indices are 32-bit with room for tile padding
+    if ((int64_t)p->B * p->H > (1 << 20)) return DIT_ERR_UNSUPPORTED;
+    if (pl->fl.fused) {
+        // fused staging keeps V in bf16 and is built for head_dim 128 with bf16 inputs only
+        if (p->in_dtype != DIT_BF16 || p->D != 128 || pl->fl.pv_op != dit::OP_BF16 ||
+            !(p->flags & DIT_FLAG_PV_BF16))
+            return DIT_ERR_UNSUPPORTED;
+    }
+    if (!strides_ok(p->sq, p->B, p->H, p->D) || !strides_ok(p->sk, p->B, p->H, p->D) ||
+        !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
+        return DIT_ERR_INVALID_ARG;
+    pl->L = L;
+    pl->nKT = (int)((L + dit::kBK - 1) / dit::kBK);
+    const int bq = 128 * pl->fl.qb;
+    pl->nQT = (int)((L + bq - 1) / bq);
+    if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
+    pl->table_entries = p->T * (p->d_t / 2) + p->Hg * (p->d_h / 2) + p->Wg * (p->d_w / 2);
+    pl->tab_off = 0;
+    pl->tiles_off = round_up((size_t)pl->table_entries * sizeof(float2), kAlign);
+    size_t tiles = pl->fl.fused ? 0 : (size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D);
+    pl->total = pl->tiles_off + round_up(tiles, kAlign);
+    if (pl->total == 0) pl->total = kAlign;
+    return DIT_OK;
+}
+
+struct CrossPlan {
+    Flags fl;
+    int nKT, nQT;
+    size_t mask_off, tiles_off, total;
+};
+
+dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
+    if (!p) return DIT_ERR_INVALID_ARG;
+    if (p->B < 1 || p->H < 1 || p->D < 1 || p->Lq < 1 || p->Lk < 1) return DIT_ERR_INVALID_ARG;
+    if (p->D != 64 && p->D != 128) return DIT_ERR_UNSUPPORTED;
+    if (!isfinite(p->scale)) return DIT_ERR_INVALID_ARG;
+    if (!dtype_ok(p->in_dtype) || !dtype_ok(p->out_dtype)) return DIT_ERR_INVALID_ARG;
+    dit_status st = parse_flags(p->flags, &pl->fl);
+    if (st != DIT_OK) return st;
+    if (pl->fl.fused) return DIT_ERR_UNSUPPORTED;
+    if (p->Lq > (1 << 24) || p->Lk > (1 << 24) || (int64_t)p->B * p->H > (1 << 20)) return DIT_ERR_UNSUPPORTED;
+    if (!strides_ok(p->sq, p->B, p->H, p->D) || !strides_ok(p->sk, p->B, p->H, p->D) ||
+        !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
+        return DIT_ERR_INVALID_ARG;
+    pl->nKT = (p->Lk + dit::kBK - 1) / dit::kBK;
+    const int bq = 128 * pl->fl.qb;
+    pl->nQT = (p->Lq + bq - 1) / bq;
+    if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
+    pl->mask_off = 0;
+    pl->tiles_off = round_up((size_t)p->B * pl->nKT * sizeof(uint64_t), kAlign);
+    pl->total = pl->tiles_off + round_up((size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D), kAlign);
+    return DIT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dit_attn_workspace_bytes(const dit_self_attn_params* p) {
+    SelfPlan pl;
+    return plan_self(p, &pl) == DIT_OK ? pl.total : 0;
+}
+
+size_t dit_cross_attn_workspace_bytes(const dit_cross_attn_params* p) {
+    CrossPlan pl;
+    return plan_cross(p, &pl) == DIT_OK ? pl.total : 0;
+}
+
+dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* out, float* lse,
+                            const dit_self_attn_params* p, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    SelfPlan pl;
+    dit_status st = plan_self(p, &pl);
+    if (st != DIT_OK) return st;
+    if (!q || !k || !v || !out) return DIT_ERR_INVALID_ARG;
+    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(k, p->sk, p->in_dtype) ||
+        !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
+        return DIT_ERR_ALIGNMENT;
+    if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
+        return DIT_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+
+    dit::RopeGeom rg;
+    rg.hd[0] = p->d_t / 2; rg.hd[1] = p->d_h / 2; rg.hd[2] = p->d_w / 2;
+    rg.off[0] = 0; rg.off[1] = p->T * rg.hd[0]; rg.off[2] = rg.off[1] + p->Hg * rg.hd[1];
+    rg.Hg = p->Hg; rg.Wg = p->Wg;
+
+    dit::TableArgs ta;
+    ta.tab = reinterpret_cast<float2*>(ws + pl.tab_off);
+    ta.n[0] = p->T; ta.n[1] = p->Hg; ta.n[2] = p->Wg;
+    ta.origin[0] = p->t0; ta.origin[1] = p->h0; ta.origin[2] = p->w0;
+    ta.rg = rg;
+    ta.base = (double)p->rope_base;
+    ta.total = pl.table_entries;
+    hipError_t e = dit::launch_rope_table(ta, s);
+    if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+
+    const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
+
+    if (!pl.fl.fused) {
+        dit::PackArgs pa;
+        memset(&pa, 0, sizeof(pa));
+        pa.k = k; pa.v = v; pa.valid = nullptr;
+        pa.tiles = ws + pl.tiles_off;
+        pa.tile_mask = nullptr;
+        pa.tab = ta.tab;
+        pa.B = p->B; pa.H = p->H; pa.Lk = (int)pl.L; pa.nKT = pl.nKT;
+        pa.in_f32 = p->in_dtype == DIT_F32;
+        pa.sk_b = p->sk.batch; pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
+        pa.sv_b = p->sv.batch; pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
+        pa.rg = rg;
+        e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
+        if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
+    }
+
+    dit::AttnArgs aa;
+    memset(&aa, 0, sizeof(aa));
+    aa.q = q; aa.out = out; aa.lse = lse;
+    aa.tiles = pl.fl.fused ? nullptr : ws + pl.tiles_off;
+    aa.tile_mask = nullptr;
+    aa.tab = ta.tab;
+    aa.k = k; aa.v = v;
+    aa.sk_b = p->sk.batch; aa.sk_t = p->sk.token; aa.sk_h = p->sk.head;
+    aa.sv_b = p->sv.batch; aa.sv_t = p->sv.token; aa.sv_h = p->sv.head;
+    aa.B = p->B; aa.H = p->H; aa.Lq = (int)pl.L; aa.Lk = (int)pl.L; aa.nKT = pl.nKT; aa.nQT = pl.nQT;
+    aa.in_f32 = p->in_dtype == DIT_F32; aa.out_f32 = p->out_dtype == DIT_F32;
+    aa.sq_b = p->sq.batch; aa.sq_t = p->sq.token; aa.sq_h = p->sq.head;
+    aa.so_b = p->so.batch; aa.so_t = p->so.token; aa.so_h = p->so.head;
+    aa.rg = rg;
+    aa.qscale = scale * dit::kLog2e;
+    return run_attn(aa, p->D, pl.fl, pl.fl.fused, s);
+}
+
+dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, const uint8_t* kv_valid,
+                                  void* out, float* lse, const dit_cross_attn_params* p, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+    CrossPlan pl;
+    dit_status st = plan_cross(p, &pl);
+    if (st != DIT_OK) return st;
+    if (!q || !k || !v || !out) return DIT_ERR_INVALID_ARG;
+    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(k, p->sk, p->in_dtype) ||
+        !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
+        return DIT_ERR_ALIGNMENT;
+    if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
+        return DIT_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
+
+    dit::PackArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    pa.k = k; pa.v = v; pa.valid = kv_valid;
+    pa.tiles = ws + pl.tiles_off;
+    pa.tile_mask = reinterpret_cast<uint64_t*>(ws + pl.mask_off);
+    pa.tab = nullptr;
+    pa.B = p->B; pa.H = p->H; pa.Lk = p->Lk; pa.nKT = pl.nKT;
+    pa.in_f32 = p->in_dtype == DIT_F32;
+    pa.sk_b = p->sk.batch; pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
+    pa.sv_b = p->sv.batch; pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
+    hipError_t e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
+    if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
+
+    dit::AttnArgs aa;
+    memset(&aa, 0, sizeof(aa));
+    aa.q = q; aa.out = out; aa.lse = lse;
+    aa.tiles = pa.tiles;
+    aa.tile_mask = pa.tile_mask;
+    aa.tab = nullptr;
+    aa.B = p->B; aa.H = p->H; aa.Lq = p->Lq; aa.Lk = p->Lk; aa.nKT = pl.nKT; aa.nQT = pl.nQT;
+    aa.in_f32 = p->in_dtype == DIT_F32; aa.out_f32 = p->out_dtype == DIT_F32;
+    aa.sq_b = p->sq.batch; aa.sq_t = p->sq.token; aa.sq_h = p->sq.head;
+    aa.so_b = p->so.batch; aa.so_t = p->so.token; aa.so_h = p->so.head;
+    aa.qscale = scale * dit::kLog2e;
+    return run_attn(aa, p->D, pl.fl, false, s);
+}
+
+void dit_attn_set_timing_events(void* before, void* after) {
+    g_ev_before = static_cast<hipEvent_t>(before);
+    g_ev_after = static_cast<hipEvent_t>(after);
+}
+
+const char* dit_strerror(dit_status s) {
+    switch (s) {
+        case DIT_OK: return "ok";
+        case DIT_ERR_INVALID_ARG: return "invalid argument";
+        case DIT_ERR_UNSUPPORTED: return "unsupported shape or flag combination";
+        case DIT_ERR_ALIGNMENT: return "pointer or stride breaks 16-byte row alignment";
+        case DIT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case DIT_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* dit_last_hip_error(void) { return g_hip_error; }
+
+int dit_attn_version(void) { return 100; }
+
+}  // extern "C"

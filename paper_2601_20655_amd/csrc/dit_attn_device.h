@@ -1,0 +1,105 @@
+// Device helpers shared by the gfx950 kernels: 16-bit operand packing, MFMA wrappers,
+// input widening and the 3-axis rotary rotation of eight consecutive channels.
+#pragma once
+#include "dit_attn_internal.h"
+
+namespace dit {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 mk4(uint32_t x, uint32_t y, uint32_t z, uint32_t w) {
+    u32x4 r = {x, y, z, w};
+    return r;
+}
+
+// Two fp32 values -> one dword of two 16-bit operands, round to nearest even (low half = a).
+template <int OP>
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+    f32x2 f = {a, b};
+    if constexpr (OP == OP_F16) {
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+    } else {
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+    }
+}
+
+template <int OP>
+__device__ __forceinline__ u32x4 pack8(const float x[8]) {
+    return mk4(pack2<OP>(x[0], x[1]), pack2<OP>(x[2], x[3]), pack2<OP>(x[4], x[5]),
+                      pack2<OP>(x[6], x[7]));
+}
+
+// D(32x32, fp32) += A(32x16) * B(16x32).  Lane l supplies row (l % 32) of A and column
+// (l % 32) of B, eight contraction indices each (group l / 32); it receives column (l % 32)
+// of D, rows 8*(r/4) + 4*(l/32) + r%4 for r = 0..15.
+template <int OP>
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
+    if constexpr (OP == OP_F16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ void widen8(u32x4 u, float x[8]) {
+    x[0] = bf16_lo(u.x); x[1] = bf16_hi(u.x);
+    x[2] = bf16_lo(u.y); x[3] = bf16_hi(u.y);
+    x[4] = bf16_lo(u.z); x[5] = bf16_hi(u.z);
+    x[6] = bf16_lo(u.w); x[7] = bf16_hi(u.w);
+}
+
+// Eight consecutive channels starting at element offset `off` (a multiple of 8) as fp32.
+__device__ __forceinline__ void load8(const void* base, int64_t off, int in_f32, float x[8]) {
+    if (in_f32) {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(base) + off);
+        float4 lo = p[0], hi = p[1];
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
+        x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+    } else {
+        widen8(*reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + off), x);
+    }
+}
+
+// Token index -> position indices along (t, h, w), counted from the grid origin.
+__device__ __forceinline__ void token_pos(int n, const RopeGeom& rg, int& pt, int& ph, int& pw) {
+    const int hw = rg.Hg * rg.Wg;
+    pt = n / hw;
+    const int rem = n - pt * hw;
+    ph = rem / rg.Wg;
+    pw = rem - ph * rg.Wg;
+}
+
+// Rotate channels [8c, 8c+8) = pairs 4c..4c+3 of a token at position indices (pt, ph, pw).
+// A pair (x0, x1) becomes (x0 cos - x1 sin, x0 sin + x1 cos); all in fp32.
+__device__ __forceinline__ void rope8(float x[8], int c, const RopeGeom& rg, const float2* tab,
+                                      int pt, int ph, int pw) {
+#pragma unroll
+    for (int pp = 0; pp < 4; ++pp) {
+        const int ip = 4 * c + pp;
+        int idx;
+        if (ip < rg.hd[0]) {
+            idx = rg.off[0] + pt * rg.hd[0] + ip;
+        } else if (ip < rg.hd[0] + rg.hd[1]) {
+            idx = rg.off[1] + ph * rg.hd[1] + (ip - rg.hd[0]);
+        } else {
+            idx = rg.off[2] + pw * rg.hd[2] + (ip - rg.hd[0] - rg.hd[1]);
+        }
+        const float2 cs = tab[idx];
+        const float x0 = x[2 * pp], x1 = x[2 * pp + 1];
+        x[2 * pp] = x0 * cs.x - x1 * cs.y;
+        x[2 * pp + 1] = x0 * cs.y + x1 * cs.x;
+    }
+}
+
+}  // namespace dit

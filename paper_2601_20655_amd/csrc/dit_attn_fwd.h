@@ -1,0 +1,329 @@
+// Flash-style attention forward for gfx950: S^T = K' Q'^T and O^T = V^T P^T on 32x32x16 MFMA
+// with fp32 accumulation, online softmax in the base-2 domain, K/V tiles double-buffered in LDS.
+//
+// Work split: a workgroup of four wavefronts owns 4*QB*32 query rows of one (batch, head);
+// each wavefront owns QB blocks of 32 rows and walks all key tiles of 64 keys.
+//
+// Keys sit on the M axis of the score product, so a lane holds 16 scores of ONE query per
+// 32x32 block: the row maximum is an in-lane reduction plus one exchange with lane^32, and the
+// probabilities, rounded to 16 bit, are already laid out as the B operand of the PV product.
+// V^T is staged with its keys permuted to the same order (see kv_prepack / stage_v_fused).
+#pragma once
+#include "dit_attn_device.h"
+
+namespace dit {
+
+// The running maximum is only raised when a row's tile maximum exceeds it by more than this
+// (base-2 exponent): probabilities then stay below 2^8, exact in the final normalisation,
+// and the accumulator rescale is skipped on most tiles.
+constexpr float kRescaleThr = 8.0f;
+
+template <int D, int QB, int QK_OP, int PV_OP, bool FUSED>
+__global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(const AttnArgs a) {
+    using G = TileGeom<D>;
+    constexpr int NKS = D / 16;           // contraction steps of the score product
+    constexpr int NDB = D / 32;           // 32-channel blocks of the output
+    constexpr int BQ = 4 * QB * 32;       // query rows per workgroup
+    constexpr int CPR = D / 8;            // 16-byte chunks per K' row
+    constexpr int KROWS_PER_PASS = kThreads / CPR;
+    constexpr int NI_K = kBK / KROWS_PER_PASS;
+    constexpr int NI_V = D / 32;          // V^T: 8 chunks per row, 32 rows per pass
+    static_assert(!FUSED || (PV_OP == OP_BF16 && D == 128), "fused staging keeps V in bf16, D = 128");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that each XCD gets a
+    // contiguous range, i.e. the query tiles of the same head share one L2.
+    int logical;
+    {
+        const int nblk = gridDim.x, bid = blockIdx.x;
+        const int xcd = bid & 7, idx = bid >> 3;
+        const int chunk = nblk >> 3, rem = nblk & 7;
+        logical = xcd * chunk + (xcd < rem ? xcd : rem) + idx;
+    }
+    const int qt = logical % a.nQT;
+    const int bh = logical / a.nQT;
+    const int b = bh / a.H, h = bh - b * a.H;
+
+    // ---- Q prologue: load, rotate, fold scale*log2(e), round once, keep as B operands ----
+    u32x4 Qf[QB][NKS];
+    int qrow[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
+        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
+        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        int pt = 0, ph = 0, pw = 0;
+        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int c = 2 * ks + half;
+            float x[8];
+            load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
+            Qf[qb][ks] = pack8<QK_OP>(x);
+        }
+    }
+
+    // ---- staging of K/V tiles ----
+    const int kchunk_off = (tid / CPR) * G::KROW + (tid % CPR) * 16;
+    const int vchunk_off = G::K_BYTES + (tid >> 3) * G::VROW + (tid & 7) * 16;
+    const uint8_t* tiles = FUSED ? nullptr : a.tiles + (size_t)bh * a.nKT * G::TILE_BYTES;
+    u32x4 preK[NI_K];
+    u32x4 preV[NI_V];       // pre-packed path: V^T chunks
+    uint32_t preW[16];      // fused path: two units of 8 keys x 2 channels
+
+    // fused path: raw K rows (rotated when written to LDS) and raw V as 8 keys x 2 channels
+    const int64_t kbase = (int64_t)b * a.sk_b + (int64_t)h * a.sk_h;
+    const int64_t vbase = (int64_t)b * a.sv_b + (int64_t)h * a.sv_h;
+
+    auto issue_loads = [&](int j) {
+        if constexpr (!FUSED) {
+            const uint8_t* src = tiles + (size_t)j * G::TILE_BYTES;
+#pragma unroll
+            for (int i = 0; i < NI_K; ++i)
+                preK[i] = *reinterpret_cast<const u32x4*>(src + kchunk_off + i * KROWS_PER_PASS * G::KROW);
+#pragma unroll
+            for (int i = 0; i < NI_V; ++i)
+                preV[i] = *reinterpret_cast<const u32x4*>(src + vchunk_off + i * 32 * G::VROW);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NI_K; ++i) {
+                const int key = j * kBK + tid / CPR + i * KROWS_PER_PASS;
+                preK[i] = mk4(0, 0, 0, 0);
+                if (key < a.Lk)
+                    preK[i] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.k) + kbase +
+                                                             (int64_t)key * a.sk_t + 8 * (tid % CPR));
+            }
+            // unit u = wave + 4*i2 names the key set (kg = u / 2, hf = u % 2); lane = channel pair
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                const int u = wave + 4 * i2;
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const int key = j * kBK + 16 * (u >> 1) + 8 * (s >> 2) + 4 * (u & 1) + (s & 3);
+                    preW[i2 * 8 + s] = 0;
+                    if (key < a.Lk)
+                        preW[i2 * 8 + s] = *reinterpret_cast<const uint32_t*>(
+                            static_cast<const uint16_t*>(a.v) + vbase + (int64_t)key * a.sv_t + 2 * lane);
+                }
+            }
+        }
+    };
+
+    auto write_lds = [&](int j, int buf) {
+        uint8_t* dst = smem + buf * G::TILE_BYTES;
+        if constexpr (!FUSED) {
+#pragma unroll
+            for (int i = 0; i < NI_K; ++i)
+                *reinterpret_cast<u32x4*>(dst + kchunk_off + i * KROWS_PER_PASS * G::KROW) = preK[i];
+#pragma unroll
+            for (int i = 0; i < NI_V; ++i)
+                *reinterpret_cast<u32x4*>(dst + vchunk_off + i * 32 * G::VROW) = preV[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < NI_K; ++i) {
+                const int key = j * kBK + tid / CPR + i * KROWS_PER_PASS;
+                const int kc = key < a.Lk ? key : a.Lk - 1;
+                float x[8];
+                widen8(preK[i], x);
+                int pt, ph, pw;
+                token_pos(kc, a.rg, pt, ph, pw);
+                rope8(x, tid % CPR, a.rg, a.tab, pt, ph, pw);
+                *reinterpret_cast<u32x4*>(dst + kchunk_off + i * KROWS_PER_PASS * G::KROW) = pack8<QK_OP>(x);
+            }
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                const int u = wave + 4 * i2;
+                uint32_t w[8];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) w[s] = preW[i2 * 8 + s];
+                u32x4 lo, hi;  // channel 2*lane and 2*lane+1, eight keys each
+                lo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
+                lo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
+                lo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100u);
+                lo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100u);
+                hi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);
+                hi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
+                hi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302u);
+                hi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302u);
+                uint8_t* vd = dst + G::K_BYTES + u * 16;
+                *reinterpret_cast<u32x4*>(vd + (2 * lane) * G::VROW) = lo;
+                *reinterpret_cast<u32x4*>(vd + (2 * lane + 1) * G::VROW) = hi;
+            }
+        }
+    };
+
+    // ---- running state ----
+    f32x16 O[NDB][QB];
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[db][qb][r] = 0.f;
+    }
+
+    const int kread_off = l32 * G::KROW + half * 16;
+    const int vread_off = G::K_BYTES + l32 * G::VROW + half * 16;
+    const uint64_t* tmask = a.tile_mask ? a.tile_mask + (size_t)b * a.nKT : nullptr;
+    const int tail = a.Lk - (a.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
+
+    issue_loads(0);
+    write_lds(0, 0);
+    __syncthreads();
+
+    for (int j = 0; j < a.nKT; ++j) {
+        const int buf = j & 1;
+        if (j + 1 < a.nKT) issue_loads(j + 1);
+
+        uint64_t mask;
+        if (tmask) {
+            mask = tmask[j];
+        } else {
+            mask = (j == a.nKT - 1 && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
+        }
+
+        if (mask != 0ull) {
+            const uint8_t* kt = smem + buf * G::TILE_BYTES + kread_off;
+            const uint8_t* vt = smem + buf * G::TILE_BYTES + vread_off;
+
+            // S^T[key][query] for two 32-key blocks
+            f32x16 S[2][QB];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) S[kb][qb][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const u32x4 ka = *reinterpret_cast<const u32x4*>(kt + kb * 32 * G::KROW + ks * 32);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) S[kb][qb] = mfma32<QK_OP>(ka, Qf[qb][ks], S[kb][qb]);
+                }
+            }
+
+            if (mask != ~0ull) {
+                // register r of block kb is key 32*kb + 8*(r/4) + 4*half + r%4 of the tile
+                const uint64_t mlane = mask >> (4 * half);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const bool ok = (mlane >> (32 * kb + 8 * (r >> 2) + (r & 3))) & 1ull;
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb) S[kb][qb][r] = ok ? S[kb][qb][r] : -INFINITY;
+                    }
+            }
+
+            u32x4 P[4][QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float mx = S[0][qb][0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[0][qb][r]);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[1][qb][r]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const bool need = mx > m_run[qb] + kRescaleThr;
+                if (__any(need)) {
+                    const float alpha = need ? __builtin_amdgcn_exp2f(m_run[qb] - mx) : 1.0f;
+                    m_run[qb] = need ? mx : m_run[qb];
+                    l_run[qb] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) O[db][qb][r] *= alpha;
+                }
+                const float mr = m_run[qb];
+                float lsum = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float p = __builtin_amdgcn_exp2f(S[kb][qb][r] - mr);
+                        S[kb][qb][r] = p;
+                        lsum += p;
+                    }
+                }
+                l_run[qb] += lsum;
+#pragma unroll
+                for (int kg = 0; kg < 4; ++kg) {
+                    const int o = 8 * (kg & 1);
+                    const f32x16& s = S[kg >> 1][qb];
+                    P[kg][qb] = mk4(pack2<PV_OP>(s[o + 0], s[o + 1]), pack2<PV_OP>(s[o + 2], s[o + 3]),
+                                           pack2<PV_OP>(s[o + 4], s[o + 5]), pack2<PV_OP>(s[o + 6], s[o + 7]));
+                }
+            }
+
+            // O^T[channel][query] += V^T[channel][key] P^T[key][query]
+#pragma unroll
+            for (int kg = 0; kg < 4; ++kg) {
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) {
+                    const u32x4 va = *reinterpret_cast<const u32x4*>(vt + db * 32 * G::VROW + kg * 32);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) O[db][qb] = mfma32<PV_OP>(va, P[kg][qb], O[db][qb]);
+                }
+            }
+        }
+
+        if (j + 1 < a.nKT) write_lds(j + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: normalise and store; lane holds channels 32*db + 8*g + 4*half + e ----
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l = l_run[qb] + __shfl_xor(l_run[qb], 32);
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        if (qrow[qb] < a.Lq) {
+            const int64_t obase = (int64_t)b * a.so_b + (int64_t)qrow[qb] * a.so_t + (int64_t)h * a.so_h;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int d0 = 32 * db + 8 * g + 4 * half;
+                    const float o0 = O[db][qb][4 * g + 0] * inv, o1 = O[db][qb][4 * g + 1] * inv;
+                    const float o2 = O[db][qb][4 * g + 2] * inv, o3 = O[db][qb][4 * g + 3] * inv;
+                    if (a.out_f32) {
+                        *reinterpret_cast<float4*>(static_cast<float*>(a.out) + obase + d0) =
+                            make_float4(o0, o1, o2, o3);
+                    } else {
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + obase + d0) =
+                            make_uint2(pack2<OP_BF16>(o0, o1), pack2<OP_BF16>(o2, o3));
+                    }
+                }
+            if (a.lse && half == 0) {
+                const float v = l > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
+                a.lse[((int64_t)b * a.H + h) * a.Lq + qrow[qb]] = v;
+            }
+        }
+    }
+}
+
+template <int D, int QB, int QK_OP, int PV_OP, bool FUSED>
+hipError_t launch_attn_inst(const AttnArgs& a, hipStream_t s) {
+    auto kern = attn_fwd_kernel<D, QB, QK_OP, PV_OP, FUSED>;
+    constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)((int64_t)a.nQT * a.B * a.H));
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace dit

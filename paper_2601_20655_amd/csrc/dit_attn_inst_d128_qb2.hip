@@ -1,0 +1,20 @@
+// Instantiations of the attention kernel for head_dim 128, 2 query block(s) per wavefront.
+#include "dit_attn_fwd.h"
+
+namespace dit {
+
+hipError_t launch_attn_d128_qb2(const AttnArgs& a, int qk_op, int pv_op, bool fused, hipStream_t s) {
+    if (!fused) {
+        if (qk_op == OP_F16 && pv_op == OP_F16) return launch_attn_inst<128, 2, OP_F16, OP_F16, false>(a, s);
+        if (qk_op == OP_F16 && pv_op == OP_BF16) return launch_attn_inst<128, 2, OP_F16, OP_BF16, false>(a, s);
+        if (qk_op == OP_BF16 && pv_op == OP_F16) return launch_attn_inst<128, 2, OP_BF16, OP_F16, false>(a, s);
+        if (qk_op == OP_BF16 && pv_op == OP_BF16) return launch_attn_inst<128, 2, OP_BF16, OP_BF16, false>(a, s);
+    }
+    if (fused && pv_op == OP_BF16) {
+        if (qk_op == OP_F16) return launch_attn_inst<128, 2, OP_F16, OP_BF16, true>(a, s);
+        if (qk_op == OP_BF16) return launch_attn_inst<128, 2, OP_BF16, OP_BF16, true>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dit

@@ -1,0 +1,84 @@
+// Internal declarations shared by the host dispatch and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dit {
+
+constexpr int kBK = 64;         // keys per K/V tile
+constexpr int kThreads = 256;   // four wavefronts per workgroup
+constexpr float kLog2e = 1.4426950408889634f;
+
+enum OperandType { OP_BF16 = 0, OP_F16 = 1 };
+
+// One K/V tile as it sits in LDS (and, pre-packed, in workspace): 64 rows of K' followed by
+// D rows of V^T.  Rows carry 16 bytes of padding so that the 16-byte operand reads of 16
+// consecutive rows fall into distinct LDS banks and every address is lane_base + immediate.
+template <int D>
+struct TileGeom {
+    static constexpr int KROW = D * 2 + 16;      // bytes per K' row (one key, D channels)
+    static constexpr int VROW = kBK * 2 + 16;    // bytes per V^T row (one channel, 64 keys)
+    static constexpr int K_BYTES = kBK * KROW;
+    static constexpr int V_BYTES = D * VROW;
+    static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
+    static constexpr int K_CHUNKS = kBK * D / 8;  // 16-byte chunks that hold data
+    static constexpr int V_CHUNKS = D * kBK / 8;
+};
+
+inline size_t tile_bytes(int D) { return D == 128 ? TileGeom<128>::TILE_BYTES : TileGeom<64>::TILE_BYTES; }
+
+// Rotary tables: float2 (cos, sin) per (axis, position index, pair).  Entry of axis a is
+// tab[off[a] + p * hd[a] + i], position index p counted from the grid origin.
+struct RopeGeom {
+    int hd[3];   // pairs per axis (d_a / 2)
+    int off[3];  // first table entry of each axis
+    int Hg, Wg;  // latent grid height and width (token -> (t,h,w) decode)
+};
+
+struct TableArgs {
+    float2* tab;
+    int n[3];       // positions per axis (T, Hg, Wg)
+    int origin[3];  // t0, h0, w0
+    RopeGeom rg;
+    double base;
+    int total;
+};
+
+struct PackArgs {
+    const void* k;
+    const void* v;
+    const uint8_t* valid;  // nullable [B, Lk]
+    uint8_t* tiles;        // [B*H, nKT, TILE_BYTES]
+    uint64_t* tile_mask;   // nullable [B, nKT]
+    const float2* tab;     // nullable (no rotation)
+    int B, H, Lk, nKT;
+    int in_f32;
+    int64_t sk_b, sk_t, sk_h, sv_b, sv_t, sv_h;
+    RopeGeom rg;
+};
+
+struct AttnArgs {
+    const void* q;
+    void* out;
+    float* lse;                 // nullable
+    const uint8_t* tiles;       // pre-packed K'/V^T tiles
+    const uint64_t* tile_mask;  // nullable [B, nKT]; bit = key of the tile attends
+    const float2* tab;          // nullable: no rotation of q
+    // raw K/V for the fused staging path
+    const void* k;
+    const void* v;
+    int64_t sk_b, sk_t, sk_h, sv_b, sv_t, sv_h;
+    int B, H, Lq, Lk, nKT, nQT;
+    int in_f32, out_f32;
+    int64_t sq_b, sq_t, sq_h, so_b, so_t, so_h;
+    RopeGeom rg;
+    float qscale;  // softmax scale * log2(e), folded into q'
+};
+
+hipError_t launch_rope_table(const TableArgs& a, hipStream_t s);
+hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
+// qb = 32-row query blocks per wavefront (1 or 2)
+hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, bool fused,
+                       hipStream_t s);
+
+}  // namespace dit

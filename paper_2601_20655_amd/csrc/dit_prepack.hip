@@ -1,0 +1,117 @@
+// Memory-bound helper kernels that run before the attention kernel on the same stream:
+//  * rope_table_kernel: (cos, sin) of every (axis, position, pair) angle, evaluated in fp64
+//    and stored as fp32, so that the rotation itself never calls a transcendental.
+//  * kv_prepack_kernel: rotates K, rounds K' and V once to the 16-bit MFMA operand types and
+//    writes each 64-key tile as the exact byte image the attention kernel keeps in LDS
+//    (K' rows, then V^T rows with keys permuted into the order the PV product consumes).
+#include "dit_attn_device.h"
+
+namespace dit {
+
+__global__ void __launch_bounds__(256) rope_table_kernel(const TableArgs a) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= a.total) return;
+    int ax = 0;
+    if (idx >= a.rg.off[2]) ax = 2;
+    else if (idx >= a.rg.off[1]) ax = 1;
+    const int local = idx - a.rg.off[ax];
+    const int hd = a.rg.hd[ax];
+    const int p = local / hd, i = local - p * hd;
+    // angle = position * base^(-2i/d_a) with d_a = 2*hd
+    const double omega = pow(a.base, -(double)i / (double)hd);
+    const double phi = (double)(a.origin[ax] + p) * omega;
+    a.tab[idx] = make_float2((float)cos(phi), (float)sin(phi));
+}
+
+hipError_t launch_rope_table(const TableArgs& a, hipStream_t s) {
+    if (a.total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((a.total + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// One workgroup per (tile, head, batch).
+template <int D, int QK_OP, int PV_OP>
+__global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) {
+    using G = TileGeom<D>;
+    constexpr int CPR = D / 8;
+    constexpr int ROWS_PER_PASS = kThreads / CPR;
+    constexpr int NI = kBK / ROWS_PER_PASS;
+    constexpr int VS = D + 2;  // padded row of the transposition buffer, in 16-bit elements
+    __shared__ __attribute__((aligned(16))) uint16_t vs[kBK * VS];
+
+    const int tid = threadIdx.x;
+    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    uint8_t* dst = a.tiles + ((size_t)(b * a.H + h) * a.nKT + j) * G::TILE_BYTES;
+    const int c = tid % CPR;
+
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int r = tid / CPR + i * ROWS_PER_PASS;
+        const int key = j * kBK + r;
+        float xk[8], xv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xk[e] = xv[e] = 0.f;
+        if (key < a.Lk) {
+            load8(a.k, (int64_t)b * a.sk_b + (int64_t)key * a.sk_t + (int64_t)h * a.sk_h + 8 * c, a.in_f32, xk);
+            load8(a.v, (int64_t)b * a.sv_b + (int64_t)key * a.sv_t + (int64_t)h * a.sv_h + 8 * c, a.in_f32, xv);
+            if (a.tab) {
+                int pt, ph, pw;
+                token_pos(key, a.rg, pt, ph, pw);
+                rope8(xk, c, a.rg, a.tab, pt, ph, pw);
+            }
+        }
+        *reinterpret_cast<u32x4*>(dst + r * G::KROW + c * 16) = pack8<QK_OP>(xk);
+        const u32x4 pv = pack8<PV_OP>(xv);
+        uint32_t* row = reinterpret_cast<uint32_t*>(vs + r * VS + 8 * c);
+        row[0] = pv.x; row[1] = pv.y; row[2] = pv.z; row[3] = pv.w;
+    }
+    __syncthreads();
+
+    // V^T chunk (d, kc): slot 4g+e holds key 16*(kc/2) + 8g + 4*(kc%2) + e of the tile
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+        const int d = (tid >> 3) + 32 * i;
+        const int kc = tid & 7;
+        const int k0 = 16 * (kc >> 1) + 4 * (kc & 1);
+        uint32_t w[4];
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int e2 = 0; e2 < 2; ++e2) {
+                const int ka = k0 + 8 * g + 2 * e2;
+                w[2 * g + e2] = (uint32_t)vs[ka * VS + d] | ((uint32_t)vs[(ka + 1) * VS + d] << 16);
+            }
+        *reinterpret_cast<u32x4*>(dst + G::K_BYTES + d * G::VROW + kc * 16) = mk4(w[0], w[1], w[2], w[3]);
+    }
+
+    if (a.tile_mask && h == 0 && tid < 64) {
+        const int key = j * kBK + tid;
+        bool ok = key < a.Lk;
+        if (ok && a.valid) ok = a.valid[(size_t)b * a.Lk + key] != 0;
+        const uint64_t m = __ballot(ok);
+        if (tid == 0) a.tile_mask[(size_t)b * a.nKT + j] = m;
+    }
+}
+
+template <int D, int QK_OP, int PV_OP>
+static hipError_t launch_prepack_inst(const PackArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((kv_prepack_kernel<D, QK_OP, PV_OP>), dim3(a.nKT, a.H, a.B), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s) {
+#define DIT_PACK_CASE(DD, QK, PV) \
+    if (D == DD && qk_op == QK && pv_op == PV) return launch_prepack_inst<DD, QK, PV>(a, s);
+    DIT_PACK_CASE(128, OP_F16, OP_F16)
+    DIT_PACK_CASE(128, OP_F16, OP_BF16)
+    DIT_PACK_CASE(128, OP_BF16, OP_F16)
+    DIT_PACK_CASE(128, OP_BF16, OP_BF16)
+    DIT_PACK_CASE(64, OP_F16, OP_F16)
+    DIT_PACK_CASE(64, OP_F16, OP_BF16)
+    DIT_PACK_CASE(64, OP_BF16, OP_F16)
+    DIT_PACK_CASE(64, OP_BF16, OP_BF16)
+#undef DIT_PACK_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dit

@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+public header declares, sizes its workspace as documented and rejects bad arguments before any
+launch (so these calls never touch the HIP runtime)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_20655_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dit_attn.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dit_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_strerror():
+    assert B.dit_attn_version() >= 100
+    assert B.dit_strerror(B.DIT_OK) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert B.dit_strerror(code) not in ("", "ok", "unknown status")
+    assert B.dit_strerror(-99) == "unknown status"
+    assert B.dit_last_hip_error() == ""
+
+
+def self_params(B_=1, H=2, D=128, grid=(2, 3, 4), split=(44, 42, 42), flags=0, in_dtype=B.DIT_BF16,
+                out_dtype=B.DIT_BF16, base=10000.0):
+    L = grid[0] * grid[1] * grid[2]
+    s = B.dit_strides(L * H * D, H * D, D)
+    return B.dit_self_attn_params(B_, H, D, grid[0], grid[1], grid[2], 0, 0, 0, split[0], split[1], split[2],
+                                  base, 0.0, in_dtype, out_dtype, flags, s, s, s, s)
+
+
+def cross_params(B_=2, H=2, D=128, Lq=100, Lk=769, flags=0):
+    sq = B.dit_strides(Lq * H * D, H * D, D)
+    sk = B.dit_strides(Lk * H * D, H * D, D)
+    return B.dit_cross_attn_params(B_, H, D, Lq, Lk, 0.0, B.DIT_BF16, B.DIT_BF16, flags, sq, sk, sk, sq)
+
+
+def up(x, a=256):
+    return (x + a - 1) // a * a
+
+
+def test_workspace_size_formula():
+    # tile image: 64 K' rows of (2D+16) bytes + D V^T rows of 144 bytes
+    for D, split in ((128, (44, 42, 42)), (64, (22, 20, 22))):
+        tile = 64 * (2 * D + 16) + D * 144
+        for grid in ((2, 3, 4), (21, 30, 52), (1, 1, 65)):
+            L = grid[0] * grid[1] * grid[2]
+            p = self_params(B_=2, H=3, D=D, grid=grid, split=split)
+            tab = grid[0] * split[0] // 2 + grid[1] * split[1] // 2 + grid[2] * split[2] // 2
+            want = up(tab * 8) + up(2 * 3 * ((L + 63) // 64) * tile)
+            assert B.dit_attn_workspace_bytes(p) == want
+    p = self_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)
+    assert B.dit_attn_workspace_bytes(p) == up((2 * 22 + 3 * 21 + 4 * 21) * 8)
+    c = cross_params()
+    assert B.dit_cross_attn_workspace_bytes(c) == up(2 * 13 * 8) + up(2 * 2 * 13 * (64 * 272 + 128 * 144))
+
+
+FAKE = 0x1000  # a 16-byte aligned non-NULL address that is never dereferenced: validation fails first
+
+
+def call_self(p, q=FAKE, k=FAKE, v=FAKE, out=FAKE, ws=0x10000, ws_bytes=1 << 40):
+    return B.lib().dit_attn_forward(q, k, v, out, None, ctypes.byref(p), ws, ws_bytes, None)
+
+
+def call_cross(p, q=FAKE, k=FAKE, v=FAKE, out=FAKE, ws=0x10000, ws_bytes=1 << 40):
+    return B.lib().dit_cross_attn_forward(q, k, v, None, out, None, ctypes.byref(p), ws, ws_bytes, None)
+
+
+def test_self_attn_rejects_bad_arguments():
+    assert B.lib().dit_attn_forward(FAKE, FAKE, FAKE, FAKE, None, None, 0x10000, 1 << 30, None) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(split=(44, 42, 40))) == B.DIT_ERR_INVALID_ARG      # sum != D
+    assert call_self(self_params(split=(43, 43, 42))) == B.DIT_ERR_INVALID_ARG      # odd sections
+    assert call_self(self_params(split=(-2, 88, 42))) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(grid=(0, 3, 4))) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(base=0.0)) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(in_dtype=7)) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(D=96, split=(32, 32, 32))) == B.DIT_ERR_UNSUPPORTED
+    assert call_self(self_params(flags=B.DIT_FLAG_QK_BF16 | B.DIT_FLAG_QK_F16)) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(flags=B.DIT_FLAG_KV_PREPACK | B.DIT_FLAG_KV_FUSED)) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(flags=1 << 20)) == B.DIT_ERR_INVALID_ARG
+    # fused staging needs bf16 inputs, bf16 PV operands, head_dim 128
+    assert call_self(self_params(flags=B.DIT_FLAG_KV_FUSED)) == B.DIT_ERR_UNSUPPORTED
+    assert call_self(self_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16, in_dtype=B.DIT_F32)) == B.DIT_ERR_UNSUPPORTED
+    assert call_self(self_params(), q=0) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(), out=0) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(), k=FAKE + 2) == B.DIT_ERR_ALIGNMENT
+    p = self_params()
+    p.sv.token = 2 * 128 + 4                                                           # rows not 16-byte aligned
+    assert call_self(p) == B.DIT_ERR_ALIGNMENT
+    p = self_params()
+    p.sq.token = 0
+    assert call_self(p) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(), ws=0) == B.DIT_ERR_WORKSPACE
+    assert call_self(self_params(), ws=0x10010) == B.DIT_ERR_WORKSPACE                 # not 256-byte aligned
+    need = B.dit_attn_workspace_bytes(self_params())
+    assert call_self(self_params(), ws_bytes=need - 1) == B.DIT_ERR_WORKSPACE
+    assert B.dit_attn_workspace_bytes(self_params(split=(44, 42, 40))) == 0
+
+
+def test_cross_attn_rejects_bad_arguments():
+    assert call_cross(cross_params(Lk=0)) == B.DIT_ERR_INVALID_ARG
+    assert call_cross(cross_params(D=32)) == B.DIT_ERR_UNSUPPORTED
+    assert call_cross(cross_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)) == B.DIT_ERR_UNSUPPORTED
+    assert call_cross(cross_params(), v=0) == B.DIT_ERR_INVALID_ARG
+    assert call_cross(cross_params(), q=FAKE + 8) == B.DIT_ERR_ALIGNMENT
+    need = B.dit_cross_attn_workspace_bytes(cross_params())
+    assert call_cross(cross_params(), ws_bytes=need - 1) == B.DIT_ERR_WORKSPACE
+    assert B.dit_last_hip_error() == ""
+
+
+def test_python_wrappers_refuse_host_tensors():
+    import torch
+
+    q = torch.zeros((1, 24, 2, 128), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        B.dit_attn_forward(q, q, q, (2, 3, 4), (44, 42, 42))
+    with pytest.raises(ValueError):
+        B.dit_cross_attn_forward(q, q, q)
