@@ -165,7 +165,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
 
-        rows = wl.sample_rows(L, cfg["seed"], edge=64, n_random=128)
+        rows = wl.sample_rows(L, cfg["seed"], edge=64, n_random=1920)  # about 15 s of fp64 work on 16 cores
         t0 = time.perf_counter()
         ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], rows=rows)
         dt = time.perf_counter() - t0

@@ -29,6 +29,18 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     }
 }
 
+// acc + lo + hi of one packed operand pair, summed in fp32 (one v_dot2c against (1, 1)).
+template <int OP>
+__device__ __forceinline__ float sum2(uint32_t packed, float acc) {
+    if constexpr (OP == OP_F16) {
+        const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, packed), one, acc, false);
+    } else {
+        const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), one, acc, false);
+    }
+}
+
 template <int OP>
 __device__ __forceinline__ u32x4 pack8(const float x[8]) {
     return mk4(pack2<OP>(x[0], x[1]), pack2<OP>(x[2], x[3]), pack2<OP>(x[4], x[5]),

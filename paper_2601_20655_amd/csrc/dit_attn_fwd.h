@@ -248,24 +248,25 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
                         for (int r = 0; r < 16; ++r) O[db][qb][r] *= alpha;
                 }
                 const float mr = m_run[qb];
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) S[kb][qb][r] = __builtin_amdgcn_exp2f(S[kb][qb][r] - mr);
+                // The row sum is taken over the ROUNDED probabilities, the same numbers the PV
+                // product consumes, so numerator and denominator stay consistent.
                 float lsum = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float p = __builtin_amdgcn_exp2f(S[kb][qb][r] - mr);
-                        S[kb][qb][r] = p;
-                        lsum += p;
-                    }
-                }
-                l_run[qb] += lsum;
 #pragma unroll
                 for (int kg = 0; kg < 4; ++kg) {
                     const int o = 8 * (kg & 1);
                     const f32x16& s = S[kg >> 1][qb];
                     P[kg][qb] = mk4(pack2<PV_OP>(s[o + 0], s[o + 1]), pack2<PV_OP>(s[o + 2], s[o + 3]),
-                                           pack2<PV_OP>(s[o + 4], s[o + 5]), pack2<PV_OP>(s[o + 6], s[o + 7]));
+                                    pack2<PV_OP>(s[o + 4], s[o + 5]), pack2<PV_OP>(s[o + 6], s[o + 7]));
+                    lsum = sum2<PV_OP>(P[kg][qb].x, lsum);
+                    lsum = sum2<PV_OP>(P[kg][qb].y, lsum);
+                    lsum = sum2<PV_OP>(P[kg][qb].z, lsum);
+                    lsum = sum2<PV_OP>(P[kg][qb].w, lsum);
                 }
+                l_run[qb] += lsum;
             }
 
             // O^T[channel][query] += V^T[channel][key] P^T[key][query]

