@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--flags", type=int, default=0, help="DIT_FLAG_* bits for both calls (0 = library defaults)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy before the timed region, so that a "
+                         "counter run (FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all heads of one request on one MI355X, no "
@@ -101,6 +104,13 @@ def main():
         B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
                            stream=stream)
         B.dit_cross_attn_forward(out, ckd, cvd, cvalid_d, out=cout, flags=pc.flags, workspace=ws, stream=stream)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # one copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -67,7 +67,12 @@ enum {
     DIT_FLAG_KV_FUSED = 1u << 5,
     /* 256 query rows per workgroup (64 per wavefront, one workgroup per CU) instead of
      * 128 (32 per wavefront, two workgroups per CU). */
-    DIT_FLAG_WIDE_QTILE = 1u << 6
+    DIT_FLAG_WIDE_QTILE = 1u << 6,
+    /* Self-attention with pre-packed K/V normally runs a software-pipelined kernel (scores of
+     * tile j+1 on the matrix pipe while tile j's softmax runs on the vector ALU, tiles streamed
+     * global->LDS directly).  This flag selects the plain one-tile-at-a-time kernel instead
+     * (the one cross-attention and FUSED always use); same results up to rounding order. */
+    DIT_FLAG_SIMPLE_SCHEDULE = 1u << 7
 };
 
 typedef struct {

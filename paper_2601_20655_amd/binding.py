@@ -28,6 +28,7 @@ DIT_FLAG_PV_F16 = 1 << 3
 DIT_FLAG_KV_PREPACK = 1 << 4
 DIT_FLAG_KV_FUSED = 1 << 5
 DIT_FLAG_WIDE_QTILE = 1 << 6
+DIT_FLAG_SIMPLE_SCHEDULE = 1 << 7
 
 EXPORTS = (
     "dit_attn_workspace_bytes",

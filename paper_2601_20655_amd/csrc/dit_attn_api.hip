@@ -13,6 +13,20 @@ hipError_t launch_attn_d128_qb2(const AttnArgs&, int, int, bool, hipStream_t);
 hipError_t launch_attn_d64_qb1(const AttnArgs&, int, int, bool, hipStream_t);
 hipError_t launch_attn_d64_qb2(const AttnArgs&, int, int, bool, hipStream_t);
 
+hipError_t launch_attn_pipe_d128_qb1(const AttnArgs&, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d128_qb2(const AttnArgs&, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d64_qb1(const AttnArgs&, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d64_qb2(const AttnArgs&, int, int, hipStream_t);
+
+// Software-pipelined kernel: pre-packed tiles, no key mask beyond the ragged tail.
+hipError_t launch_attn_pipe(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, hipStream_t s) {
+    if (D == 128 && qb == 1) return launch_attn_pipe_d128_qb1(a, qk_op, pv_op, s);
+    if (D == 128 && qb == 2) return launch_attn_pipe_d128_qb2(a, qk_op, pv_op, s);
+    if (D == 64 && qb == 1) return launch_attn_pipe_d64_qb1(a, qk_op, pv_op, s);
+    if (D == 64 && qb == 2) return launch_attn_pipe_d64_qb2(a, qk_op, pv_op, s);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, bool fused, hipStream_t s) {
     if (D == 128 && qb == 1) return launch_attn_d128_qb1(a, qk_op, pv_op, fused, s);
     if (D == 128 && qb == 2) return launch_attn_d128_qb2(a, qk_op, pv_op, fused, s);
@@ -37,13 +51,14 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Flags {
     int qk_op, pv_op, qb;
-    bool fused;
+    bool fused, simple;
 };
 
 // Resolve flag bits into operand types and staging mode.
 dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
-                           DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE;
+                           DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
+                           DIT_FLAG_SIMPLE_SCHEDULE;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
@@ -52,6 +67,7 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     out->pv_op = (f & DIT_FLAG_PV_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
     out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
+    out->simple = (f & DIT_FLAG_SIMPLE_SCHEDULE) != 0;
     return DIT_OK;
 }
 
@@ -60,8 +76,12 @@ dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused,
     const bool timed = g_ev_before && g_ev_after;
     hipError_t e;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
-    e = dit::launch_attn(aa, D, fl.qb, fl.qk_op, fl.pv_op, fused, s);
-    if (e != hipSuccess) return hip_fail(e, "attn_fwd_kernel");
+    if (!fused && !fl.simple && !aa.tile_mask) {
+        e = dit::launch_attn_pipe(aa, D, fl.qb, fl.qk_op, fl.pv_op, s);
+    } else {
+        e = dit::launch_attn(aa, D, fl.qb, fl.qk_op, fl.pv_op, fused, s);
+    }
+    if (e != hipSuccess) return hip_fail(e, "attention kernel");
     if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     return DIT_OK;
 }

@@ -1,0 +1,383 @@
+// Software-pipelined attention forward for gfx950 (pre-packed K'/V^T tiles, no key mask other
+// than the ragged tail).  Same math and operand layouts as attn_fwd_kernel; what changes is
+// the schedule inside a wavefront, so that the matrix pipe and the vector ALU work at the same
+// time instead of taking turns:
+//
+//   iteration j, part A:  S(j+1)^T = K'(j+1) Q'^T  on MFMA   ||  P(j) = exp2(S(j) - m), row sums on VALU
+//   iteration j, part B:  O^T += V^T(j) P(j)^T     on MFMA   ||  row maxima of S(j+1), rescale test on VALU
+//
+// K/V tiles reach LDS by direct global->LDS loads (no staging registers): while iteration j runs,
+// K'(j+2) and V^T(j+1) stream into the buffers iteration j-1 has finished with.
+//
+// Scores are kept RELATIVE to the running maximum: the score MFMA chain starts from an
+// accumulator filled with -m instead of zero, so exp2 applies to the MFMA result directly and the
+// per-score subtraction disappears from the vector ALU.  When a row's maximum has to move (rare,
+// thresholded), the accumulator, the row sum and the pending score tile are shifted together.
+#pragma once
+#include "dit_attn_fwd.h"
+
+namespace dit {
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Lane l keeps max(x[l % 32], x[32 + l % 32]): one swap of the two 32-lane halves, no LDS trip.
+__device__ __forceinline__ float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// max(a, b, c) in one instruction (scores are never NaN, so no canonicalisation is needed)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+template <int D, int QB, int QK_OP, int PV_OP>
+__global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
+    using G = TileGeom<D>;
+    constexpr int NKS = D / 16;
+    constexpr int NDB = D / 32;
+    constexpr int BQ = 4 * QB * 32;
+    constexpr int NI = G::PART_KIB / 4;  // full rounds of wavefront-wide 1 KiB loads per tile part
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    // LDS map: K buffers 0/1, then V buffers 0/1
+    uint8_t* const kbuf = smem;
+    uint8_t* const vbuf = smem + 2 * G::K_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+
+    int logical;
+    {
+        const int nblk = gridDim.x, bid = blockIdx.x;
+        const int xcd = bid & 7, idx = bid >> 3;
+        const int chunk = nblk >> 3, rem = nblk & 7;
+        logical = xcd * chunk + (xcd < rem ? xcd : rem) + idx;
+    }
+    const int qt = logical % a.nQT;
+    const int bh = logical / a.nQT;
+    const int b = bh / a.H, h = bh - b * a.H;
+
+    // ---- Q prologue (identical to attn_fwd_kernel) ----
+    u32x4 Qf[QB][NKS];
+    int qrow[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
+        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
+        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        int pt = 0, ph = 0, pw = 0;
+        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int c = 2 * ks + half;
+            float x[8];
+            load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
+            Qf[qb][ks] = pack8<QK_OP>(x);
+        }
+    }
+
+    // ---- tile streaming.  A tile part is PART_KIB pieces of 1 KiB (64 lanes x 16 bytes).  Wavefront
+    // w moves pieces w, w+4, ... of both parts; the two odd pieces of the K part go to wavefronts
+    // 0 and 1, those of the V part to wavefronts 2 and 3: nine loads each at head_dim 128, no branch.
+    const uint8_t* const tiles = a.tiles + (size_t)bh * a.nKT * G::TILE_BYTES;  // wavefront-uniform
+    const uint32_t lane_off = lane * 16;
+    const int last = a.nKT - 1;
+    auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
+        tk = tk < last ? tk : last;  // past the end: re-fetch the last tile into a buffer nobody reads
+        tv = tv < last ? tv : last;
+        const uint8_t* ksrc = tiles + (size_t)tk * G::TILE_BYTES;
+        const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
+        uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
+        uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int c = (wave + 4 * i) * 1024;
+            __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
+        }
+        const int c = (4 * NI + (wave & 1)) * 1024;
+        const uint8_t* osrc = wave < 2 ? ksrc : vsrc;
+        uint8_t* odst = wave < 2 ? kdst : vdst;
+        __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
+    };
+    auto dma_wait_and_sync = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+
+    // ---- running state ----
+    f32x16 O[NDB][QB];
+    f32x16 negm[QB];  // every element = -m_run: the accumulator a score MFMA chain starts from
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = 0.f;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[db][qb][r] = 0.f;
+    }
+
+    const int kread_off = l32 * G::KROW + half * 16;
+    const int vread_off = l32 * G::VROW + half * 16;
+    const int tail = a.Lk - last * kBK;  // valid keys of the last tile (1..64)
+
+    // S^T of one tile: two 32-key blocks per query block
+    auto qk_tile = [&](f32x16 (&S)[2][QB], int buf) {
+        const uint8_t* kt = kbuf + buf * G::K_BYTES + kread_off;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) S[kb][qb][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const u32x4 ka = *reinterpret_cast<const u32x4*>(kt + kb * 32 * G::KROW + ks * 32);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) S[kb][qb] = mfma32<QK_OP>(ka, Qf[qb][ks], S[kb][qb]);
+            }
+        }
+    };
+
+    // keys >= Lk of the last tile leave the softmax
+    auto mask_tail = [&](f32x16 (&S)[2][QB]) {
+        const uint64_t mlane = ((1ull << tail) - 1ull) >> (4 * half);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const bool ok = (mlane >> (32 * kb + 8 * (r >> 2) + (r & 3))) & 1ull;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) S[kb][qb][r] = ok ? S[kb][qb][r] : -INFINITY;
+            }
+    };
+
+    // Row maxima of a score tile (relative to m_run once the loop runs); mx_new receives them.
+    float mx_new[QB];
+    auto row_max = [&](const f32x16 (&S)[2][QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float mx = S[0][qb][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[0][qb][r]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[1][qb][r]);
+            mx_new[qb] = max_across_halves(mx);
+        }
+    };
+    auto any_row_needs_shift = [&]() -> bool {
+        bool need = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) need |= mx_new[qb] > kRescaleThr;
+        return __any(need);
+    };
+    // Raise the running maximum of the rows whose pending tile S (relative scores) tops the
+    // threshold: m += shift, and everything expressed relative to m moves with it.
+    auto shift_rows = [&](f32x16 (&S)[2][QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float shift = mx_new[qb] > kRescaleThr ? mx_new[qb] : 0.f;
+            const float alpha = __builtin_amdgcn_exp2f(-shift);
+            m_run[qb] += shift;
+            l_run[qb] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                negm[qb][r] = -m_run[qb];
+                S[0][qb][r] -= shift;
+                S[1][qb][r] -= shift;
+            }
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) O[db][qb][r] *= alpha;
+        }
+    };
+
+    // One pipelined iteration: Sc holds the relative scores of tile j (all <= threshold), Sn
+    // receives those of tile j + 1.  Both parts are written as MFMA steps with a slice of vector
+    // work attached to each, and the compiler is told not to move anything across step
+    // boundaries, so the instruction stream alternates matrix and vector instructions.
+    constexpr int LA = 6;                    // LDS fragment reads issued this many fragments ahead
+    constexpr int NCH = 16 * QB;             // vector slices: two scores of one query block each
+    constexpr int NA = 2 * NKS * QB;         // MFMA steps of part A
+    constexpr int NB = 4 * NDB * QB;         // MFMA steps of part B
+    constexpr int CPA = NCH / NA, CPB = NCH / NB;
+    constexpr int PRE = 4;                   // exp slices issued before the first MFMA, covering LDS latency
+    static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
+    static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
+
+    auto iteration = [&](f32x16 (&Sc)[2][QB], f32x16 (&Sn)[2][QB], int j) {
+        const uint8_t* kt = kbuf + ((j + 1) & 1) * G::K_BYTES + kread_off;
+        const uint8_t* vt = vbuf + (j & 1) * G::V_BYTES + vread_off;
+        auto kfrag = [&](int f) { return *reinterpret_cast<const u32x4*>(kt + (f & 1) * 32 * G::KROW + (f >> 1) * 32); };
+        auto vfrag = [&](int g) { return *reinterpret_cast<const u32x4*>(vt + (g % NDB) * 32 * G::VROW + (g / NDB) * 32); };
+
+        // ---- part A: S(j+1) on MFMA, P(j) and row sums on VALU ----
+        u32x4 kf[2 * NKS], vf[4 * NDB];
+#pragma unroll
+        for (int f = 0; f < LA; ++f) kf[f] = kfrag(f);
+        dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
+
+        uint32_t Pd[QB][16];
+        float ls[QB][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) ls[qb][0] = ls[qb][1] = 0.f;
+        // slice c = (query block c / 16, dword i = c % 16): scores 2i, 2i+1 of that block
+        auto exp_slice = [&](int c) {
+            const int qv = c / 16, i = c % 16;
+            Sc[i / 8][qv][(2 * i) % 16] = __builtin_amdgcn_exp2f(Sc[i / 8][qv][(2 * i) % 16]);
+            Sc[i / 8][qv][(2 * i + 1) % 16] = __builtin_amdgcn_exp2f(Sc[i / 8][qv][(2 * i + 1) % 16]);
+        };
+        // the row sum runs over the ROUNDED probabilities, the numbers the PV product consumes
+        auto pack_slice = [&](int c) {
+            const int qv = c / 16, i = c % 16;
+            Pd[qv][i] = pack2<PV_OP>(Sc[i / 8][qv][(2 * i) % 16], Sc[i / 8][qv][(2 * i + 1) % 16]);
+            ls[qv][i & 1] = sum2<PV_OP>(Pd[qv][i], ls[qv][i & 1]);
+        };
+#pragma unroll
+        for (int c = 0; c < PRE; ++c) exp_slice(c);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            const int f = t / QB, qb = t % QB, ks = f >> 1, kb = f & 1;
+            if (qb == 0 && f + LA < 2 * NKS) kf[f + LA] = kfrag(f + LA);
+            // the last steps of part A fetch the first V^T fragments of part B
+            if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
+            Sn[kb][qb] = mfma32<QK_OP>(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb]);
+#pragma unroll
+            for (int cc = 0; cc < CPA; ++cc) {
+                const int c = t * CPA + cc;
+                if (c + PRE < NCH) exp_slice(c + PRE);
+                pack_slice(c);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            l_run[qb] += ls[qb][0] + ls[qb][1];
+            asm volatile("" : "+v"(l_run[qb]));  // keeps the row-sum chain in part A (it would sink past the barrier)
+        }
+
+        // ---- part B: O += V^T(j) P(j) on MFMA, row maxima of S(j+1) on VALU ----
+        float pm[QB][4];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pm[qb][e] = -INFINITY;
+        auto max_slice = [&](int c) {
+            const int qv = c / 16, i = c % 16;
+            pm[qv][i & 3] = max3(pm[qv][i & 3], Sn[i / 8][qv][(2 * i) % 16], Sn[i / 8][qv][(2 * i + 1) % 16]);
+        };
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int g = u / QB, qb = u % QB, kg = g / NDB, db = g % NDB;
+            if (qb == 0 && g + LA < 4 * NDB) vf[g + LA] = vfrag(g + LA);
+            const u32x4 pb = mk4(Pd[qb][4 * kg], Pd[qb][4 * kg + 1], Pd[qb][4 * kg + 2], Pd[qb][4 * kg + 3]);
+            O[db][qb] = mfma32<PV_OP>(vf[g], pb, O[db][qb]);
+            // the first two steps leave the last score MFMAs time to retire
+            if (u >= 2) {
+#pragma unroll
+                for (int cc = 0; cc < CPB; ++cc) max_slice((u - 2) * CPB + cc);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int c = (NB - 2) * CPB; c < NCH; ++c) max_slice(c);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            mx_new[qb] = max_across_halves(fmaxf(max3(pm[qb][0], pm[qb][1], pm[qb][2]), pm[qb][3]));
+        bool need = any_row_needs_shift();
+        dma_wait_and_sync();
+        // rare paths, outside the pipelined block
+        if (j + 1 == last && tail < kBK) {
+            mask_tail(Sn);
+            row_max(Sn);
+            need = any_row_needs_shift();
+        }
+        // after the last tile Sn holds scores of a stale buffer: never let them touch the state
+        if (need && j < last) shift_rows(Sn);
+    };
+
+    // ---- prologue: tiles 0 (K, V) and 1 (K); scores of tile 0 become the first running maximum ----
+    dma_tiles(0, 0, 0, 0);
+    dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
+    dma_wait_and_sync();
+    f32x16 S0[2][QB], S1[2][QB];
+    qk_tile(S0, 0);
+    __syncthreads();  // every wavefront has read K'(0) before iteration 0 streams K'(2) over it
+    if (last == 0 && tail < kBK) mask_tail(S0);
+    row_max(S0);  // finite: every tile holds at least one valid key
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = mx_new[qb];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            negm[qb][r] = -m_run[qb];
+            S0[0][qb][r] -= m_run[qb];
+            S0[1][qb][r] -= m_run[qb];
+        }
+    }
+
+    int j = 0;
+    for (; j + 1 < a.nKT; j += 2) {
+        iteration(S0, S1, j);
+        iteration(S1, S0, j + 1);
+    }
+    if (j < a.nKT) iteration(S0, S1, j);
+
+    // ---- epilogue ----
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l = l_run[qb] + __shfl_xor(l_run[qb], 32);
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        if (qrow[qb] < a.Lq) {
+            const int64_t obase = (int64_t)b * a.so_b + (int64_t)qrow[qb] * a.so_t + (int64_t)h * a.so_h;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int d0 = 32 * db + 8 * g + 4 * half;
+                    const float o0 = O[db][qb][4 * g + 0] * inv, o1 = O[db][qb][4 * g + 1] * inv;
+                    const float o2 = O[db][qb][4 * g + 2] * inv, o3 = O[db][qb][4 * g + 3] * inv;
+                    if (a.out_f32) {
+                        *reinterpret_cast<float4*>(static_cast<float*>(a.out) + obase + d0) =
+                            make_float4(o0, o1, o2, o3);
+                    } else {
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + obase + d0) =
+                            make_uint2(pack2<OP_BF16>(o0, o1), pack2<OP_BF16>(o2, o3));
+                    }
+                }
+            if (a.lse && half == 0) {
+                const float v = l > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
+                a.lse[((int64_t)b * a.H + h) * a.Lq + qrow[qb]] = v;
+            }
+        }
+    }
+}
+
+template <int D, int QB, int QK_OP, int PV_OP>
+hipError_t launch_attn_pipe_inst(const AttnArgs& a, hipStream_t s) {
+    auto kern = attn_fwd_pipe_kernel<D, QB, QK_OP, PV_OP>;
+    constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)((int64_t)a.nQT * a.B * a.H));
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace dit

@@ -1,5 +1,5 @@
 // Instantiations of the attention kernel for head_dim 128, 1 query block(s) per wavefront.
-#include "dit_attn_fwd.h"
+#include "dit_attn_fwd_pipe.h"
 
 namespace dit {
 
@@ -14,6 +14,14 @@ hipError_t launch_attn_d128_qb1(const AttnArgs& a, int qk_op, int pv_op, bool fu
         if (qk_op == OP_F16) return launch_attn_inst<128, 1, OP_F16, OP_BF16, true>(a, s);
         if (qk_op == OP_BF16) return launch_attn_inst<128, 1, OP_BF16, OP_BF16, true>(a, s);
     }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_pipe_d128_qb1(const AttnArgs& a, int qk_op, int pv_op, hipStream_t s) {
+    if (qk_op == OP_F16 && pv_op == OP_F16) return launch_attn_pipe_inst<128, 1, OP_F16, OP_F16>(a, s);
+    if (qk_op == OP_F16 && pv_op == OP_BF16) return launch_attn_pipe_inst<128, 1, OP_F16, OP_BF16>(a, s);
+    if (qk_op == OP_BF16 && pv_op == OP_F16) return launch_attn_pipe_inst<128, 1, OP_BF16, OP_F16>(a, s);
+    if (qk_op == OP_BF16 && pv_op == OP_BF16) return launch_attn_pipe_inst<128, 1, OP_BF16, OP_BF16>(a, s);
     return hipErrorInvalidValue;
 }
 

@@ -1,5 +1,5 @@
 // Instantiations of the attention kernel for head_dim 64, 2 query block(s) per wavefront.
-#include "dit_attn_fwd.h"
+#include "dit_attn_fwd_pipe.h"
 
 namespace dit {
 
@@ -10,6 +10,14 @@ hipError_t launch_attn_d64_qb2(const AttnArgs& a, int qk_op, int pv_op, bool fus
         if (qk_op == OP_BF16 && pv_op == OP_F16) return launch_attn_inst<64, 2, OP_BF16, OP_F16, false>(a, s);
         if (qk_op == OP_BF16 && pv_op == OP_BF16) return launch_attn_inst<64, 2, OP_BF16, OP_BF16, false>(a, s);
     }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_pipe_d64_qb2(const AttnArgs& a, int qk_op, int pv_op, hipStream_t s) {
+    if (qk_op == OP_F16 && pv_op == OP_F16) return launch_attn_pipe_inst<64, 2, OP_F16, OP_F16>(a, s);
+    if (qk_op == OP_F16 && pv_op == OP_BF16) return launch_attn_pipe_inst<64, 2, OP_F16, OP_BF16>(a, s);
+    if (qk_op == OP_BF16 && pv_op == OP_F16) return launch_attn_pipe_inst<64, 2, OP_BF16, OP_F16>(a, s);
+    if (qk_op == OP_BF16 && pv_op == OP_BF16) return launch_attn_pipe_inst<64, 2, OP_BF16, OP_BF16>(a, s);
     return hipErrorInvalidValue;
 }
 

@@ -14,15 +14,17 @@ enum OperandType { OP_BF16 = 0, OP_F16 = 1 };
 // One K/V tile as it sits in LDS (and, pre-packed, in workspace): 64 rows of K' followed by
 // D rows of V^T.  Rows carry 16 bytes of padding so that the 16-byte operand reads of 16
 // consecutive rows fall into distinct LDS banks and every address is lane_base + immediate.
+// Each part is padded to 4*n + 2 KiB so that four wavefronts can stream it with n
+// wavefront-wide 16-byte loads each plus one more load on two of them.
 template <int D>
 struct TileGeom {
     static constexpr int KROW = D * 2 + 16;      // bytes per K' row (one key, D channels)
     static constexpr int VROW = kBK * 2 + 16;    // bytes per V^T row (one channel, 64 keys)
-    static constexpr int K_BYTES = kBK * KROW;
-    static constexpr int V_BYTES = D * VROW;
+    static constexpr int PART_KIB = D == 128 ? 18 : 10;
+    static constexpr int K_BYTES = PART_KIB * 1024;  // >= 64 * KROW
+    static constexpr int V_BYTES = PART_KIB * 1024;  // >= D * VROW
     static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
-    static constexpr int K_CHUNKS = kBK * D / 8;  // 16-byte chunks that hold data
-    static constexpr int V_CHUNKS = D * kBK / 8;
+    static_assert(kBK * KROW <= K_BYTES && D * VROW <= V_BYTES && PART_KIB % 4 == 2, "tile part sizes");
 };
 
 inline size_t tile_bytes(int D) { return D == 128 ? TileGeom<128>::TILE_BYTES : TileGeom<64>::TILE_BYTES; }

@@ -55,9 +55,10 @@ def up(x, a=256):
 
 
 def test_workspace_size_formula():
-    # tile image: 64 K' rows of (2D+16) bytes + D V^T rows of 144 bytes
+    # tile image: 64 K' rows of (2D+16) bytes and D V^T rows of 144 bytes, each part padded to 18 / 10 KiB
     for D, split in ((128, (44, 42, 42)), (64, (22, 20, 22))):
-        tile = 64 * (2 * D + 16) + D * 144
+        tile = 2 * (18 if D == 128 else 10) * 1024
+        assert 64 * (2 * D + 16) <= tile // 2 and D * 144 <= tile // 2
         for grid in ((2, 3, 4), (21, 30, 52), (1, 1, 65)):
             L = grid[0] * grid[1] * grid[2]
             p = self_params(B_=2, H=3, D=D, grid=grid, split=split)
@@ -67,7 +68,7 @@ def test_workspace_size_formula():
     p = self_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)
     assert B.dit_attn_workspace_bytes(p) == up((2 * 22 + 3 * 21 + 4 * 21) * 8)
     c = cross_params()
-    assert B.dit_cross_attn_workspace_bytes(c) == up(2 * 13 * 8) + up(2 * 2 * 13 * (64 * 272 + 128 * 144))
+    assert B.dit_cross_attn_workspace_bytes(c) == up(2 * 13 * 8) + up(2 * 2 * 13 * 36 * 1024)
 
 
 FAKE = 0x1000  # a 16-byte aligned non-NULL address that is never dereferenced: validation fails first
