@@ -72,7 +72,10 @@ enum {
      * tile j+1 on the matrix pipe while tile j's softmax runs on the vector ALU, tiles streamed
      * global->LDS directly).  This flag selects the plain one-tile-at-a-time kernel instead
      * (the one cross-attention and FUSED always use); same results up to rounding order. */
-    DIT_FLAG_SIMPLE_SCHEDULE = 1u << 7
+    DIT_FLAG_SIMPLE_SCHEDULE = 1u << 7,
+    /* Pipelined self-attention kernel with 8 wavefronts per workgroup: twice the query rows
+     * share each K/V tile in LDS, halving the L2 -> LDS tile traffic. */
+    DIT_FLAG_BIG_WORKGROUP = 1u << 8
 };
 
 typedef struct {

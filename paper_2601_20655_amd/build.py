@@ -29,8 +29,10 @@ def _compile(src, extra):
     return obj, log
 
 
-def build_library(verbose=False, extra=(), jobs=None):
+def build_library(verbose=False, extra=(), jobs=None, out=LIB, obj_dir=OBJ):
     """Compile every .hip under csrc/ and link the shared library.  Always recompiles."""
+    global OBJ
+    OBJ = obj_dir
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     jobs = jobs or min(8, len(srcs))
@@ -39,9 +41,9 @@ def build_library(verbose=False, extra=(), jobs=None):
     for obj, log in results:
         if verbose and log.strip():
             print(log)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [o for o, _ in results]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + [o for o, _ in results]
     subprocess.check_call(cmd)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

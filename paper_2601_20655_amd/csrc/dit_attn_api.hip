@@ -13,17 +13,17 @@ hipError_t launch_attn_d128_qb2(const AttnArgs&, int, int, bool, hipStream_t);
 hipError_t launch_attn_d64_qb1(const AttnArgs&, int, int, bool, hipStream_t);
 hipError_t launch_attn_d64_qb2(const AttnArgs&, int, int, bool, hipStream_t);
 
-hipError_t launch_attn_pipe_d128_qb1(const AttnArgs&, int, int, hipStream_t);
-hipError_t launch_attn_pipe_d128_qb2(const AttnArgs&, int, int, hipStream_t);
-hipError_t launch_attn_pipe_d64_qb1(const AttnArgs&, int, int, hipStream_t);
-hipError_t launch_attn_pipe_d64_qb2(const AttnArgs&, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d128_qb1(const AttnArgs&, int, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d128_qb2(const AttnArgs&, int, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d64_qb1(const AttnArgs&, int, int, int, hipStream_t);
+hipError_t launch_attn_pipe_d64_qb2(const AttnArgs&, int, int, int, hipStream_t);
 
 // Software-pipelined kernel: pre-packed tiles, no key mask beyond the ragged tail.
-hipError_t launch_attn_pipe(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, hipStream_t s) {
-    if (D == 128 && qb == 1) return launch_attn_pipe_d128_qb1(a, qk_op, pv_op, s);
-    if (D == 128 && qb == 2) return launch_attn_pipe_d128_qb2(a, qk_op, pv_op, s);
-    if (D == 64 && qb == 1) return launch_attn_pipe_d64_qb1(a, qk_op, pv_op, s);
-    if (D == 64 && qb == 2) return launch_attn_pipe_d64_qb2(a, qk_op, pv_op, s);
+hipError_t launch_attn_pipe(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, int nw, hipStream_t s) {
+    if (D == 128 && qb == 1) return launch_attn_pipe_d128_qb1(a, qk_op, pv_op, nw, s);
+    if (D == 128 && qb == 2) return launch_attn_pipe_d128_qb2(a, qk_op, pv_op, nw, s);
+    if (D == 64 && qb == 1) return launch_attn_pipe_d64_qb1(a, qk_op, pv_op, nw, s);
+    if (D == 64 && qb == 2) return launch_attn_pipe_d64_qb2(a, qk_op, pv_op, nw, s);
     return hipErrorInvalidValue;
 }
 
@@ -50,7 +50,7 @@ constexpr size_t kAlign = 256;
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Flags {
-    int qk_op, pv_op, qb;
+    int qk_op, pv_op, qb, nw;
     bool fused, simple;
 };
 
@@ -58,7 +58,7 @@ struct Flags {
 dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
                            DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
-                           DIT_FLAG_SIMPLE_SCHEDULE;
+                           DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
@@ -68,6 +68,7 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
     out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
     out->simple = (f & DIT_FLAG_SIMPLE_SCHEDULE) != 0;
+    out->nw = (f & DIT_FLAG_BIG_WORKGROUP) ? 8 : 4;
     return DIT_OK;
 }
 
@@ -77,7 +78,7 @@ dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused,
     hipError_t e;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     if (!fused && !fl.simple && !aa.tile_mask) {
-        e = dit::launch_attn_pipe(aa, D, fl.qb, fl.qk_op, fl.pv_op, s);
+        e = dit::launch_attn_pipe(aa, D, fl.qb, fl.qk_op, fl.pv_op, fl.nw, s);
     } else {
         e = dit::launch_attn(aa, D, fl.qb, fl.qk_op, fl.pv_op, fused, s);
     }
@@ -135,7 +136,9 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
         return DIT_ERR_INVALID_ARG;
     pl->L = L;
     pl->nKT = (int)((L + dit::kBK - 1) / dit::kBK);
-    const int bq = 128 * pl->fl.qb;
+    if (pl->fl.fused || pl->fl.simple) pl->fl.nw = 4;  // only the pipelined kernel has the 8-wavefront form
+    if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;  // would need 512 registers x 512 lanes
+    const int bq = 32 * pl->fl.nw * pl->fl.qb;
     pl->nQT = (int)((L + bq - 1) / bq);
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
     pl->table_entries = p->T * (p->d_t / 2) + p->Hg * (p->d_h / 2) + p->Wg * (p->d_w / 2);
@@ -167,7 +170,8 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
         !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
         return DIT_ERR_INVALID_ARG;
     pl->nKT = (p->Lk + dit::kBK - 1) / dit::kBK;
-    const int bq = 128 * pl->fl.qb;
+    pl->fl.nw = 4;
+    const int bq = 32 * pl->fl.nw * pl->fl.qb;
     pl->nQT = (p->Lq + bq - 1) / bq;
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
     pl->mask_off = 0;

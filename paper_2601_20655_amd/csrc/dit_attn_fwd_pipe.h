@@ -16,6 +16,14 @@
 #pragma once
 #include "dit_attn_fwd.h"
 
+// Schedule constants of the pipelined kernel (overridable at build time for tuning sweeps).
+#ifndef DIT_PIPE_LA
+#define DIT_PIPE_LA 6   // LDS fragment reads are issued this many fragments ahead of their MFMA
+#endif
+#ifndef DIT_PIPE_PRE
+#define DIT_PIPE_PRE 4  // exp slices issued before the first MFMA of an iteration (covers LDS latency)
+#endif
+
 namespace dit {
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -34,13 +42,16 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     return r;
 }
 
-template <int D, int QB, int QK_OP, int PV_OP>
-__global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
+// NW = wavefronts per workgroup (4 or 8); the workgroup owns NW*QB*32 query rows that share every
+// K/V tile in LDS.
+template <int D, int QB, int QK_OP, int PV_OP, int NW>
+__global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
     using G = TileGeom<D>;
     constexpr int NKS = D / 16;
     constexpr int NDB = D / 32;
-    constexpr int BQ = 4 * QB * 32;
-    constexpr int NI = G::PART_KIB / 4;  // full rounds of wavefront-wide 1 KiB loads per tile part
+    constexpr int BQ = NW * QB * 32;
+    constexpr int NI = G::PART_KIB / NW;  // full rounds of wavefront-wide 1 KiB loads per tile part
+    static_assert(G::PART_KIB - NW * NI == 2, "two odd pieces per tile part");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     // LDS map: K buffers 0/1, then V buffers 0/1
@@ -86,8 +97,8 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_pipe_kerne
     }
 
     // ---- tile streaming.  A tile part is PART_KIB pieces of 1 KiB (64 lanes x 16 bytes).  Wavefront
-    // w moves pieces w, w+4, ... of both parts; the two odd pieces of the K part go to wavefronts
-    // 0 and 1, those of the V part to wavefronts 2 and 3: nine loads each at head_dim 128, no branch.
+    // w moves pieces w, w+NW, ... of both parts; the two odd pieces of the K part go to wavefronts
+    // 0 and 1, those of the V part to wavefronts 2 and 3.
     const uint8_t* const tiles = a.tiles + (size_t)bh * a.nKT * G::TILE_BYTES;  // wavefront-uniform
     const uint32_t lane_off = lane * 16;
     const int last = a.nKT - 1;
@@ -100,14 +111,16 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_pipe_kerne
         uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int c = (wave + 4 * i) * 1024;
+            const int c = (wave + NW * i) * 1024;
             __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
         }
-        const int c = (4 * NI + (wave & 1)) * 1024;
-        const uint8_t* osrc = wave < 2 ? ksrc : vsrc;
-        uint8_t* odst = wave < 2 ? kdst : vdst;
-        __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
+        if (NW == 4 || wave < 4) {
+            const int c = (NW * NI + (wave & 1)) * 1024;
+            const uint8_t* osrc = wave < 2 ? ksrc : vsrc;
+            uint8_t* odst = wave < 2 ? kdst : vdst;
+            __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
+        }
     };
     auto dma_wait_and_sync = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -210,12 +223,12 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_pipe_kerne
     // receives those of tile j + 1.  Both parts are written as MFMA steps with a slice of vector
     // work attached to each, and the compiler is told not to move anything across step
     // boundaries, so the instruction stream alternates matrix and vector instructions.
-    constexpr int LA = 6;                    // LDS fragment reads issued this many fragments ahead
+    constexpr int LA = DIT_PIPE_LA;          // LDS fragment reads issued this many fragments ahead
     constexpr int NCH = 16 * QB;             // vector slices: two scores of one query block each
     constexpr int NA = 2 * NKS * QB;         // MFMA steps of part A
     constexpr int NB = 4 * NDB * QB;         // MFMA steps of part B
     constexpr int CPA = NCH / NA, CPB = NCH / NB;
-    constexpr int PRE = 4;                   // exp slices issued before the first MFMA, covering LDS latency
+    constexpr int PRE = DIT_PIPE_PRE;        // exp slices issued before the first MFMA, covering LDS latency
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
 
@@ -368,15 +381,15 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_pipe_kerne
     }
 }
 
-template <int D, int QB, int QK_OP, int PV_OP>
+template <int D, int QB, int QK_OP, int PV_OP, int NW>
 hipError_t launch_attn_pipe_inst(const AttnArgs& a, hipStream_t s) {
-    auto kern = attn_fwd_pipe_kernel<D, QB, QK_OP, PV_OP>;
+    auto kern = attn_fwd_pipe_kernel<D, QB, QK_OP, PV_OP, NW>;
     constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((int64_t)a.nQT * a.B * a.H));
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, s, a);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), smem, s, a);
     return hipGetLastError();
 }
 

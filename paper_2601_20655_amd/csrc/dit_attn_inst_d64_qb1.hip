@@ -13,11 +13,15 @@ hipError_t launch_attn_d64_qb1(const AttnArgs& a, int qk_op, int pv_op, bool fus
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_attn_pipe_d64_qb1(const AttnArgs& a, int qk_op, int pv_op, hipStream_t s) {
-    if (qk_op == OP_F16 && pv_op == OP_F16) return launch_attn_pipe_inst<64, 1, OP_F16, OP_F16>(a, s);
-    if (qk_op == OP_F16 && pv_op == OP_BF16) return launch_attn_pipe_inst<64, 1, OP_F16, OP_BF16>(a, s);
-    if (qk_op == OP_BF16 && pv_op == OP_F16) return launch_attn_pipe_inst<64, 1, OP_BF16, OP_F16>(a, s);
-    if (qk_op == OP_BF16 && pv_op == OP_BF16) return launch_attn_pipe_inst<64, 1, OP_BF16, OP_BF16>(a, s);
+hipError_t launch_attn_pipe_d64_qb1(const AttnArgs& a, int qk_op, int pv_op, int nw, hipStream_t s) {
+#define DIT_PIPE_CASE(QK, PV)                                                                   \
+    if (qk_op == QK && pv_op == PV)                                                              \
+        return nw == 8 ? launch_attn_pipe_inst<64, 1, QK, PV, 8>(a, s) : launch_attn_pipe_inst<64, 1, QK, PV, 4>(a, s);
+    DIT_PIPE_CASE(OP_F16, OP_F16)
+    DIT_PIPE_CASE(OP_F16, OP_BF16)
+    DIT_PIPE_CASE(OP_BF16, OP_F16)
+    DIT_PIPE_CASE(OP_BF16, OP_BF16)
+#undef DIT_PIPE_CASE
     return hipErrorInvalidValue;
 }
 

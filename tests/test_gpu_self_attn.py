@@ -45,16 +45,27 @@ def test_tiny_config_fp32_inputs_all_rows():
     compare(to_f64(outb), refb, bf16_out=True, what="tiny bf16->bf16")
 
 
+SHAPES = {
+    "qb1_4w": 0,
+    "qb2_4w": B.DIT_FLAG_WIDE_QTILE,
+    "qb1_8w": B.DIT_FLAG_BIG_WORKGROUP,
+    "simple_qb1": B.DIT_FLAG_SIMPLE_SCHEDULE,
+    "simple_qb2": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
+}
+
+
 @pytest.mark.parametrize("name", sorted(VARIANTS))
-@pytest.mark.parametrize("wide", [False, True])
+@pytest.mark.parametrize("wide", sorted(SHAPES))
 def test_mid_config_all_rows(name, wide):
-    """6,240 tokens x 4 heads: 98 key tiles (ragged tail of 32), all rows compared."""
+    """6,240 tokens x 4 heads: 98 key tiles (ragged tail of 32), all rows compared, for every
+    operand-type variant and every kernel shape (query rows per wavefront, wavefronts per
+    workgroup, pipelined or plain schedule)."""
     import torch
 
     cfg = wl.CONFIGS["mid"]
     q, k, v = wl.self_attn_inputs(cfg)
     ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"])
-    flags = VARIANTS[name] | (B.DIT_FLAG_WIDE_QTILE if wide else 0)
+    flags = VARIANTS[name] | SHAPES[wide]
     out = run_self(cfg, q, k, v, flags=flags, out_dtype=torch.float32)
     compare(to_f64(out), ref, what="mid %s wide=%s f32 out" % (name, wide))
     out = run_self(cfg, q, k, v, flags=flags)
@@ -99,7 +110,7 @@ def test_ragged_sizes(grid, D):
     cfg = dict(B=2, grid=grid, H=3, D=D, split=split, dtype="bf16", seed=99 + D + grid[2])
     q, k, v = wl.self_attn_inputs(cfg)
     ref, ref_lse = oracle.self_attn(q, k, v, grid, split, want_lse=True)
-    for flags in (0, B.DIT_FLAG_WIDE_QTILE) + ((B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16,) if D == 128 else ()):
+    for flags in tuple(SHAPES.values()) + ((B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16,) if D == 128 else ()):
         out, lse = run_self(cfg, q, k, v, flags=flags, out_dtype=torch.float32, want_lse=True)
         compare(to_f64(out), ref, what="ragged %s D=%d flags=%d" % (grid, D, flags))
         assert np.max(np.abs(to_f64(lse) - ref_lse)) < 5e-3
@@ -115,7 +126,7 @@ def test_peaky_softmax_origin_scale_base():
     cfg = dict(B=1, grid=(3, 9, 17), H=2, D=128, split=(44, 42, 42), dtype="bf16", seed=4242)
     q, k, v = wl.self_attn_inputs(cfg, gain=2.0)
     ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], origin=(5, -3, 11), scale=0.11, base=500.0)
-    for flags in (0, B.DIT_FLAG_WIDE_QTILE, B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16):
+    for flags in tuple(SHAPES.values()) + (B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16,):
         out = run_self(cfg, q, k, v, flags=flags, out_dtype=torch.float32, origin=(5, -3, 11), scale=0.11, base=500.0)
         compare(to_f64(out), ref, what="peaky flags=%d" % flags)
 
