@@ -73,9 +73,12 @@ enum {
      * global->LDS directly).  This flag selects the plain one-tile-at-a-time kernel instead
      * (the one cross-attention and FUSED always use); same results up to rounding order. */
     DIT_FLAG_SIMPLE_SCHEDULE = 1u << 7,
-    /* Pipelined self-attention kernel with 8 wavefronts per workgroup: twice the query rows
-     * share each K/V tile in LDS, halving the L2 -> LDS tile traffic. */
-    DIT_FLAG_BIG_WORKGROUP = 1u << 8
+    /* Workgroup size of the pipelined self-attention kernel.  BIG: 8 wavefronts, 256 query rows
+     * share each K/V tile in LDS (half the L2 -> LDS tile traffic).  SMALL: 4 wavefronts, 128
+     * rows, two workgroups per CU.  Neither flag: BIG when that still gives every CU at least
+     * two workgroups, else SMALL. */
+    DIT_FLAG_BIG_WORKGROUP = 1u << 8,
+    DIT_FLAG_SMALL_WORKGROUP = 1u << 9
 };
 
 typedef struct {

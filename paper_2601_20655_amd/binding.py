@@ -30,6 +30,7 @@ DIT_FLAG_KV_FUSED = 1 << 5
 DIT_FLAG_WIDE_QTILE = 1 << 6
 DIT_FLAG_SIMPLE_SCHEDULE = 1 << 7
 DIT_FLAG_BIG_WORKGROUP = 1 << 8
+DIT_FLAG_SMALL_WORKGROUP = 1 << 9
 
 EXPORTS = (
     "dit_attn_workspace_bytes",

@@ -58,7 +58,7 @@ struct Flags {
 dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
                            DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
-                           DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP;
+                           DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP | DIT_FLAG_SMALL_WORKGROUP;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
@@ -68,7 +68,8 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
     out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
     out->simple = (f & DIT_FLAG_SIMPLE_SCHEDULE) != 0;
-    out->nw = (f & DIT_FLAG_BIG_WORKGROUP) ? 8 : 4;
+    if ((f & DIT_FLAG_BIG_WORKGROUP) && (f & DIT_FLAG_SMALL_WORKGROUP)) return DIT_ERR_INVALID_ARG;
+    out->nw = (f & DIT_FLAG_BIG_WORKGROUP) ? 8 : (f & DIT_FLAG_SMALL_WORKGROUP) ? 4 : 0;  // 0 = choose by size
     return DIT_OK;
 }
 
@@ -136,8 +137,13 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
         return DIT_ERR_INVALID_ARG;
     pl->L = L;
     pl->nKT = (int)((L + dit::kBK - 1) / dit::kBK);
-    if (pl->fl.fused || pl->fl.simple) pl->fl.nw = 4;  // only the pipelined kernel has the 8-wavefront form
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;  // would need 512 registers x 512 lanes
+    if (pl->fl.fused || pl->fl.simple || pl->fl.qb == 2) {
+        pl->fl.nw = 4;  // only the pipelined 32-rows-per-wavefront kernel has the 8-wavefront form
+    } else if (pl->fl.nw == 0) {
+        // 8 wavefronts when 256-row workgroups still cover the 256 CUs at least twice over
+        pl->fl.nw = ((L + 255) / 256) * p->B * p->H >= 512 ? 8 : 4;
+    }
     const int bq = 32 * pl->fl.nw * pl->fl.qb;
     pl->nQT = (int)((L + bq - 1) / bq);
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;

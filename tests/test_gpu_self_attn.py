@@ -46,7 +46,8 @@ def test_tiny_config_fp32_inputs_all_rows():
 
 
 SHAPES = {
-    "qb1_4w": 0,
+    "auto": 0,
+    "qb1_4w": B.DIT_FLAG_SMALL_WORKGROUP,
     "qb2_4w": B.DIT_FLAG_WIDE_QTILE,
     "qb1_8w": B.DIT_FLAG_BIG_WORKGROUP,
     "simple_qb1": B.DIT_FLAG_SIMPLE_SCHEDULE,
