@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
 
+# HBM bytes per launch of the self-attention kernel at the dit_14b shape, default flags, from the
+# FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
+# keyed by library version: a library whose kernel has changed since reports null.
+TRAFFIC_BYTES_BY_VERSION = {101: 3.69e9}
+
 
 class HipEvents:
     """Raw hipEvent_t pairs (ctypes on the HIP runtime) for the library's timing hook."""
@@ -168,7 +173,7 @@ def main():
             "peak": PEAK_TFLOPS_16BIT_DENSE,
             "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_TFLOPS_16BIT_DENSE, 4),
-            "traffic": None,
+            "traffic": TRAFFIC_BYTES_BY_VERSION.get(B.dit_attn_version()) if args.flags == 0 else None,
         },
     }
 
