@@ -125,7 +125,8 @@ dit_status dit_attn_forward(const void *q, const void *k, const void *v, void *o
  * embeddings, concatenated by the caller), no positional rotation, ONE joint softmax over
  * the Lk keys.  kv_valid (nullable): uint8 [B, Lk] dense, 1 = key attends, 0 = padding.
  * A request with no valid key yields out = 0 and lse = -inf.
- * Flags: QK_* and PV_* and WIDE_QTILE apply; K/V are always pre-packed.
+ * Flags: QK_*, PV_*, WIDE_QTILE, SIMPLE_SCHEDULE and the workgroup-size flags apply; K/V are always
+ * pre-packed; tiles without a valid key are neither loaded nor computed.
  */
 typedef struct {
     int32_t B, H, D;

@@ -78,7 +78,7 @@ dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused,
     const bool timed = g_ev_before && g_ev_after;
     hipError_t e;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
-    if (!fused && !fl.simple && !aa.tile_mask) {
+    if (!fused && !fl.simple) {
         e = dit::launch_attn_pipe(aa, D, fl.qb, fl.qk_op, fl.pv_op, fl.nw, s);
     } else {
         e = dit::launch_attn(aa, D, fl.qb, fl.qk_op, fl.pv_op, fused, s);
@@ -159,7 +159,7 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
 struct CrossPlan {
     Flags fl;
     int nKT, nQT;
-    size_t mask_off, tiles_off, total;
+    size_t mask_off, list_off, count_off, tiles_off, total;
 };
 
 dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
@@ -176,12 +176,22 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
         !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
         return DIT_ERR_INVALID_ARG;
     pl->nKT = (p->Lk + dit::kBK - 1) / dit::kBK;
-    pl->fl.nw = 4;
+    if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
+    if (pl->fl.simple || pl->fl.qb == 2) {
+        pl->fl.nw = 4;
+    } else if (pl->fl.nw == 0) {
+        // few key tiles per query tile: two small workgroups per CU overlap each other's
+        // prologue and epilogue better than one large workgroup saves on tile traffic (measured)
+        pl->fl.nw = 4;
+    }
     const int bq = 32 * pl->fl.nw * pl->fl.qb;
     pl->nQT = (p->Lq + bq - 1) / bq;
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
+    // workspace: per-tile key masks, compacted list of non-empty tiles, their count, tile images
     pl->mask_off = 0;
-    pl->tiles_off = round_up((size_t)p->B * pl->nKT * sizeof(uint64_t), kAlign);
+    pl->list_off = round_up((size_t)p->B * pl->nKT * sizeof(uint64_t), kAlign);
+    pl->count_off = pl->list_off + round_up((size_t)p->B * pl->nKT * sizeof(int), kAlign);
+    pl->tiles_off = pl->count_off + round_up((size_t)p->B * sizeof(int), kAlign);
     pl->total = pl->tiles_off + round_up((size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D), kAlign);
     return DIT_OK;
 }
@@ -291,6 +301,8 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.k = k; pa.v = v; pa.valid = kv_valid;
     pa.tiles = ws + pl.tiles_off;
     pa.tile_mask = reinterpret_cast<uint64_t*>(ws + pl.mask_off);
+    pa.tile_list = reinterpret_cast<int*>(ws + pl.list_off);
+    pa.tile_count = reinterpret_cast<int*>(ws + pl.count_off);
     pa.tab = nullptr;
     pa.B = p->B; pa.H = p->H; pa.Lk = p->Lk; pa.nKT = pl.nKT;
     pa.in_f32 = p->in_dtype == DIT_F32;
@@ -298,12 +310,16 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.sv_b = p->sv.batch; pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
     hipError_t e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
     if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
+    e = dit::launch_tile_compact(pa, s);
+    if (e != hipSuccess) return hip_fail(e, "tile_compact_kernel");
 
     dit::AttnArgs aa;
     memset(&aa, 0, sizeof(aa));
     aa.q = q; aa.out = out; aa.lse = lse;
     aa.tiles = pa.tiles;
     aa.tile_mask = pa.tile_mask;
+    aa.tile_list = pa.tile_list;
+    aa.tile_count = pa.tile_count;
     aa.tab = nullptr;
     aa.B = p->B; aa.H = p->H; aa.Lq = p->Lq; aa.Lk = p->Lk; aa.nKT = pl.nKT; aa.nQT = pl.nQT;
     aa.in_f32 = p->in_dtype == DIT_F32; aa.out_f32 = p->out_dtype == DIT_F32;
@@ -332,6 +348,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 101; }
+int dit_attn_version(void) { return 102; }
 
 }  // extern "C"

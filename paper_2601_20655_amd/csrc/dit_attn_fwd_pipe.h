@@ -1,5 +1,6 @@
-// Software-pipelined attention forward for gfx950 (pre-packed K'/V^T tiles, no key mask other
-// than the ragged tail).  Same math and operand layouts as attn_fwd_kernel; what changes is
+// Software-pipelined attention forward for gfx950 (pre-packed K'/V^T tiles; LISTED = false: every
+// tile attends and only the ragged tail is masked; LISTED = true: per-tile 64-bit key masks and a
+// compacted list of the non-empty tiles, the cross-attention form).  Same math and operand layouts as attn_fwd_kernel; what changes is
 // the schedule inside a wavefront, so that the matrix pipe and the vector ALU work at the same
 // time instead of taking turns:
 //
@@ -44,7 +45,7 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 
 // NW = wavefronts per workgroup (4 or 8); the workgroup owns NW*QB*32 query rows that share every
 // K/V tile in LDS.
-template <int D, int QB, int QK_OP, int PV_OP, int NW>
+template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
 __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
     using G = TileGeom<D>;
     constexpr int NKS = D / 16;
@@ -101,10 +102,25 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     // 0 and 1, those of the V part to wavefronts 2 and 3.
     const uint8_t* const tiles = a.tiles + (size_t)bh * a.nKT * G::TILE_BYTES;  // wavefront-uniform
     const uint32_t lane_off = lane * 16;
-    const int last = a.nKT - 1;
+    // The loop runs over "steps"; step j works on tile tile_of(j).  Without a list that is tile j.
+    const int* const tlist = LISTED ? a.tile_list + (size_t)b * a.nKT : nullptr;
+    const uint64_t* const tmask = LISTED ? a.tile_mask + (size_t)b * a.nKT : nullptr;
+    const int n_steps = LISTED ? a.tile_count[b] : a.nKT;
+    const int last = n_steps - 1;
+    const int tail = a.Lk - (a.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
+    auto tile_of = [&](int j) -> int {
+        j = j < last ? j : last;  // past the end: the last tile again (fetched into a buffer nobody reads)
+        if constexpr (LISTED) return tlist[j];
+        return j;
+    };
+    auto mask_of = [&](int j) -> uint64_t {
+        if (j > last) return ~0ull;
+        if constexpr (LISTED) return tmask[tlist[j]];
+        return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
+    };
     auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
-        tk = tk < last ? tk : last;  // past the end: re-fetch the last tile into a buffer nobody reads
-        tv = tv < last ? tv : last;
+        tk = tile_of(tk);
+        tv = tile_of(tv);
         const uint8_t* ksrc = tiles + (size_t)tk * G::TILE_BYTES;
         const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
         uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
@@ -143,8 +159,6 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
 
     const int kread_off = l32 * G::KROW + half * 16;
     const int vread_off = l32 * G::VROW + half * 16;
-    const int tail = a.Lk - last * kBK;  // valid keys of the last tile (1..64)
-
     // S^T of one tile: two 32-key blocks per query block
     auto qk_tile = [&](f32x16 (&S)[2][QB], int buf) {
         const uint8_t* kt = kbuf + buf * G::K_BYTES + kread_off;
@@ -165,9 +179,9 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         }
     };
 
-    // keys >= Lk of the last tile leave the softmax
-    auto mask_tail = [&](f32x16 (&S)[2][QB]) {
-        const uint64_t mlane = ((1ull << tail) - 1ull) >> (4 * half);
+    // keys whose mask bit is clear leave the softmax
+    auto mask_apply = [&](f32x16 (&S)[2][QB], uint64_t mask) {
+        const uint64_t mlane = mask >> (4 * half);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -315,8 +329,9 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         bool need = any_row_needs_shift();
         dma_wait_and_sync();
         // rare paths, outside the pipelined block
-        if (j + 1 == last && tail < kBK) {
-            mask_tail(Sn);
+        const uint64_t mnext = mask_of(j + 1);
+        if (mnext != ~0ull) {
+            mask_apply(Sn, mnext);
             row_max(Sn);
             need = any_row_needs_shift();
         }
@@ -324,6 +339,7 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         if (need && j < last) shift_rows(Sn);
     };
 
+    if (n_steps > 0) {  // (a request with no valid key skips to the epilogue: zeros, lse = -inf)
     // ---- prologue: tiles 0 (K, V) and 1 (K); scores of tile 0 become the first running maximum ----
     dma_tiles(0, 0, 0, 0);
     dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
@@ -331,8 +347,8 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     f32x16 S0[2][QB], S1[2][QB];
     qk_tile(S0, 0);
     __syncthreads();  // every wavefront has read K'(0) before iteration 0 streams K'(2) over it
-    if (last == 0 && tail < kBK) mask_tail(S0);
-    row_max(S0);  // finite: every tile holds at least one valid key
+    if (mask_of(0) != ~0ull) mask_apply(S0, mask_of(0));
+    row_max(S0);  // finite: every listed tile holds at least one valid key
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         m_run[qb] = mx_new[qb];
@@ -345,11 +361,12 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     }
 
     int j = 0;
-    for (; j + 1 < a.nKT; j += 2) {
+    for (; j + 1 < n_steps; j += 2) {
         iteration(S0, S1, j);
         iteration(S1, S0, j + 1);
     }
-    if (j < a.nKT) iteration(S0, S1, j);
+    if (j < n_steps) iteration(S0, S1, j);
+    }
 
     // ---- epilogue ----
 #pragma unroll
@@ -381,9 +398,9 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     }
 }
 
-template <int D, int QB, int QK_OP, int PV_OP, int NW>
+template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
 hipError_t launch_attn_pipe_inst(const AttnArgs& a, hipStream_t s) {
-    auto kern = attn_fwd_pipe_kernel<D, QB, QK_OP, PV_OP, NW>;
+    auto kern = attn_fwd_pipe_kernel<D, QB, QK_OP, PV_OP, NW, LISTED>;
     constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);

@@ -18,9 +18,15 @@ hipError_t launch_attn_d128_qb2(const AttnArgs& a, int qk_op, int pv_op, bool fu
 }
 
 hipError_t launch_attn_pipe_d128_qb2(const AttnArgs& a, int qk_op, int pv_op, int nw, hipStream_t s) {
-#define DIT_PIPE_CASE(QK, PV)                                                                   \
-    if (qk_op == QK && pv_op == PV)                                                              \
-        return nw == 8 ? launch_attn_pipe_inst<128, 2, QK, PV, 8>(a, s) : launch_attn_pipe_inst<128, 2, QK, PV, 4>(a, s);
+    const bool listed = a.tile_mask != nullptr;
+#define DIT_PIPE_CASE(QK, PV)                                                                       \
+    if (qk_op == QK && pv_op == PV) {                                                                \
+        if (listed)                                                                                  \
+            return nw == 8 ? launch_attn_pipe_inst<128, 2, QK, PV, 8, true>(a, s)                     \
+                           : launch_attn_pipe_inst<128, 2, QK, PV, 4, true>(a, s);                    \
+        return nw == 8 ? launch_attn_pipe_inst<128, 2, QK, PV, 8, false>(a, s)                        \
+                       : launch_attn_pipe_inst<128, 2, QK, PV, 4, false>(a, s);                       \
+    }
     DIT_PIPE_CASE(OP_F16, OP_F16)
     DIT_PIPE_CASE(OP_F16, OP_BF16)
     DIT_PIPE_CASE(OP_BF16, OP_F16)

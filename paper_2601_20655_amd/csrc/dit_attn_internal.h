@@ -52,6 +52,8 @@ struct PackArgs {
     const uint8_t* valid;  // nullable [B, Lk]
     uint8_t* tiles;        // [B*H, nKT, TILE_BYTES]
     uint64_t* tile_mask;   // nullable [B, nKT]
+    int* tile_list;        // nullable [B, nKT], filled by launch_tile_compact
+    int* tile_count;       // nullable [B]
     const float2* tab;     // nullable (no rotation)
     int B, H, Lk, nKT;
     int in_f32;
@@ -65,6 +67,8 @@ struct AttnArgs {
     float* lse;                 // nullable
     const uint8_t* tiles;       // pre-packed K'/V^T tiles
     const uint64_t* tile_mask;  // nullable [B, nKT]; bit = key of the tile attends
+    const int* tile_list;       // with tile_mask: [B, nKT] indices of the tiles with any valid key, ascending
+    const int* tile_count;      // with tile_mask: [B] how many entries of tile_list are used
     const float2* tab;          // nullable: no rotation of q
     // raw K/V for the fused staging path
     const void* k;
@@ -79,6 +83,8 @@ struct AttnArgs {
 
 hipError_t launch_rope_table(const TableArgs& a, hipStream_t s);
 hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
+// after launch_prepack: compact the non-empty tiles of every batch entry into tile_list / tile_count
+hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s);
 // qb = 32-row query blocks per wavefront (1 or 2)
 hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, bool fused,
                        hipStream_t s);

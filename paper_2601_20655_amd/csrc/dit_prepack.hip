@@ -93,6 +93,29 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     }
 }
 
+// One wavefront per batch entry: tile_list[b] = ascending indices of tiles whose key mask is not empty.
+__global__ void __launch_bounds__(64) tile_compact_kernel(const uint64_t* tile_mask, int* tile_list,
+                                                          int* tile_count, int nKT) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const uint64_t* m = tile_mask + (size_t)b * nKT;
+    int* out = tile_list + (size_t)b * nKT;
+    int count = 0;
+    for (int base = 0; base < nKT; base += 64) {
+        const int t = base + lane;
+        const bool keep = t < nKT && m[t] != 0ull;
+        const uint64_t votes = __ballot(keep);
+        if (keep) out[count + __popcll(votes & ((1ull << lane) - 1ull))] = t;
+        count += __popcll(votes);
+    }
+    if (lane == 0) tile_count[b] = count;
+}
+
+hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(tile_compact_kernel, dim3(a.B), dim3(64), 0, s, a.tile_mask, a.tile_list, a.tile_count,
+                       a.nKT);
+    return hipGetLastError();
+}
+
 template <int D, int QK_OP, int PV_OP>
 static hipError_t launch_prepack_inst(const PackArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((kv_prepack_kernel<D, QK_OP, PV_OP>), dim3(a.nKT, a.H, a.B), dim3(kThreads), 0, s, a);

@@ -68,7 +68,7 @@ def test_workspace_size_formula():
     p = self_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)
     assert B.dit_attn_workspace_bytes(p) == up((2 * 22 + 3 * 21 + 4 * 21) * 8)
     c = cross_params()
-    assert B.dit_cross_attn_workspace_bytes(c) == up(2 * 13 * 8) + up(2 * 2 * 13 * 36 * 1024)
+    assert B.dit_cross_attn_workspace_bytes(c) == up(2 * 13 * 8) + up(2 * 13 * 4) + up(2 * 4) + up(2 * 2 * 13 * 36 * 1024)
 
 
 FAKE = 0x1000  # a 16-byte aligned non-NULL address that is never dereferenced: validation fails first

@@ -19,8 +19,18 @@ def run_cross(q, k, v, valid, **kw):
     return res
 
 
+SHAPES = {
+    "auto": 0,
+    "qb1_4w": B.DIT_FLAG_SMALL_WORKGROUP,
+    "qb1_8w": B.DIT_FLAG_BIG_WORKGROUP,
+    "qb2_4w": B.DIT_FLAG_WIDE_QTILE,
+    "simple_qb1": B.DIT_FLAG_SIMPLE_SCHEDULE,
+    "simple_qb2": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
+}
+
+
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("wide", [False, True])
+@pytest.mark.parametrize("wide", sorted(SHAPES))
 def test_small_cross_with_masks(D, wide):
     import torch
 
@@ -29,7 +39,7 @@ def test_small_cross_with_masks(D, wide):
     valid[2, :] = 0
     valid[2, 700] = 1  # a request with a single valid key: output = that value row
     ref, ref_lse = oracle.cross_attn(q, k, v, valid, want_lse=True)
-    flags = B.DIT_FLAG_WIDE_QTILE if wide else 0
+    flags = SHAPES[wide]
     out, lse = run_cross(q, k, v, valid, flags=flags, out_dtype=torch.float32, want_lse=True)
     compare(to_f64(out), ref, what="cross D=%d wide=%s" % (D, wide))
     assert np.max(np.abs(to_f64(lse) - ref_lse)) < 5e-3
@@ -52,12 +62,13 @@ def test_fully_masked_request_and_garbage_under_mask():
     kb[0, valid[0] == 0] = 3.0e4; vb[0, valid[0] == 0] = -3.0e4
     k2, v2 = wl.f32_to_bf16_bits(kb), wl.f32_to_bf16_bits(vb)
     ref, ref_lse = oracle.cross_attn(q, k2, v2, valid, want_lse=True)
-    out, lse = run_cross(q, k2, v2, valid, out_dtype=torch.float32, want_lse=True)
-    o = to_f64(out)
-    compare(o[0], ref[0], what="garbage under mask")
-    assert np.all(o[1] == 0.0)
-    assert np.all(np.isneginf(to_f64(lse)[1]))
     assert np.all(np.isneginf(ref_lse[1]))
+    for name, flags in sorted(SHAPES.items()):
+        out, lse = run_cross(q, k2, v2, valid, out_dtype=torch.float32, want_lse=True, flags=flags)
+        o = to_f64(out)
+        compare(o[0], ref[0], what="garbage under mask, %s" % name)
+        assert np.all(o[1] == 0.0)
+        assert np.all(np.isneginf(to_f64(lse)[1]))
 
 
 def test_full_size_cross_sampled_rows():
