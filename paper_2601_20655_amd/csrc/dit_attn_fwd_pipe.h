@@ -25,7 +25,25 @@
 #define DIT_PIPE_PRE 4  // exp slices issued before the first MFMA of an iteration (covers LDS latency)
 #endif
 
+#ifndef DIT_PIPE_DSTEP
+#define DIT_PIPE_DSTEP 0  // one tile-streaming load every this many MFMA steps of part A; 0 (all up front) measured best
+#endif
+#ifndef DIT_PIPE_BALANCED
+#define DIT_PIPE_BALANCED 1  // move 6 of the 16 softmax slices from part A into part B (32-row wavefronts, d128)
+#endif
+
 namespace dit {
+
+// Balanced schedule (16 MFMA steps per part, 16 softmax slices): which slice gets its exp2 / its
+// pack+sum after MFMA step t of part A resp. step u of part B (-1: none).  Slices 0..3 take their
+// exp2 before step 0.  A slice is packed at least two steps after its exp2, and part B's PV steps
+// 4*kg.. read the packed slices 4*kg..4*kg+3, so slice c must be packed before step 4*(c/4).
+constexpr int bal_a_exp(int t) { return (t % 2 == 0 && t <= 10) ? 4 + t / 2 : -1; }
+constexpr int bal_a_pack(int t) { return (t % 2 == 1 && t <= 11) ? t / 2 : (t >= 12 ? t - 6 : -1); }
+constexpr int bal_b_exp(int u) { return u <= 2 ? 10 + u : ((u % 2 == 0 && u <= 8) ? 11 + u / 2 : -1); }
+constexpr int bal_b_pack(int u) {
+    return (u % 2 == 1 && u >= 3 && u <= 9) ? 10 + (u - 3) / 2 : (u == 10 ? 14 : (u == 11 ? 15 : -1));
+}
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -118,25 +136,33 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         if constexpr (LISTED) return tmask[tlist[j]];
         return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
     };
-    auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
+    // One tile pair = NDMA loads per wavefront: pieces 2i (K part) and 2i+1 (V part) for i < NI, then
+    // the odd piece.  dma_piece(i, ...) issues load i alone, so the loads can either go out together
+    // at the top of an iteration or be spread over part A (DIT_PIPE_DSTEP).
+    constexpr int NDMA = 2 * NI + 1;
+    auto dma_piece = [&](int i, int tk, int kb_, int tv, int vb_) {
         tk = tile_of(tk);
         tv = tile_of(tv);
         const uint8_t* ksrc = tiles + (size_t)tk * G::TILE_BYTES;
         const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
         uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
         uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int c = (wave + NW * i) * 1024;
-            __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
-        }
-        if (NW == 4 || wave < 4) {
+        if (i < 2 * NI) {
+            const int c = (wave + NW * (i >> 1)) * 1024;
+            if ((i & 1) == 0)
+                __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
+        } else if (NW == 4 || wave < 4) {
             const int c = (NW * NI + (wave & 1)) * 1024;
             const uint8_t* osrc = wave < 2 ? ksrc : vsrc;
             uint8_t* odst = wave < 2 ? kdst : vdst;
             __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
         }
+    };
+    auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
+#pragma unroll
+        for (int i = 0; i < NDMA; ++i) dma_piece(i, tk, kb_, tv, vb_);
     };
     auto dma_wait_and_sync = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -245,6 +271,9 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     constexpr int PRE = DIT_PIPE_PRE;        // exp slices issued before the first MFMA, covering LDS latency
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
+    // tile-streaming loads: spread over part A when they all fit before its end, else up front
+    constexpr int DSTEP = (DIT_PIPE_DSTEP > 0 && DIT_PIPE_DSTEP * (NDMA - 1) < NA) ? DIT_PIPE_DSTEP : 0;
+    constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4;
 
     auto iteration = [&](f32x16 (&Sc)[2][QB], f32x16 (&Sn)[2][QB], int j) {
         const uint8_t* kt = kbuf + ((j + 1) & 1) * G::K_BYTES + kread_off;
@@ -256,7 +285,7 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         u32x4 kf[2 * NKS], vf[4 * NDB];
 #pragma unroll
         for (int f = 0; f < LA; ++f) kf[f] = kfrag(f);
-        dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
+        if constexpr (DSTEP == 0) dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
 
         uint32_t Pd[QB][16];
         float ls[QB][2];
@@ -283,19 +312,22 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
             if (qb == 0 && f + LA < 2 * NKS) kf[f + LA] = kfrag(f + LA);
             // the last steps of part A fetch the first V^T fragments of part B
             if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
+            if constexpr (DSTEP > 0) {
+                if (t % DSTEP == 0 && t / DSTEP < NDMA) dma_piece(t / DSTEP, j + 2, j & 1, j + 1, (j + 1) & 1);
+            }
             Sn[kb][qb] = mfma32<QK_OP>(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb]);
+            if constexpr (BAL) {
+                if (bal_a_exp(t) >= 0) exp_slice(bal_a_exp(t));
+                if (bal_a_pack(t) >= 0) pack_slice(bal_a_pack(t));
+            } else {
 #pragma unroll
-            for (int cc = 0; cc < CPA; ++cc) {
-                const int c = t * CPA + cc;
-                if (c + PRE < NCH) exp_slice(c + PRE);
-                pack_slice(c);
+                for (int cc = 0; cc < CPA; ++cc) {
+                    const int c = t * CPA + cc;
+                    if (c + PRE < NCH) exp_slice(c + PRE);
+                    pack_slice(c);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            l_run[qb] += ls[qb][0] + ls[qb][1];
-            asm volatile("" : "+v"(l_run[qb]));  // keeps the row-sum chain in part A (it would sink past the barrier)
         }
 
         // ---- part B: O += V^T(j) P(j) on MFMA, row maxima of S(j+1) on VALU ----
@@ -319,10 +351,19 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
 #pragma unroll
                 for (int cc = 0; cc < CPB; ++cc) max_slice((u - 2) * CPB + cc);
             }
+            if constexpr (BAL) {
+                if (bal_b_exp(u) >= 0) exp_slice(bal_b_exp(u));
+                if (bal_b_pack(u) >= 0) pack_slice(bal_b_pack(u));
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int c = (NB - 2) * CPB; c < NCH; ++c) max_slice(c);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            l_run[qb] += ls[qb][0] + ls[qb][1];
+            asm volatile("" : "+v"(l_run[qb]));  // keeps the row-sum chain here (it would sink past the barrier)
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
             mx_new[qb] = max_across_halves(fmaxf(max3(pm[qb][0], pm[qb][1], pm[qb][2]), pm[qb][3]));
