@@ -25,7 +25,7 @@ PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
 # HBM bytes per launch of the self-attention kernel at the dit_14b shape, default flags, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
 # keyed by library version: a library whose kernel has changed since reports null.
-TRAFFIC_BYTES_BY_VERSION = {101: 3.69e9, 102: 3.69e9}  # 102 changed the cross-attention kernel only
+TRAFFIC_BYTES_BY_VERSION = {103: 4.09e9}
 
 
 class HipEvents:
@@ -167,7 +167,7 @@ def main():
             "flops_per_step": flops_self + flops_cross,
         },
         "roofline": {
-            "kernel": "attn_fwd_kernel (self-attention, 32,760 x 32,760 x 40 heads)",
+            "kernel": "attn_fwd_pipe_kernel (self-attention, 32,760 x 32,760 x 40 heads)",
             "bound": "mfma",
             "achieved": round(achieved, 2),
             "peak": PEAK_TFLOPS_16BIT_DENSE,

@@ -78,7 +78,11 @@ enum {
      * rows, two workgroups per CU.  Neither flag: BIG when that still gives every CU at least
      * two workgroups, else SMALL. */
     DIT_FLAG_BIG_WORKGROUP = 1u << 8,
-    DIT_FLAG_SMALL_WORKGROUP = 1u << 9
+    DIT_FLAG_SMALL_WORKGROUP = 1u << 9,
+    /* Cross-attention runs the plain kernel by default: with a dozen key tiles per query tile its
+     * shorter prologue beats the pipelined kernel's better steady state (measured).  This flag
+     * selects the pipelined kernel there too.  No effect on self-attention. */
+    DIT_FLAG_PIPELINED_SCHEDULE = 1u << 10
 };
 
 typedef struct {
@@ -125,8 +129,8 @@ dit_status dit_attn_forward(const void *q, const void *k, const void *v, void *o
  * embeddings, concatenated by the caller), no positional rotation, ONE joint softmax over
  * the Lk keys.  kv_valid (nullable): uint8 [B, Lk] dense, 1 = key attends, 0 = padding.
  * A request with no valid key yields out = 0 and lse = -inf.
- * Flags: QK_*, PV_*, WIDE_QTILE, SIMPLE_SCHEDULE and the workgroup-size flags apply; K/V are always
- * pre-packed; tiles without a valid key are neither loaded nor computed.
+ * Flags: QK_*, PV_*, WIDE_QTILE, PIPELINED_SCHEDULE and (with it) the workgroup-size flags apply; K/V are
+ * always pre-packed; tiles without a valid key are neither loaded nor computed.
  */
 typedef struct {
     int32_t B, H, D;

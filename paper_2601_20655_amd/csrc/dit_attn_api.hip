@@ -51,14 +51,15 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Flags {
     int qk_op, pv_op, qb, nw;
-    bool fused, simple;
+    bool fused, simple, pipelined;
 };
 
 // Resolve flag bits into operand types and staging mode.
 dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
                            DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
-                           DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP | DIT_FLAG_SMALL_WORKGROUP;
+                           DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP | DIT_FLAG_SMALL_WORKGROUP |
+                           DIT_FLAG_PIPELINED_SCHEDULE;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
@@ -67,7 +68,9 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     out->pv_op = (f & DIT_FLAG_PV_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
     out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
+    if ((f & DIT_FLAG_SIMPLE_SCHEDULE) && (f & DIT_FLAG_PIPELINED_SCHEDULE)) return DIT_ERR_INVALID_ARG;
     out->simple = (f & DIT_FLAG_SIMPLE_SCHEDULE) != 0;
+    out->pipelined = (f & DIT_FLAG_PIPELINED_SCHEDULE) != 0;
     if ((f & DIT_FLAG_BIG_WORKGROUP) && (f & DIT_FLAG_SMALL_WORKGROUP)) return DIT_ERR_INVALID_ARG;
     out->nw = (f & DIT_FLAG_BIG_WORKGROUP) ? 8 : (f & DIT_FLAG_SMALL_WORKGROUP) ? 4 : 0;  // 0 = choose by size
     return DIT_OK;
@@ -177,6 +180,7 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
         return DIT_ERR_INVALID_ARG;
     pl->nKT = (p->Lk + dit::kBK - 1) / dit::kBK;
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
+    if (!pl->fl.pipelined) pl->fl.simple = true;  // cross-attention default: the plain kernel
     if (pl->fl.simple || pl->fl.qb == 2) {
         pl->fl.nw = 4;
     } else if (pl->fl.nw == 0) {
@@ -348,6 +352,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 102; }
+int dit_attn_version(void) { return 103; }
 
 }  // extern "C"

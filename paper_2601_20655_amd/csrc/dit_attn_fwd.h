@@ -49,28 +49,6 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
     const int bh = logical / a.nQT;
     const int b = bh / a.H, h = bh - b * a.H;
 
-    // ---- Q prologue: load, rotate, fold scale*log2(e), round once, keep as B operands ----
-    u32x4 Qf[QB][NKS];
-    int qrow[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
-        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
-        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
-        int pt = 0, ph = 0, pw = 0;
-        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const int c = 2 * ks + half;
-            float x[8];
-            load8(a.q, base + 8 * c, a.in_f32, x);
-            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
-            Qf[qb][ks] = pack8<QK_OP>(x);
-        }
-    }
-
     // ---- staging of K/V tiles ----
     const int kchunk_off = (tid / CPR) * G::KROW + (tid % CPR) * 16;
     const int vchunk_off = G::K_BYTES + (tid >> 3) * G::VROW + (tid & 7) * 16;
@@ -175,25 +153,61 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
 
     const int kread_off = l32 * G::KROW + half * 16;
     const int vread_off = G::K_BYTES + l32 * G::VROW + half * 16;
+    // With key masks (cross-attention) the loop runs over the compacted list of tiles that hold a
+    // valid key; otherwise over all tiles, of which only the last can be ragged.
     const uint64_t* tmask = a.tile_mask ? a.tile_mask + (size_t)b * a.nKT : nullptr;
+    const int* tlist = a.tile_mask ? a.tile_list + (size_t)b * a.nKT : nullptr;
+    const int n_steps = a.tile_mask ? a.tile_count[b] : a.nKT;
     const int tail = a.Lk - (a.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
+    auto tile_of = [&](int j) -> int { return tlist ? tlist[j] : j; };
 
-    issue_loads(0);
-    write_lds(0, 0);
-    __syncthreads();
+    // the first tile is on its way while the Q prologue waits for its own loads
+    int tile = 0;
+    if (n_steps > 0) {
+        tile = tile_of(0);
+        issue_loads(tile);
+    }
 
-    for (int j = 0; j < a.nKT; ++j) {
+    // ---- Q prologue: load, rotate, fold scale*log2(e), round once, keep as B operands ----
+    u32x4 Qf[QB][NKS];
+    int qrow[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
+        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
+        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        int pt = 0, ph = 0, pw = 0;
+        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int c = 2 * ks + half;
+            float x[8];
+            load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
+            Qf[qb][ks] = pack8<QK_OP>(x);
+        }
+    }
+
+    if (n_steps > 0) {
+        write_lds(tile, 0);
+        __syncthreads();
+    }
+
+    for (int j = 0; j < n_steps; ++j) {
         const int buf = j & 1;
-        if (j + 1 < a.nKT) issue_loads(j + 1);
+        const int next_tile = j + 1 < n_steps ? tile_of(j + 1) : 0;
+        if (j + 1 < n_steps) issue_loads(next_tile);
 
         uint64_t mask;
         if (tmask) {
-            mask = tmask[j];
+            mask = tmask[tile];
         } else {
-            mask = (j == a.nKT - 1 && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
+            mask = (tile == a.nKT - 1 && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
         }
 
-        if (mask != 0ull) {
+        {
             const uint8_t* kt = smem + buf * G::TILE_BYTES + kread_off;
             const uint8_t* vt = smem + buf * G::TILE_BYTES + vread_off;
 
@@ -281,8 +295,9 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
             }
         }
 
-        if (j + 1 < a.nKT) write_lds(j + 1, buf ^ 1);
+        if (j + 1 < n_steps) write_lds(next_tile, buf ^ 1);
         __syncthreads();
+        tile = next_tile;
     }
 
     // ---- epilogue: normalise and store; lane holds channels 32*db + 8*g + 4*half + e ----

@@ -28,6 +28,9 @@
 #ifndef DIT_PIPE_DSTEP
 #define DIT_PIPE_DSTEP 0  // one tile-streaming load every this many MFMA steps of part A; 0 (all up front) measured best
 #endif
+#ifndef DIT_PIPE_DMA_DUTY
+#define DIT_PIPE_DMA_DUTY 0  // 8-wavefront workgroups: wavefronts 0-3 / 4-7 take turns streaming the whole tile pair
+#endif
 #ifndef DIT_PIPE_BALANCED
 #define DIT_PIPE_BALANCED 1  // move 6 of the 16 softmax slices from part A into part B (32-row wavefronts, d128)
 #endif
@@ -93,27 +96,8 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     const int bh = logical / a.nQT;
     const int b = bh / a.H, h = bh - b * a.H;
 
-    // ---- Q prologue (identical to attn_fwd_kernel) ----
-    u32x4 Qf[QB][NKS];
+    u32x4 Qf[QB][NKS];  // filled after the first tiles have been requested
     int qrow[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
-        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
-        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
-        int pt = 0, ph = 0, pw = 0;
-        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const int c = 2 * ks + half;
-            float x[8];
-            load8(a.q, base + 8 * c, a.in_f32, x);
-            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
-            Qf[qb][ks] = pack8<QK_OP>(x);
-        }
-    }
 
     // ---- tile streaming.  A tile part is PART_KIB pieces of 1 KiB (64 lanes x 16 bytes).  Wavefront
     // w moves pieces w, w+NW, ... of both parts; the two odd pieces of the K part go to wavefronts
@@ -163,6 +147,29 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) dma_piece(i, tk, kb_, tv, vb_);
+    };
+    // Duty form for 8 wavefronts: one wavefront per SIMD (0-3 on even steps, 4-7 on odd steps)
+    // streams the whole tile pair, 9 loads each at d128, while its SIMD neighbour keeps the
+    // matrix pipe busy.
+    auto dma_tiles_duty = [&](int j, int tk, int kb_, int tv, int vb_) {
+        if ((wave >> 2) != (j & 1)) return;
+        tk = tile_of(tk);
+        tv = tile_of(tv);
+        const uint8_t* ksrc = tiles + (size_t)tk * G::TILE_BYTES;
+        const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
+        uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
+        uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
+        const int w4 = wave & 3;
+#pragma unroll
+        for (int i = 0; i < G::PART_KIB / 4; ++i) {
+            const int c = (w4 + 4 * i) * 1024;
+            __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
+        }
+        const int c = (4 * (G::PART_KIB / 4) + (w4 & 1)) * 1024;
+        const uint8_t* osrc = w4 < 2 ? ksrc : vsrc;
+        uint8_t* odst = w4 < 2 ? kdst : vdst;
+        __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
     };
     auto dma_wait_and_sync = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -272,7 +279,8 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
     // tile-streaming loads: spread over part A when they all fit before its end, else up front
-    constexpr int DSTEP = (DIT_PIPE_DSTEP > 0 && DIT_PIPE_DSTEP * (NDMA - 1) < NA) ? DIT_PIPE_DSTEP : 0;
+    constexpr int DSTEP = (DIT_PIPE_DSTEP > 0 && DIT_PIPE_DSTEP * (NDMA - 1) < NA && !(NW == 8 && DIT_PIPE_DMA_DUTY))
+                              ? DIT_PIPE_DSTEP : 0;
     constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4;
 
     auto iteration = [&](f32x16 (&Sc)[2][QB], f32x16 (&Sn)[2][QB], int j) {
@@ -285,7 +293,11 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         u32x4 kf[2 * NKS], vf[4 * NDB];
 #pragma unroll
         for (int f = 0; f < LA; ++f) kf[f] = kfrag(f);
-        if constexpr (DSTEP == 0) dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
+        if constexpr (NW == 8 && DIT_PIPE_DMA_DUTY) {
+            dma_tiles_duty(j, j + 2, j & 1, j + 1, (j + 1) & 1);
+        } else if constexpr (DSTEP == 0) {
+            dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
+        }
 
         uint32_t Pd[QB][16];
         float ls[QB][2];
@@ -380,10 +392,34 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
         if (need && j < last) shift_rows(Sn);
     };
 
+    // ---- prologue: tiles 0 (K, V) and 1 (K) start streaming, then Q is loaded while they fly ----
+    if (n_steps > 0) {
+        dma_tiles(0, 0, 0, 0);
+        dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
+    }
+
+    // ---- Q: load, rotate, fold scale*log2(e), round once, keep as B operands ----
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
+        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
+        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        int pt = 0, ph = 0, pw = 0;
+        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int c = 2 * ks + half;
+            float x[8];
+            load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
+            Qf[qb][ks] = pack8<QK_OP>(x);
+        }
+    }
+
     if (n_steps > 0) {  // (a request with no valid key skips to the epilogue: zeros, lse = -inf)
-    // ---- prologue: tiles 0 (K, V) and 1 (K); scores of tile 0 become the first running maximum ----
-    dma_tiles(0, 0, 0, 0);
-    dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
+    // scores of tile 0 become the first running maximum
     dma_wait_and_sync();
     f32x16 S0[2][QB], S1[2][QB];
     qk_tile(S0, 0);

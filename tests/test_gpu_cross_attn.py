@@ -21,9 +21,9 @@ def run_cross(q, k, v, valid, **kw):
 
 SHAPES = {
     "auto": 0,
-    "qb1_4w": B.DIT_FLAG_SMALL_WORKGROUP,
-    "qb1_8w": B.DIT_FLAG_BIG_WORKGROUP,
-    "qb2_4w": B.DIT_FLAG_WIDE_QTILE,
+    "pipe_qb1_4w": B.DIT_FLAG_PIPELINED_SCHEDULE | B.DIT_FLAG_SMALL_WORKGROUP,
+    "pipe_qb1_8w": B.DIT_FLAG_PIPELINED_SCHEDULE | B.DIT_FLAG_BIG_WORKGROUP,
+    "pipe_qb2_4w": B.DIT_FLAG_PIPELINED_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
     "simple_qb1": B.DIT_FLAG_SIMPLE_SCHEDULE,
     "simple_qb2": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
 }
