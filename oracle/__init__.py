@@ -6,6 +6,7 @@ package; the GPU library never does.  See dit_oracle.c for what is computed and 
 from .dit_oracle import (  # noqa: F401
     build,
     cross_attn,
+    cross_attn_decoupled,
     num_threads,
     rope3d,
     self_attn,

@@ -144,3 +144,27 @@ def cross_attn(q, k, v, kv_valid=None, scale=0.0, rows=None, want_lse=False, pro
     if probs_of is not None:
         res += (probs,)
     return res[0] if len(res) == 1 else res
+
+
+def cross_attn_decoupled(q, k, v, split, kv_valid=None, scale=0.0, rows=None):
+    """Decoupled cross-attention: keys [0, split) and [split, Lk) are two separate conditioning
+    sequences (text, image), each with its OWN softmax; the two attention outputs are added:
+
+        out = softmax(scale q k_A^T) v_A + softmax(scale q k_B^T) v_B.
+
+    A group with no valid key (or no key at all) contributes zero.  This is the definition written
+    out: two independent calls of the joint-softmax routine on the two key ranges, summed.
+    """
+    k = np.ascontiguousarray(k)
+    v = np.ascontiguousarray(v)
+    Lk = k.shape[1]
+    if not 0 <= split <= Lk:
+        raise ValueError("split must lie in [0, Lk]")
+    total = None
+    for lo, hi in ((0, split), (split, Lk)):
+        if hi == lo:
+            continue
+        val = None if kv_valid is None else np.ascontiguousarray(kv_valid[:, lo:hi])
+        part = cross_attn(q, k[:, lo:hi], v[:, lo:hi], val, scale=scale, rows=rows)
+        total = part if total is None else total + part
+    return total

@@ -326,3 +326,51 @@ def test_bad_arguments_are_rejected(rng):
         oracle.self_attn(q, q, q, (2, 2, 1), (4, 2, 2), rows=[4])
     with pytest.raises(ValueError):
         oracle.cross_attn(q, q, q, rows=[-1])
+
+
+def brute_decoupled(q, k, v, split, valid, scale):
+    """One head, pure loops: two explicit softmaxes over the two key ranges, outputs added."""
+    Lq, D = q.shape
+    out = np.zeros((Lq, D))
+    for n in range(Lq):
+        for lo, hi in ((0, split), (split, k.shape[0])):
+            keys = [m for m in range(lo, hi) if valid[m]]
+            if not keys:
+                continue
+            s = [scale * float(np.dot(q[n], k[m])) for m in keys]
+            mx = max(s)
+            e = [math.exp(x - mx) for x in s]
+            z = math.fsum(e)
+            for w, m in zip(e, keys):
+                out[n] += (w / z) * v[m]
+    return out
+
+
+def test_decoupled_cross_attention_pins(rng):
+    B, Lq, Lk, H, D, split = 2, 5, 13, 2, 8, 6
+    q = rng.standard_normal((B, Lq, H, D)); k = rng.standard_normal((B, Lk, H, D)); v = rng.standard_normal((B, Lk, H, D))
+    valid = np.ones((B, Lk), np.uint8); valid[0, [1, 4, 9]] = 0; valid[1, split:] = 0   # request 1: second group empty
+    out = oracle.cross_attn_decoupled(q, k, v, split, valid, scale=0.4)
+    for b in range(B):
+        for h in range(H):
+            np.testing.assert_allclose(out[b, :, h], brute_decoupled(q[b, :, h], k[b, :, h], v[b, :, h], split, valid[b], 0.4),
+                                       atol=1e-13)
+    # an empty second group leaves the joint softmax over the first
+    np.testing.assert_allclose(out[1], oracle.cross_attn(q[1:], k[1:, :split], v[1:, :split], valid[1:, :split], scale=0.4)[0], atol=0)
+    # split at either end is the joint softmax over everything
+    joint = oracle.cross_attn(q, k, v, valid, scale=0.4)
+    np.testing.assert_allclose(oracle.cross_attn_decoupled(q, k, v, Lk, valid, scale=0.4), joint, atol=0)
+    np.testing.assert_allclose(oracle.cross_attn_decoupled(q, k, v, 0, valid, scale=0.4), joint, atol=0)
+    # constant values: each non-empty group returns c, so the sum is (number of non-empty groups) * c
+    c = rng.standard_normal(D)
+    vc = np.broadcast_to(c, v.shape).copy()
+    oc = oracle.cross_attn_decoupled(q, k, vc, split, valid)
+    np.testing.assert_allclose(oc[0], np.broadcast_to(2 * c, oc[0].shape), atol=1e-14)
+    np.testing.assert_allclose(oc[1], np.broadcast_to(c, oc[1].shape), atol=1e-14)
+    # q = 0: uniform weights inside each group -> mean of group A + mean of group B (valid keys only)
+    o0 = oracle.cross_attn_decoupled(np.zeros_like(q), k, v, split, valid)
+    a_idx = [m for m in range(split) if valid[0, m]]; b_idx = [m for m in range(split, Lk) if valid[0, m]]
+    want = v[0, a_idx].mean(axis=0) + v[0, b_idx].mean(axis=0)
+    np.testing.assert_allclose(o0[0], np.broadcast_to(want, o0[0].shape), atol=1e-14)
+    # it is NOT the joint softmax in general
+    assert np.max(np.abs(out[0] - joint[0])) > 1e-2
