@@ -126,8 +126,14 @@ dit_status dit_attn_forward(const void *q, const void *k, const void *v, void *o
 
 /*
  * Cross-attention of Lq query tokens over Lk conditioning tokens (text then image
- * embeddings, concatenated by the caller), no positional rotation, ONE joint softmax over
- * the Lk keys.  kv_valid (nullable): uint8 [B, Lk] dense, 1 = key attends, 0 = padding.
+ * embeddings, concatenated by the caller), no positional rotation.
+ * Lk_split = 0 (or Lk): ONE joint softmax over the Lk keys.
+ * 0 < Lk_split < Lk: decoupled form -- keys [0, Lk_split) and [Lk_split, Lk) are two
+ * conditioning sequences with a softmax each, and the two attention outputs are added:
+ *     out = softmax(scale q k_A^T) v_A + softmax(scale q k_B^T) v_B;
+ * a sequence without a valid key contributes zero.  The first partial result is held in fp16
+ * while the second is accumulated.  lse must be NULL and PIPELINED_SCHEDULE / WIDE_QTILE are
+ * not available in this form (DIT_ERR_UNSUPPORTED).  kv_valid (nullable): uint8 [B, Lk] dense, 1 = key attends, 0 = padding.
  * A request with no valid key yields out = 0 and lse = -inf.
  * Flags: QK_*, PV_*, WIDE_QTILE, PIPELINED_SCHEDULE and (with it) the workgroup-size flags apply; K/V are
  * always pre-packed; tiles without a valid key are neither loaded nor computed.
@@ -139,6 +145,7 @@ typedef struct {
     int32_t in_dtype; /* dit_dtype of q, k, v */
     int32_t out_dtype;
     uint32_t flags;
+    int32_t Lk_split; /* 0: joint softmax; else first key of the second conditioning sequence */
     dit_strides sq, sk, sv, so;
 } dit_cross_attn_params;
 

@@ -68,7 +68,7 @@ class dit_cross_attn_params(ctypes.Structure):
         ("Lq", ctypes.c_int32), ("Lk", ctypes.c_int32),
         ("scale", ctypes.c_float),
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
-        ("flags", ctypes.c_uint32),
+        ("flags", ctypes.c_uint32), ("Lk_split", ctypes.c_int32),
         ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
     ]
 
@@ -163,9 +163,9 @@ def self_attn_params(q, k, v, out, grid, split, origin=(0, 0, 0), rope_base=1000
         _strides(q), _strides(k), _strides(v), _strides(out))
 
 
-def cross_attn_params(q, k, v, out, scale=0.0, flags=0):
+def cross_attn_params(q, k, v, out, scale=0.0, flags=0, split=0):
     B, Lq, H, D = q.shape
-    return dit_cross_attn_params(B, H, D, Lq, k.shape[1], scale, _dtype_code(q), _dtype_code(out), flags,
+    return dit_cross_attn_params(B, H, D, Lq, k.shape[1], scale, _dtype_code(q), _dtype_code(out), flags, split,
                                  _strides(q), _strides(k), _strides(v), _strides(out))
 
 
@@ -213,8 +213,9 @@ def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0),
 
 
 def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0, flags=0, out_dtype=None,
-                           workspace=None, stream=None, want_lse=False):
-    """Cross-attention: q [B, Lq, H, D]; k, v [B, Lk, H, D]; kv_valid uint8 [B, Lk] or None."""
+                           workspace=None, stream=None, want_lse=False, split=0):
+    """Cross-attention: q [B, Lq, H, D]; k, v [B, Lk, H, D]; kv_valid uint8 [B, Lk] or None.
+    split > 0 selects the decoupled form (separate softmax over keys [0, split) and [split, Lk))."""
     import torch
 
     if not q.is_cuda:
@@ -227,7 +228,7 @@ def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0
     if kv_valid is not None:
         if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, k.shape[1]):
             raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
-    p = cross_attn_params(q, k, v, out, scale, flags)
+    p = cross_attn_params(q, k, v, out, scale, flags, split)
     need = dit_cross_attn_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)

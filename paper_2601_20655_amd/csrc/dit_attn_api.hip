@@ -81,7 +81,9 @@ dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused,
     const bool timed = g_ev_before && g_ev_after;
     hipError_t e;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
-    if (!fused && !fl.simple) {
+    if (aa.tile_count_a) {
+        e = dit::launch_attn_split(aa, D, fl.qk_op, fl.pv_op, s);
+    } else if (!fused && !fl.simple) {
         e = dit::launch_attn_pipe(aa, D, fl.qb, fl.qk_op, fl.pv_op, fl.nw, s);
     } else {
         e = dit::launch_attn(aa, D, fl.qb, fl.qk_op, fl.pv_op, fused, s);
@@ -162,7 +164,8 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
 struct CrossPlan {
     Flags fl;
     int nKT, nQT;
-    size_t mask_off, list_off, count_off, tiles_off, total;
+    int split, nTA;  // decoupled form: first key of the second sequence, tiles of the first (0, 0: joint)
+    size_t mask_off, list_off, count_off, count_a_off, tiles_off, total;
 };
 
 dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
@@ -178,7 +181,11 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     if (!strides_ok(p->sq, p->B, p->H, p->D) || !strides_ok(p->sk, p->B, p->H, p->D) ||
         !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
         return DIT_ERR_INVALID_ARG;
-    pl->nKT = (p->Lk + dit::kBK - 1) / dit::kBK;
+    if (p->Lk_split < 0 || p->Lk_split > p->Lk) return DIT_ERR_INVALID_ARG;
+    pl->split = (p->Lk_split == p->Lk) ? 0 : p->Lk_split;  // a split at either end is the joint softmax
+    pl->nTA = (pl->split + dit::kBK - 1) / dit::kBK;
+    pl->nKT = pl->nTA + (p->Lk - pl->split + dit::kBK - 1) / dit::kBK;
+    if (pl->split > 0 && (pl->fl.pipelined || pl->fl.qb == 2)) return DIT_ERR_UNSUPPORTED;
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
     if (!pl->fl.pipelined) pl->fl.simple = true;  // cross-attention default: the plain kernel
     if (pl->fl.simple || pl->fl.qb == 2) {
@@ -195,7 +202,8 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     pl->mask_off = 0;
     pl->list_off = round_up((size_t)p->B * pl->nKT * sizeof(uint64_t), kAlign);
     pl->count_off = pl->list_off + round_up((size_t)p->B * pl->nKT * sizeof(int), kAlign);
-    pl->tiles_off = pl->count_off + round_up((size_t)p->B * sizeof(int), kAlign);
+    pl->count_a_off = pl->count_off + round_up((size_t)p->B * sizeof(int), kAlign);
+    pl->tiles_off = pl->count_a_off + round_up((size_t)p->B * sizeof(int), kAlign);
     pl->total = pl->tiles_off + round_up((size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D), kAlign);
     return DIT_OK;
 }
@@ -293,6 +301,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
         !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
         return DIT_ERR_ALIGNMENT;
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
+    if (lse && pl.split > 0) return DIT_ERR_UNSUPPORTED;  // two softmaxes have no single log-sum-exp
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
         return DIT_ERR_WORKSPACE;
 
@@ -307,6 +316,9 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.tile_mask = reinterpret_cast<uint64_t*>(ws + pl.mask_off);
     pa.tile_list = reinterpret_cast<int*>(ws + pl.list_off);
     pa.tile_count = reinterpret_cast<int*>(ws + pl.count_off);
+    pa.tile_count_a = pl.split > 0 ? reinterpret_cast<int*>(ws + pl.count_a_off) : nullptr;
+    pa.split = pl.split;
+    pa.nTA = pl.nTA;
     pa.tab = nullptr;
     pa.B = p->B; pa.H = p->H; pa.Lk = p->Lk; pa.nKT = pl.nKT;
     pa.in_f32 = p->in_dtype == DIT_F32;
@@ -324,6 +336,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     aa.tile_mask = pa.tile_mask;
     aa.tile_list = pa.tile_list;
     aa.tile_count = pa.tile_count;
+    aa.tile_count_a = pa.tile_count_a;
     aa.tab = nullptr;
     aa.B = p->B; aa.H = p->H; aa.Lq = p->Lq; aa.Lk = p->Lk; aa.nKT = pl.nKT; aa.nQT = pl.nQT;
     aa.in_f32 = p->in_dtype == DIT_F32; aa.out_f32 = p->out_dtype == DIT_F32;
@@ -352,6 +365,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 103; }
+int dit_attn_version(void) { return 104; }
 
 }  // extern "C"

@@ -18,7 +18,10 @@ namespace dit {
 // and the accumulator rescale is skipped on most tiles.
 constexpr float kRescaleThr = 8.0f;
 
-template <int D, int QB, int QK_OP, int PV_OP, bool FUSED>
+// SPLIT: decoupled cross-attention.  The first tile_count_a[b] listed tiles form one softmax, the
+// rest a second one; when the loop crosses over, the first result is normalised, parked in
+// registers as fp16 and added back in the epilogue.
+template <int D, int QB, int QK_OP, int PV_OP, bool FUSED, bool SPLIT = false>
 __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(const AttnArgs a) {
     using G = TileGeom<D>;
     constexpr int NKS = D / 16;           // contraction steps of the score product
@@ -29,6 +32,7 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
     constexpr int NI_K = kBK / KROWS_PER_PASS;
     constexpr int NI_V = D / 32;          // V^T: 8 chunks per row, 32 rows per pass
     static_assert(!FUSED || (PV_OP == OP_BF16 && D == 128), "fused staging keeps V in bf16, D = 128");
+    static_assert(!SPLIT || !FUSED, "the decoupled form works on pre-packed tiles");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -195,8 +199,37 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
         __syncthreads();
     }
 
+    // first softmax's output, fp16 pairs in the accumulator's lane layout (zero until the switch)
+    uint32_t first[SPLIT ? QB : 1][SPLIT ? NDB * 8 : 1];
+    const int n_first = SPLIT ? a.tile_count_a[b] : -1;
+    if constexpr (SPLIT) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int i = 0; i < NDB * 8; ++i) first[qb][i] = 0u;
+    }
+
     for (int j = 0; j < n_steps; ++j) {
         const int buf = j & 1;
+        if constexpr (SPLIT) {
+            if (j == n_first) {  // wave-uniform: the second conditioning sequence starts here
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32);
+                    const float inv = l > 0.f ? 1.0f / l : 0.f;
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) {
+                            first[qb][db * 8 + r / 2] = pack2<OP_F16>(O[db][qb][r] * inv, O[db][qb][r + 1] * inv);
+                            O[db][qb][r] = 0.f;
+                            O[db][qb][r + 1] = 0.f;
+                        }
+                    m_run[qb] = -INFINITY;
+                    l_run[qb] = 0.f;
+                }
+            }
+        }
         const int next_tile = j + 1 < n_steps ? tile_of(j + 1) : 0;
         if (j + 1 < n_steps) issue_loads(next_tile);
 
@@ -312,8 +345,14 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int d0 = 32 * db + 8 * g + 4 * half;
-                    const float o0 = O[db][qb][4 * g + 0] * inv, o1 = O[db][qb][4 * g + 1] * inv;
-                    const float o2 = O[db][qb][4 * g + 2] * inv, o3 = O[db][qb][4 * g + 3] * inv;
+                    float o0 = O[db][qb][4 * g + 0] * inv, o1 = O[db][qb][4 * g + 1] * inv;
+                    float o2 = O[db][qb][4 * g + 2] * inv, o3 = O[db][qb][4 * g + 3] * inv;
+                    if constexpr (SPLIT) {
+                        const f16x2 f01 = __builtin_bit_cast(f16x2, first[qb][db * 8 + 2 * g]);
+                        const f16x2 f23 = __builtin_bit_cast(f16x2, first[qb][db * 8 + 2 * g + 1]);
+                        o0 += (float)f01[0]; o1 += (float)f01[1];
+                        o2 += (float)f23[0]; o3 += (float)f23[1];
+                    }
                     if (a.out_f32) {
                         *reinterpret_cast<float4*>(static_cast<float*>(a.out) + obase + d0) =
                             make_float4(o0, o1, o2, o3);
@@ -330,9 +369,9 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
     }
 }
 
-template <int D, int QB, int QK_OP, int PV_OP, bool FUSED>
+template <int D, int QB, int QK_OP, int PV_OP, bool FUSED, bool SPLIT = false>
 hipError_t launch_attn_inst(const AttnArgs& a, hipStream_t s) {
-    auto kern = attn_fwd_kernel<D, QB, QK_OP, PV_OP, FUSED>;
+    auto kern = attn_fwd_kernel<D, QB, QK_OP, PV_OP, FUSED, SPLIT>;
     constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);

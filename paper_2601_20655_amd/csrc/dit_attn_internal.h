@@ -54,6 +54,8 @@ struct PackArgs {
     uint64_t* tile_mask;   // nullable [B, nKT]
     int* tile_list;        // nullable [B, nKT], filled by launch_tile_compact
     int* tile_count;       // nullable [B]
+    int* tile_count_a;     // nullable [B]: listed tiles that belong to the first key group
+    int split, nTA;        // split > 0: keys [0, split) fill tiles [0, nTA), keys [split, Lk) the rest
     const float2* tab;     // nullable (no rotation)
     int B, H, Lk, nKT;
     int in_f32;
@@ -69,6 +71,7 @@ struct AttnArgs {
     const uint64_t* tile_mask;  // nullable [B, nKT]; bit = key of the tile attends
     const int* tile_list;       // with tile_mask: [B, nKT] indices of the tiles with any valid key, ascending
     const int* tile_count;      // with tile_mask: [B] how many entries of tile_list are used
+    const int* tile_count_a;    // decoupled cross-attention: [B] how many of them form the first softmax
     const float2* tab;          // nullable: no rotation of q
     // raw K/V for the fused staging path
     const void* k;
@@ -88,5 +91,7 @@ hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s);
 // qb = 32-row query blocks per wavefront (1 or 2)
 hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, bool fused,
                        hipStream_t s);
+// plain kernel, two softmaxes (AttnArgs::tile_count_a set), 32 rows per wavefront
+hipError_t launch_attn_split(const AttnArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
 
 }  // namespace dit

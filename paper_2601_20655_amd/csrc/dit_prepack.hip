@@ -43,15 +43,19 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     uint8_t* dst = a.tiles + ((size_t)(b * a.H + h) * a.nKT + j) * G::TILE_BYTES;
     const int c = tid % CPR;
+    // keys of this tile: [key0, key0 + 64) clipped to key_end (two key groups when split > 0)
+    const bool second = a.split > 0 && j >= a.nTA;
+    const int key0 = second ? a.split + (j - a.nTA) * kBK : j * kBK;
+    const int key_end = (a.split > 0 && !second) ? a.split : a.Lk;
 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int r = tid / CPR + i * ROWS_PER_PASS;
-        const int key = j * kBK + r;
+        const int key = key0 + r;
         float xk[8], xv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) xk[e] = xv[e] = 0.f;
-        if (key < a.Lk) {
+        if (key < key_end) {
             load8(a.k, (int64_t)b * a.sk_b + (int64_t)key * a.sk_t + (int64_t)h * a.sk_h + 8 * c, a.in_f32, xk);
             load8(a.v, (int64_t)b * a.sv_b + (int64_t)key * a.sv_t + (int64_t)h * a.sv_h + 8 * c, a.in_f32, xv);
             if (a.tab) {
@@ -85,8 +89,8 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     }
 
     if (a.tile_mask && h == 0 && tid < 64) {
-        const int key = j * kBK + tid;
-        bool ok = key < a.Lk;
+        const int key = key0 + tid;
+        bool ok = key < key_end;
         if (ok && a.valid) ok = a.valid[(size_t)b * a.Lk + key] != 0;
         const uint64_t m = __ballot(ok);
         if (tid == 0) a.tile_mask[(size_t)b * a.nKT + j] = m;
@@ -95,24 +99,28 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
 
 // One wavefront per batch entry: tile_list[b] = ascending indices of tiles whose key mask is not empty.
 __global__ void __launch_bounds__(64) tile_compact_kernel(const uint64_t* tile_mask, int* tile_list,
-                                                          int* tile_count, int nKT) {
+                                                          int* tile_count, int* tile_count_a, int nKT, int nTA) {
     const int b = blockIdx.x, lane = threadIdx.x;
     const uint64_t* m = tile_mask + (size_t)b * nKT;
     int* out = tile_list + (size_t)b * nKT;
-    int count = 0;
+    int count = 0, count_a = 0;
     for (int base = 0; base < nKT; base += 64) {
         const int t = base + lane;
         const bool keep = t < nKT && m[t] != 0ull;
         const uint64_t votes = __ballot(keep);
         if (keep) out[count + __popcll(votes & ((1ull << lane) - 1ull))] = t;
         count += __popcll(votes);
+        count_a += __popcll(__ballot(keep && t < nTA));
     }
-    if (lane == 0) tile_count[b] = count;
+    if (lane == 0) {
+        tile_count[b] = count;
+        if (tile_count_a) tile_count_a[b] = count_a;
+    }
 }
 
 hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(tile_compact_kernel, dim3(a.B), dim3(64), 0, s, a.tile_mask, a.tile_list, a.tile_count,
-                       a.nKT);
+                       a.tile_count_a, a.nKT, a.nTA);
     return hipGetLastError();
 }
 

@@ -84,3 +84,53 @@ def test_full_size_cross_sampled_rows():
     del out
     out = run_cross(q, k, v, valid, out_dtype=torch.float32)
     compare(to_f64(out[:, torch.from_numpy(rows).cuda()]), ref, what="cross_14b f32 out")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("n_text,n_image", [(200, 57), (128, 64), (7, 300), (512, 257)])
+def test_decoupled_cross_attention(D, n_text, n_image):
+    """Two softmaxes (text keys, image keys) added: splits on and off tile boundaries, padded text,
+    one request whose text is fully masked, one whose image part is fully masked."""
+    import torch
+
+    cfg = dict(B=4, Lq=300, n_text=n_text, n_image=n_image, H=2, D=D, dtype="bf16", min_text=1, seed=900 + D + n_text)
+    q, k, v, valid, text_len = wl.cross_attn_inputs(cfg)
+    valid[2, :n_text] = 0          # request 2: only the image sequence attends
+    valid[3, n_text:] = 0          # request 3: only the text sequence attends
+    ref = oracle.cross_attn_decoupled(q, k, v, n_text, valid)
+    for flags in (0, B.DIT_FLAG_QK_F16 | B.DIT_FLAG_PV_BF16):
+        out = run_cross(q, k, v, valid, out_dtype=torch.float32, split=n_text, flags=flags)
+        compare(to_f64(out), ref, what="decoupled D=%d split=%d flags=%d" % (D, n_text, flags))
+    out = run_cross(q, k, v, valid, split=n_text)
+    compare(to_f64(out), ref, bf16_out=True, what="decoupled D=%d split=%d bf16 out" % (D, n_text))
+    # no mask at all, and a split at the end (= joint softmax)
+    ref2 = oracle.cross_attn_decoupled(q, k, v, n_text, None)
+    compare(to_f64(run_cross(q, k, v, None, out_dtype=torch.float32, split=n_text)), ref2, what="decoupled no mask")
+    ref3 = oracle.cross_attn(q, k, v, valid)
+    compare(to_f64(run_cross(q, k, v, valid, out_dtype=torch.float32, split=n_text + n_image)), ref3,
+            what="split at Lk is the joint softmax")
+
+
+def test_decoupled_rejects_lse():
+    import torch
+
+    cfg = dict(B=1, Lq=64, n_text=64, n_image=64, H=1, D=128, dtype="bf16", min_text=1, seed=5)
+    q, k, v, valid, _ = wl.cross_attn_inputs(cfg)
+    with pytest.raises(B.DitError) as e:
+        run_cross(q, k, v, valid, split=64, want_lse=True)
+    assert e.value.status == B.DIT_ERR_UNSUPPORTED
+
+
+def test_full_size_decoupled_cross_sampled_rows():
+    """cross_14b shape with the text / image keys as two softmaxes (split at 512)."""
+    import torch
+
+    cfg = wl.CONFIGS["cross_14b"]
+    q, k, v, valid, text_len = wl.cross_attn_inputs(cfg)
+    rows = wl.sample_rows(cfg["Lq"], cfg["seed"], edge=64, n_random=128)
+    ref = oracle.cross_attn_decoupled(q, k, v, cfg["n_text"], valid, rows=rows)
+    out = run_cross(q, k, v, valid, out_dtype=torch.float32, split=cfg["n_text"])
+    compare(to_f64(out[:, torch.from_numpy(rows).cuda()]), ref, what="cross_14b decoupled f32 out")
+    del out
+    out = run_cross(q, k, v, valid, split=cfg["n_text"])
+    compare(to_f64(out[:, torch.from_numpy(rows).cuda()]), ref, bf16_out=True, what="cross_14b decoupled bf16 out")
