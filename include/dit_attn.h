@@ -157,6 +157,45 @@ dit_status dit_cross_attn_forward(const void *q, const void *k, const void *v,
                                   size_t workspace_bytes, void *stream);
 
 /*
+ * Self-attention of several requests in one call (batched serving: the Diffusion stage works on
+ * a batch of Tasks whose videos differ in resolution and length, Sec. 4.4 "TaskWorker").
+ * Request i has its own latent grid grids[i] = (T, Hg, Wg) and L_i = T*Hg*Wg tokens; the requests
+ * are packed back to back along the token axis, request i occupying rows
+ * [sum_{j<i} L_j, sum_{j<=i} L_j) of q, k, v and out, each addressed as
+ * base + n*stride.token + h*stride.head + c (stride.batch is ignored).  A token attends to the
+ * tokens of its own request only; positions, rotation and softmax are those of dit_attn_forward
+ * applied per request, with one origin, RoPE split, base and scale for all.
+ * `grids` is a HOST array of n_requests entries, read during the call only.  At most
+ * DIT_MAX_REQUESTS requests and 2^24 tokens in total (DIT_ERR_UNSUPPORTED beyond).
+ * Flags: QK_*, PV_*, BIG_WORKGROUP / SMALL_WORKGROUP; KV_FUSED, WIDE_QTILE and SIMPLE_SCHEDULE are
+ * not available (DIT_ERR_UNSUPPORTED).
+ * lse (nullable): fp32 [H, total tokens] dense.
+ */
+#define DIT_MAX_REQUESTS 64
+
+typedef struct {
+    int32_t T, Hg, Wg;
+} dit_grid;
+
+typedef struct {
+    int32_t n_requests, H, D;
+    const dit_grid *grids; /* host pointer */
+    int32_t t0, h0, w0;    /* position origin of every request */
+    int32_t d_t, d_h, d_w; /* RoPE split */
+    float rope_base;
+    float scale;           /* <= 0 selects 1/sqrt(D) */
+    int32_t in_dtype, out_dtype;
+    uint32_t flags;
+    dit_strides sq, sk, sv, so;
+} dit_varlen_attn_params;
+
+size_t dit_attn_varlen_workspace_bytes(const dit_varlen_attn_params *p);
+
+dit_status dit_attn_varlen_forward(const void *q, const void *k, const void *v, void *out,
+                                   float *lse, const dit_varlen_attn_params *p, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
  * Timing hook for benchmarks and profilers (not part of the attention definition): while
  * both handles are non-NULL, every forward call made by the calling thread records the
  * hipEvent_t `before` on the stream just before the attention kernel and `after` just after

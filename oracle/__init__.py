@@ -7,6 +7,7 @@ from .dit_oracle import (  # noqa: F401
     build,
     cross_attn,
     cross_attn_decoupled,
+    self_attn_packed,
     num_threads,
     rope3d,
     self_attn,

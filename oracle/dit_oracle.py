@@ -111,6 +111,30 @@ def self_attn(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, scale=0.0, r
     return res[0] if len(res) == 1 else res
 
 
+def self_attn_packed(q, k, v, grids, split, origin=(0, 0, 0), base=10000.0, scale=0.0, want_lse=False):
+    """Self-attention of several requests packed along the token axis: q, k, v [sum L_i, H, D],
+    request i on its own grid grids[i] = (T, Hg, Wg) with L_i = T*Hg*Wg tokens.  Requests do not
+    see each other, so this is the definition written out: one self_attn call per request on its
+    rows.  Returns out [sum L_i, H, D] float64 (and lse [H, sum L_i])."""
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    N, H, D = q.shape
+    assert sum(int(np.prod(g)) for g in grids) == N, "grids must add up to the packed token count"
+    out = np.empty((N, H, D), dtype=np.float64)
+    lse = np.empty((H, N), dtype=np.float64) if want_lse else None
+    n0 = 0
+    for g in grids:
+        L = int(np.prod(g))
+        sl = slice(n0, n0 + L)
+        res = self_attn(q[None, sl], k[None, sl], v[None, sl], g, split, origin=origin, base=base, scale=scale,
+                        want_lse=want_lse)
+        if want_lse:
+            out[sl], lse[:, sl] = res[0][0], res[1][0]
+        else:
+            out[sl] = res[0]
+        n0 += L
+    return (out, lse) if want_lse else out
+
+
 def cross_attn(q, k, v, kv_valid=None, scale=0.0, rows=None, want_lse=False, probs_of=None):
     """Cross-attention, joint softmax over Lk keys with a key-padding mask.
 

@@ -38,6 +38,8 @@ EXPORTS = (
     "dit_attn_forward",
     "dit_cross_attn_workspace_bytes",
     "dit_cross_attn_forward",
+    "dit_attn_varlen_workspace_bytes",
+    "dit_attn_varlen_forward",
     "dit_attn_set_timing_events",
     "dit_strerror",
     "dit_last_hip_error",
@@ -73,6 +75,26 @@ class dit_cross_attn_params(ctypes.Structure):
     ]
 
 
+DIT_MAX_REQUESTS = 64
+
+
+class dit_grid(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("Hg", ctypes.c_int32), ("Wg", ctypes.c_int32)]
+
+
+class dit_varlen_attn_params(ctypes.Structure):
+    _fields_ = [
+        ("n_requests", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("grids", ctypes.POINTER(dit_grid)),
+        ("t0", ctypes.c_int32), ("h0", ctypes.c_int32), ("w0", ctypes.c_int32),
+        ("d_t", ctypes.c_int32), ("d_h", ctypes.c_int32), ("d_w", ctypes.c_int32),
+        ("rope_base", ctypes.c_float), ("scale", ctypes.c_float),
+        ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("flags", ctypes.c_uint32),
+        ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
+    ]
+
+
 class DitError(RuntimeError):
     def __init__(self, status, what):
         self.status = int(status)
@@ -104,6 +126,11 @@ def lib():
         L.dit_cross_attn_forward.restype = ctypes.c_int
         L.dit_cross_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(dit_cross_attn_params),
                                              vp, ctypes.c_size_t, vp]
+        L.dit_attn_varlen_workspace_bytes.restype = ctypes.c_size_t
+        L.dit_attn_varlen_workspace_bytes.argtypes = [ctypes.POINTER(dit_varlen_attn_params)]
+        L.dit_attn_varlen_forward.restype = ctypes.c_int
+        L.dit_attn_varlen_forward.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(dit_varlen_attn_params), vp,
+                                              ctypes.c_size_t, vp]
         L.dit_attn_set_timing_events.restype = None
         L.dit_attn_set_timing_events.argtypes = [vp, vp]
         L.dit_strerror.restype = ctypes.c_char_p
@@ -167,6 +194,29 @@ def cross_attn_params(q, k, v, out, scale=0.0, flags=0, split=0):
     B, Lq, H, D = q.shape
     return dit_cross_attn_params(B, H, D, Lq, k.shape[1], scale, _dtype_code(q), _dtype_code(out), flags, split,
                                  _strides(q), _strides(k), _strides(v), _strides(out))
+
+
+def _strides3(t):
+    """[N, H, D] tensor (packed requests) -> dit_strides with batch stride 0."""
+    if t.dim() != 3 or t.stride(2) != 1:
+        raise ValueError("expected a [tokens, H, D] tensor with contiguous channels")
+    return dit_strides(0, t.stride(0), t.stride(1))
+
+
+def varlen_attn_params(q, k, v, out, grids, split, origin=(0, 0, 0), rope_base=10000.0, scale=0.0, flags=0):
+    """grids: sequence of (T, Hg, Wg).  The returned struct keeps the host grid array alive."""
+    N, H, D = q.shape
+    arr = (dit_grid * max(len(grids), 1))(*[dit_grid(*g) for g in grids])
+    p = dit_varlen_attn_params(
+        len(grids), H, D, ctypes.cast(arr, ctypes.POINTER(dit_grid)), origin[0], origin[1], origin[2],
+        split[0], split[1], split[2], rope_base, scale, _dtype_code(q), _dtype_code(out), flags,
+        _strides3(q), _strides3(k), _strides3(v), _strides3(out))
+    p._grids_keepalive = arr
+    return p
+
+
+def dit_attn_varlen_workspace_bytes(params):
+    return int(lib().dit_attn_varlen_workspace_bytes(ctypes.byref(params)))
 
 
 def dit_attn_workspace_bytes(params):
@@ -239,4 +289,32 @@ def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0
                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if st != DIT_OK:
         raise DitError(st, "dit_cross_attn_forward")
+    return (out, lse) if lse is not None else out
+
+
+def dit_attn_varlen_forward(q, k, v, grids, split, out=None, lse=None, origin=(0, 0, 0), rope_base=10000.0,
+                            scale=0.0, flags=0, out_dtype=None, workspace=None, stream=None, want_lse=False):
+    """Self-attention of several requests packed along the token axis: q, k, v [sum L_i, H, D],
+    grids = [(T, Hg, Wg), ...] with L_i = T*Hg*Wg.  Returns out (and lse [H, sum L_i] if asked)."""
+    import torch
+
+    if not q.is_cuda:
+        raise ValueError("dit_attn_varlen_forward needs device tensors")
+    N, H, D = q.shape
+    if sum(g[0] * g[1] * g[2] for g in grids) != N:
+        raise ValueError("the grids do not add up to the token count of q")
+    if out is None:
+        out = torch.empty((N, H, D), dtype=out_dtype or q.dtype, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((H, N), dtype=torch.float32, device=q.device)
+    p = varlen_attn_params(q, k, v, out, grids, split, origin, rope_base, scale, flags)
+    need = dit_attn_varlen_workspace_bytes(p)
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    st = lib().dit_attn_varlen_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                       lse.data_ptr() if lse is not None else None, ctypes.byref(p),
+                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                       _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_attn_varlen_forward")
     return (out, lse) if lse is not None else out

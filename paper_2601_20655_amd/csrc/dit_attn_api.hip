@@ -38,6 +38,8 @@ hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, b
 
 namespace {
 
+static_assert(DIT_MAX_REQUESTS == dit::kMaxRequests, "request limit of the ABI and of the kernel table");
+
 thread_local char g_hip_error[256] = "";
 thread_local hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
 
@@ -158,6 +160,98 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
     size_t tiles = pl->fl.fused ? 0 : (size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D);
     pl->total = pl->tiles_off + round_up(tiles, kAlign);
     if (pl->total == 0) pl->total = kAlign;
+    return DIT_OK;
+}
+
+struct VarlenPlan {
+    Flags fl;
+    dit::VarlenTable vt;
+    int maxT, maxHg, maxWg;
+    int table_entries;
+    size_t tab_off, tiles_off, total;
+};
+
+dit_status plan_varlen(const dit_varlen_attn_params* p, VarlenPlan* pl) {
+    if (!p || !p->grids) return DIT_ERR_INVALID_ARG;
+    if (p->n_requests < 1 || p->H < 1 || p->D < 1) return DIT_ERR_INVALID_ARG;
+    if (p->n_requests > DIT_MAX_REQUESTS) return DIT_ERR_UNSUPPORTED;
+    if (p->D != 64 && p->D != 128) return DIT_ERR_UNSUPPORTED;
+    if (p->d_t < 0 || p->d_h < 0 || p->d_w < 0 || ((p->d_t | p->d_h | p->d_w) & 1) ||
+        p->d_t + p->d_h + p->d_w != p->D)
+        return DIT_ERR_INVALID_ARG;
+    if (!(p->rope_base > 0.f) || !isfinite(p->rope_base) || !isfinite(p->scale)) return DIT_ERR_INVALID_ARG;
+    if (!dtype_ok(p->in_dtype) || !dtype_ok(p->out_dtype)) return DIT_ERR_INVALID_ARG;
+    dit_status st = parse_flags(p->flags, &pl->fl);
+    if (st != DIT_OK) return st;
+    // only the pipelined kernel with pre-packed tiles and 32 rows per wavefront has this form
+    if (pl->fl.fused || pl->fl.simple || pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
+    if (p->H > (1 << 16)) return DIT_ERR_UNSUPPORTED;
+    if (!strides_ok(p->sq, 1, p->H, p->D) || !strides_ok(p->sk, 1, p->H, p->D) ||
+        !strides_ok(p->sv, 1, p->H, p->D) || !strides_ok(p->so, 1, p->H, p->D))
+        return DIT_ERR_INVALID_ARG;
+
+    const int n = p->n_requests;
+    int64_t Ls[DIT_MAX_REQUESTS], tok0[DIT_MAX_REQUESTS];
+    int order[DIT_MAX_REQUESTS];
+    int64_t total = 0, big_blocks = 0;
+    pl->maxT = pl->maxHg = pl->maxWg = 0;
+    for (int i = 0; i < n; ++i) {
+        const dit_grid& g = p->grids[i];
+        if (g.T < 1 || g.Hg < 1 || g.Wg < 1) return DIT_ERR_INVALID_ARG;
+        Ls[i] = (int64_t)g.T * g.Hg * g.Wg;
+        if (Ls[i] > (1 << 24)) return DIT_ERR_UNSUPPORTED;
+        tok0[i] = total;
+        total += Ls[i];
+        big_blocks += (Ls[i] + 255) / 256 * p->H;
+        if (g.T > pl->maxT) pl->maxT = g.T;
+        if (g.Hg > pl->maxHg) pl->maxHg = g.Hg;
+        if (g.Wg > pl->maxWg) pl->maxWg = g.Wg;
+        order[i] = i;
+    }
+    if (total > (1 << 24)) return DIT_ERR_UNSUPPORTED;  // token indices are 32-bit with room for tile padding
+    if (pl->fl.nw == 0) pl->fl.nw = big_blocks >= 512 ? 8 : 4;
+    const int bq = 32 * pl->fl.nw;
+    // longest request first (stable, so equal lengths keep the caller's order)
+    for (int i = 1; i < n; ++i) {
+        const int o = order[i];
+        int j = i;
+        for (; j > 0 && Ls[order[j - 1]] < Ls[o]; --j) order[j] = order[j - 1];
+        order[j] = o;
+    }
+    dit::VarlenTable& vt = pl->vt;
+    memset(&vt, 0, sizeof(vt));
+    vt.n = n;
+    vt.total_tokens = (int)total;
+    int tile0 = 0;
+    int64_t queue[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int r = 0; r < n; ++r) {
+        const int i = order[r];
+        dit::ReqDesc& d = vt.r[r];
+        d.tok0 = (int)tok0[i];
+        d.L = (int)Ls[i];
+        d.Hg = p->grids[i].Hg;
+        d.Wg = p->grids[i].Wg;
+        d.nKT = (int)((Ls[i] + dit::kBK - 1) / dit::kBK);
+        d.nQT = (int)((Ls[i] + bq - 1) / bq);
+        d.tile0 = tile0;
+        tile0 += d.nKT;
+        // the kernel's rule: XCD x takes heads h with (r*H + h) % 8 == x
+        for (int x = 0; x < 8; ++x) {
+            const int h_first = (x - r * p->H) & 7;
+            const int heads = h_first < p->H ? (p->H - h_first + 7) >> 3 : 0;
+            queue[x] += (int64_t)heads * d.nQT;
+        }
+    }
+    vt.total_tiles = tile0;
+    int64_t qmax = 0;
+    for (int x = 0; x < 8; ++x) qmax = queue[x] > qmax ? queue[x] : qmax;
+    if (8 * qmax > 0x7fffffffLL || (int64_t)tile0 * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
+    vt.queue_len = (int)qmax;
+
+    pl->table_entries = pl->maxT * (p->d_t / 2) + pl->maxHg * (p->d_h / 2) + pl->maxWg * (p->d_w / 2);
+    pl->tab_off = 0;
+    pl->tiles_off = round_up((size_t)pl->table_entries * sizeof(float2), kAlign);
+    pl->total = pl->tiles_off + round_up((size_t)tile0 * p->H * dit::tile_bytes(p->D), kAlign);
     return DIT_OK;
 }
 
@@ -346,6 +440,80 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     return run_attn(aa, p->D, pl.fl, false, s);
 }
 
+size_t dit_attn_varlen_workspace_bytes(const dit_varlen_attn_params* p) {
+    VarlenPlan pl;
+    return plan_varlen(p, &pl) == DIT_OK ? pl.total : 0;
+}
+
+dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, void* out, float* lse,
+                                   const dit_varlen_attn_params* p, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    VarlenPlan pl;
+    dit_status st = plan_varlen(p, &pl);
+    if (st != DIT_OK) return st;
+    if (!q || !k || !v || !out) return DIT_ERR_INVALID_ARG;
+    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(k, p->sk, p->in_dtype) ||
+        !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
+        return DIT_ERR_ALIGNMENT;
+    if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
+        return DIT_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+
+    // one table for all requests, long enough for the largest extent on each axis
+    dit::RopeGeom rg;
+    rg.hd[0] = p->d_t / 2; rg.hd[1] = p->d_h / 2; rg.hd[2] = p->d_w / 2;
+    rg.off[0] = 0; rg.off[1] = pl.maxT * rg.hd[0]; rg.off[2] = rg.off[1] + pl.maxHg * rg.hd[1];
+    rg.Hg = pl.maxHg; rg.Wg = pl.maxWg;  // replaced per request inside the kernels
+
+    dit::TableArgs ta;
+    ta.tab = reinterpret_cast<float2*>(ws + pl.tab_off);
+    ta.n[0] = pl.maxT; ta.n[1] = pl.maxHg; ta.n[2] = pl.maxWg;
+    ta.origin[0] = p->t0; ta.origin[1] = p->h0; ta.origin[2] = p->w0;
+    ta.rg = rg;
+    ta.base = (double)p->rope_base;
+    ta.total = pl.table_entries;
+    hipError_t e = dit::launch_rope_table(ta, s);
+    if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+
+    const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
+
+    dit::PackArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    pa.k = k; pa.v = v;
+    pa.tiles = ws + pl.tiles_off;
+    pa.tab = ta.tab;
+    pa.B = 1; pa.H = p->H; pa.Lk = pl.vt.total_tokens; pa.nKT = pl.vt.total_tiles;
+    pa.in_f32 = p->in_dtype == DIT_F32;
+    pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
+    pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
+    pa.rg = rg;
+    e = dit::launch_prepack_varlen(pa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
+    if (e != hipSuccess) return hip_fail(e, "kv_prepack_varlen_kernel");
+
+    dit::AttnArgs aa;
+    memset(&aa, 0, sizeof(aa));
+    aa.q = q; aa.out = out; aa.lse = lse;
+    aa.tiles = pa.tiles;
+    aa.tab = ta.tab;
+    aa.B = 1; aa.H = p->H; aa.Lq = pl.vt.total_tokens; aa.Lk = pl.vt.total_tokens;
+    aa.nKT = pl.vt.total_tiles; aa.nQT = 0;
+    aa.in_f32 = p->in_dtype == DIT_F32; aa.out_f32 = p->out_dtype == DIT_F32;
+    aa.sq_t = p->sq.token; aa.sq_h = p->sq.head;
+    aa.so_t = p->so.token; aa.so_h = p->so.head;
+    aa.rg = rg;
+    aa.qscale = scale * dit::kLog2e;
+
+    const bool timed = g_ev_before && g_ev_after;
+    if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    e = dit::launch_attn_pipe_varlen(aa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, pl.fl.nw, s);
+    if (e != hipSuccess) return hip_fail(e, "attention kernel");
+    if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    return DIT_OK;
+}
+
 void dit_attn_set_timing_events(void* before, void* after) {
     g_ev_before = static_cast<hipEvent_t>(before);
     g_ev_after = static_cast<hipEvent_t>(after);
@@ -365,6 +533,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 104; }
+int dit_attn_version(void) { return 105; }
 
 }  // extern "C"

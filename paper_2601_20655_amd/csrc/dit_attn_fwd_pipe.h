@@ -64,10 +64,21 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     return r;
 }
 
+// The sequence one workgroup works on: which query tile of which (sequence, head), and where that
+// sequence's rows and tiles start.
+struct PipeView {
+    int qt, h, b;          // query tile, head, batch entry (b indexes the tile lists, LISTED only)
+    int Lq, Lk, nKT;
+    const uint8_t* tiles;  // tile images of this (sequence, head)
+    int64_t q_off, o_off;  // element offsets of row 0 of this (sequence, head) in q / out
+    int64_t lse_off;       // index of row 0 in lse
+    int Hg, Wg;            // latent grid of this sequence
+};
+
 // NW = wavefronts per workgroup (4 or 8); the workgroup owns NW*QB*32 query rows that share every
 // K/V tile in LDS.
 template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
-__global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView& pv) {
     using G = TileGeom<D>;
     constexpr int NKS = D / 16;
     constexpr int NDB = D / 32;
@@ -84,17 +95,10 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-
-    int logical;
-    {
-        const int nblk = gridDim.x, bid = blockIdx.x;
-        const int xcd = bid & 7, idx = bid >> 3;
-        const int chunk = nblk >> 3, rem = nblk & 7;
-        logical = xcd * chunk + (xcd < rem ? xcd : rem) + idx;
-    }
-    const int qt = logical % a.nQT;
-    const int bh = logical / a.nQT;
-    const int b = bh / a.H, h = bh - b * a.H;
+    const int qt = pv.qt, b = pv.b;
+    RopeGeom rg = a.rg;
+    rg.Hg = pv.Hg;
+    rg.Wg = pv.Wg;
 
     u32x4 Qf[QB][NKS];  // filled after the first tiles have been requested
     int qrow[QB];
@@ -102,14 +106,14 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     // ---- tile streaming.  A tile part is PART_KIB pieces of 1 KiB (64 lanes x 16 bytes).  Wavefront
     // w moves pieces w, w+NW, ... of both parts; the two odd pieces of the K part go to wavefronts
     // 0 and 1, those of the V part to wavefronts 2 and 3.
-    const uint8_t* const tiles = a.tiles + (size_t)bh * a.nKT * G::TILE_BYTES;  // wavefront-uniform
+    const uint8_t* const tiles = pv.tiles;  // wavefront-uniform
     const uint32_t lane_off = lane * 16;
     // The loop runs over "steps"; step j works on tile tile_of(j).  Without a list that is tile j.
-    const int* const tlist = LISTED ? a.tile_list + (size_t)b * a.nKT : nullptr;
-    const uint64_t* const tmask = LISTED ? a.tile_mask + (size_t)b * a.nKT : nullptr;
-    const int n_steps = LISTED ? a.tile_count[b] : a.nKT;
+    const int* const tlist = LISTED ? a.tile_list + (size_t)b * pv.nKT : nullptr;
+    const uint64_t* const tmask = LISTED ? a.tile_mask + (size_t)b * pv.nKT : nullptr;
+    const int n_steps = LISTED ? a.tile_count[b] : pv.nKT;
     const int last = n_steps - 1;
-    const int tail = a.Lk - (a.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
+    const int tail = pv.Lk - (pv.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
     auto tile_of = [&](int j) -> int {
         j = j < last ? j : last;  // past the end: the last tile again (fetched into a buffer nobody reads)
         if constexpr (LISTED) return tlist[j];
@@ -402,16 +406,16 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
-        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
-        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        const int qr = qrow[qb] < pv.Lq ? qrow[qb] : pv.Lq - 1;
+        const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
         int pt = 0, ph = 0, pw = 0;
-        if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
+        if (a.tab) token_pos(qr, rg, pt, ph, pw);
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             const int c = 2 * ks + half;
             float x[8];
             load8(a.q, base + 8 * c, a.in_f32, x);
-            if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
+            if (a.tab) rope8(x, c, rg, a.tab, pt, ph, pw);
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
             Qf[qb][ks] = pack8<QK_OP>(x);
@@ -450,8 +454,8 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     for (int qb = 0; qb < QB; ++qb) {
         const float l = l_run[qb] + __shfl_xor(l_run[qb], 32);
         const float inv = l > 0.f ? 1.0f / l : 0.f;
-        if (qrow[qb] < a.Lq) {
-            const int64_t obase = (int64_t)b * a.so_b + (int64_t)qrow[qb] * a.so_t + (int64_t)h * a.so_h;
+        if (qrow[qb] < pv.Lq) {
+            const int64_t obase = pv.o_off + (int64_t)qrow[qb] * a.so_t;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -469,10 +473,74 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
                 }
             if (a.lse && half == 0) {
                 const float v = l > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
-                a.lse[((int64_t)b * a.H + h) * a.Lq + qrow[qb]] = v;
+                a.lse[pv.lse_off + qrow[qb]] = v;
             }
         }
     }
+}
+
+// blockIdx -> logical workgroup such that each XCD (workgroups are dealt to the 8 XCDs round-robin)
+// works through one contiguous range of logical workgroups: neighbours share K/V tiles in its L2.
+__device__ __forceinline__ int xcd_contiguous_block() {
+    const int nblk = gridDim.x, bid = blockIdx.x;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int chunk = nblk >> 3, rem = nblk & 7;
+    return xcd * chunk + (xcd < rem ? xcd : rem) + idx;
+}
+
+// One sequence per batch entry, all of the same length.
+template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
+__global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
+    const int logical = xcd_contiguous_block();
+    const int bh = logical / a.nQT;
+    PipeView pv;
+    pv.qt = logical % a.nQT;
+    pv.b = bh / a.H;
+    pv.h = bh - pv.b * a.H;
+    pv.Lq = a.Lq;
+    pv.Lk = a.Lk;
+    pv.nKT = a.nKT;
+    pv.tiles = a.tiles + (size_t)bh * a.nKT * TileGeom<D>::TILE_BYTES;
+    pv.q_off = (int64_t)pv.b * a.sq_b + (int64_t)pv.h * a.sq_h;
+    pv.o_off = (int64_t)pv.b * a.so_b + (int64_t)pv.h * a.so_h;
+    pv.lse_off = ((int64_t)pv.b * a.H + pv.h) * a.Lq;
+    pv.Hg = a.rg.Hg;
+    pv.Wg = a.rg.Wg;
+    attn_pipe_body<D, QB, QK_OP, PV_OP, NW, LISTED>(a, pv);
+}
+
+// Packed requests of different lengths (self-attention, no lists).  XCD x owns the (request, head)
+// pairs with (table index * H + head) % 8 == x and walks them in table order, so every XCD gets
+// a near-equal share of every request and meets the longest ones first.  Workgroups past the end
+// of their XCD's queue leave at once.
+template <int D, int QK_OP, int PV_OP, int NW>
+__global__ void __launch_bounds__(64 * NW, 2) attn_fwd_pipe_varlen_kernel(const AttnArgs a, const VarlenTable vt) {
+    const int xcd = blockIdx.x & 7;
+    int idx = blockIdx.x >> 3;
+    int r = 0, h_first = 0;
+    for (; r < vt.n; ++r) {
+        h_first = (xcd - r * a.H) & 7;
+        const int heads = h_first < a.H ? (a.H - h_first + 7) >> 3 : 0;
+        const int nblk = heads * vt.r[r].nQT;
+        if (idx < nblk) break;
+        idx -= nblk;
+    }
+    if (r == vt.n) return;  // uniform over the workgroup, before any barrier
+    const ReqDesc& rq = vt.r[r];
+    PipeView pv;
+    pv.qt = idx % rq.nQT;
+    pv.h = h_first + 8 * (idx / rq.nQT);
+    pv.b = 0;
+    pv.Lq = rq.L;
+    pv.Lk = rq.L;
+    pv.nKT = rq.nKT;
+    pv.tiles = a.tiles + ((size_t)rq.tile0 * a.H + (size_t)pv.h * rq.nKT) * TileGeom<D>::TILE_BYTES;
+    pv.q_off = (int64_t)rq.tok0 * a.sq_t + (int64_t)pv.h * a.sq_h;
+    pv.o_off = (int64_t)rq.tok0 * a.so_t + (int64_t)pv.h * a.so_h;
+    pv.lse_off = (int64_t)pv.h * vt.total_tokens + rq.tok0;
+    pv.Hg = rq.Hg;
+    pv.Wg = rq.Wg;
+    attn_pipe_body<D, 1, QK_OP, PV_OP, NW, false>(a, pv);
 }
 
 template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
@@ -484,6 +552,17 @@ hipError_t launch_attn_pipe_inst(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((int64_t)a.nQT * a.B * a.H));
     hipLaunchKernelGGL(kern, grid, dim3(64 * NW), smem, s, a);
+    return hipGetLastError();
+}
+
+template <int D, int QK_OP, int PV_OP, int NW>
+hipError_t launch_attn_pipe_varlen_inst(const AttnArgs& a, const VarlenTable& vt, hipStream_t s) {
+    auto kern = attn_fwd_pipe_varlen_kernel<D, QK_OP, PV_OP, NW>;
+    constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * vt.queue_len)), dim3(64 * NW), smem, s, a, vt);
     return hipGetLastError();
 }
 

@@ -84,7 +84,31 @@ struct AttnArgs {
     float qscale;  // softmax scale * log2(e), folded into q'
 };
 
+// Several requests with their own latent grids packed back to back along the token axis
+// (batched serving): one descriptor per request, passed to the kernels by value.
+constexpr int kMaxRequests = 64;
+struct ReqDesc {
+    int tok0;    // first token of the request in the packed tensors
+    int L;       // its tokens = T * Hg * Wg
+    int Hg, Wg;  // grid height and width (token -> position decode)
+    int nKT;     // key tiles
+    int nQT;     // query tiles
+    int tile0;   // key tiles of all earlier table entries (per head)
+    int pad_;
+};
+// Table order is the order workgroups are handed out in (longest request first), not token order.
+struct VarlenTable {
+    int n;             // requests
+    int total_tokens;  // sum of L
+    int total_tiles;   // sum of nKT
+    int queue_len;     // workgroups per XCD queue; the grid is 8 * queue_len
+    ReqDesc r[kMaxRequests];
+};
+
 hipError_t launch_rope_table(const TableArgs& a, hipStream_t s);
+hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, hipStream_t s);
+hipError_t launch_attn_pipe_varlen(const AttnArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, int nw,
+                                   hipStream_t s);
 hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
 // after launch_prepack: compact the non-empty tiles of every batch entry into tile_list / tile_count
 hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s);

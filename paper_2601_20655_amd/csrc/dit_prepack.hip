@@ -29,42 +29,41 @@ hipError_t launch_rope_table(const TableArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// One workgroup per (tile, head, batch).
+// What one workgroup packs: 64 keys of one (batch or request, head).
+struct PackTile {
+    uint8_t* dst;        // tile image
+    int64_t k_off, v_off;  // element offset of key 0 of this sequence for this head
+    int key0, key_end;   // keys [key0, key0 + 64) clipped to key_end
+    RopeGeom rg;         // with this sequence's grid
+};
+
 template <int D, int QK_OP, int PV_OP>
-__global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) {
+__device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, uint16_t* vs) {
     using G = TileGeom<D>;
     constexpr int CPR = D / 8;
     constexpr int ROWS_PER_PASS = kThreads / CPR;
     constexpr int NI = kBK / ROWS_PER_PASS;
     constexpr int VS = D + 2;  // padded row of the transposition buffer, in 16-bit elements
-    __shared__ __attribute__((aligned(16))) uint16_t vs[kBK * VS];
-
     const int tid = threadIdx.x;
-    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    uint8_t* dst = a.tiles + ((size_t)(b * a.H + h) * a.nKT + j) * G::TILE_BYTES;
     const int c = tid % CPR;
-    // keys of this tile: [key0, key0 + 64) clipped to key_end (two key groups when split > 0)
-    const bool second = a.split > 0 && j >= a.nTA;
-    const int key0 = second ? a.split + (j - a.nTA) * kBK : j * kBK;
-    const int key_end = (a.split > 0 && !second) ? a.split : a.Lk;
 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int r = tid / CPR + i * ROWS_PER_PASS;
-        const int key = key0 + r;
+        const int key = t.key0 + r;
         float xk[8], xv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) xk[e] = xv[e] = 0.f;
-        if (key < key_end) {
-            load8(a.k, (int64_t)b * a.sk_b + (int64_t)key * a.sk_t + (int64_t)h * a.sk_h + 8 * c, a.in_f32, xk);
-            load8(a.v, (int64_t)b * a.sv_b + (int64_t)key * a.sv_t + (int64_t)h * a.sv_h + 8 * c, a.in_f32, xv);
+        if (key < t.key_end) {
+            load8(a.k, t.k_off + (int64_t)key * a.sk_t + 8 * c, a.in_f32, xk);
+            load8(a.v, t.v_off + (int64_t)key * a.sv_t + 8 * c, a.in_f32, xv);
             if (a.tab) {
                 int pt, ph, pw;
-                token_pos(key, a.rg, pt, ph, pw);
-                rope8(xk, c, a.rg, a.tab, pt, ph, pw);
+                token_pos(key, t.rg, pt, ph, pw);
+                rope8(xk, c, t.rg, a.tab, pt, ph, pw);
             }
         }
-        *reinterpret_cast<u32x4*>(dst + r * G::KROW + c * 16) = pack8<QK_OP>(xk);
+        *reinterpret_cast<u32x4*>(t.dst + r * G::KROW + c * 16) = pack8<QK_OP>(xk);
         const u32x4 pv = pack8<PV_OP>(xv);
         uint32_t* row = reinterpret_cast<uint32_t*>(vs + r * VS + 8 * c);
         row[0] = pv.x; row[1] = pv.y; row[2] = pv.z; row[3] = pv.w;
@@ -85,16 +84,57 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
                 const int ka = k0 + 8 * g + 2 * e2;
                 w[2 * g + e2] = (uint32_t)vs[ka * VS + d] | ((uint32_t)vs[(ka + 1) * VS + d] << 16);
             }
-        *reinterpret_cast<u32x4*>(dst + G::K_BYTES + d * G::VROW + kc * 16) = mk4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<u32x4*>(t.dst + G::K_BYTES + d * G::VROW + kc * 16) = mk4(w[0], w[1], w[2], w[3]);
     }
+}
+
+// One workgroup per (tile, head, batch).
+template <int D, int QK_OP, int PV_OP>
+__global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) {
+    using G = TileGeom<D>;
+    __shared__ __attribute__((aligned(16))) uint16_t vs[kBK * (D + 2)];
+    const int tid = threadIdx.x;
+    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    PackTile t;
+    t.dst = a.tiles + ((size_t)(b * a.H + h) * a.nKT + j) * G::TILE_BYTES;
+    t.k_off = (int64_t)b * a.sk_b + (int64_t)h * a.sk_h;
+    t.v_off = (int64_t)b * a.sv_b + (int64_t)h * a.sv_h;
+    // keys of this tile: [key0, key0 + 64) clipped to key_end (two key groups when split > 0)
+    const bool second = a.split > 0 && j >= a.nTA;
+    t.key0 = second ? a.split + (j - a.nTA) * kBK : j * kBK;
+    t.key_end = (a.split > 0 && !second) ? a.split : a.Lk;
+    t.rg = a.rg;
+    pack_tile<D, QK_OP, PV_OP>(a, t, vs);
 
     if (a.tile_mask && h == 0 && tid < 64) {
-        const int key = key0 + tid;
-        bool ok = key < key_end;
+        const int key = t.key0 + tid;
+        bool ok = key < t.key_end;
         if (ok && a.valid) ok = a.valid[(size_t)b * a.Lk + key] != 0;
         const uint64_t m = __ballot(ok);
         if (tid == 0) a.tile_mask[(size_t)b * a.nKT + j] = m;
     }
+}
+
+// Packed requests: one workgroup per (tile of any request, head).
+template <int D, int QK_OP, int PV_OP>
+__global__ void __launch_bounds__(kThreads) kv_prepack_varlen_kernel(const PackArgs a, const VarlenTable vt) {
+    using G = TileGeom<D>;
+    __shared__ __attribute__((aligned(16))) uint16_t vs[kBK * (D + 2)];
+    const int gj = blockIdx.x, h = blockIdx.y;
+    int r = 0;
+    while (r + 1 < vt.n && gj >= vt.r[r + 1].tile0) ++r;
+    const ReqDesc& q = vt.r[r];
+    const int j = gj - q.tile0;
+    PackTile t;
+    t.dst = a.tiles + ((size_t)q.tile0 * a.H + (size_t)h * q.nKT + j) * G::TILE_BYTES;
+    t.k_off = (int64_t)q.tok0 * a.sk_t + (int64_t)h * a.sk_h;
+    t.v_off = (int64_t)q.tok0 * a.sv_t + (int64_t)h * a.sv_h;
+    t.key0 = j * kBK;
+    t.key_end = q.L;
+    t.rg = a.rg;
+    t.rg.Hg = q.Hg;
+    t.rg.Wg = q.Wg;
+    pack_tile<D, QK_OP, PV_OP>(a, t, vs);
 }
 
 // One wavefront per batch entry: tile_list[b] = ascending indices of tiles whose key mask is not empty.
@@ -128,6 +168,25 @@ template <int D, int QK_OP, int PV_OP>
 static hipError_t launch_prepack_inst(const PackArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((kv_prepack_kernel<D, QK_OP, PV_OP>), dim3(a.nKT, a.H, a.B), dim3(kThreads), 0, s, a);
     return hipGetLastError();
+}
+
+hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, hipStream_t s) {
+#define DIT_PACKV_CASE(DD, QK, PV)                                                                        \
+    if (D == DD && qk_op == QK && pv_op == PV) {                                                           \
+        hipLaunchKernelGGL((kv_prepack_varlen_kernel<DD, QK, PV>), dim3(vt.total_tiles, a.H), dim3(kThreads), 0, \
+                           s, a, vt);                                                                      \
+        return hipGetLastError();                                                                          \
+    }
+    DIT_PACKV_CASE(128, OP_F16, OP_F16)
+    DIT_PACKV_CASE(128, OP_F16, OP_BF16)
+    DIT_PACKV_CASE(128, OP_BF16, OP_F16)
+    DIT_PACKV_CASE(128, OP_BF16, OP_BF16)
+    DIT_PACKV_CASE(64, OP_F16, OP_F16)
+    DIT_PACKV_CASE(64, OP_F16, OP_BF16)
+    DIT_PACKV_CASE(64, OP_BF16, OP_F16)
+    DIT_PACKV_CASE(64, OP_BF16, OP_BF16)
+#undef DIT_PACKV_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s) {

@@ -25,6 +25,16 @@ CONFIGS = {
     # mid-size shape for an all-rows comparison that spans several tiles and a ragged tail
     "mid": dict(kind="self", B=1, grid=(4, 30, 52), H=4, D=128, split=(44, 42, 42),
                 dtype="bf16", seed=20655 + 6),
+    # several requests of different grids packed along the token axis (batched serving)
+    "varlen_small": dict(kind="varlen", grids=((2, 5, 7), (3, 16, 20), (1, 1, 1), (4, 9, 13), (2, 16, 16),
+                                               (1, 8, 8)),
+                         H=4, D=128, split=(44, 42, 42), dtype="bf16", seed=20655 + 7),
+    "varlen_small_d64": dict(kind="varlen", grids=((3, 7, 9), (1, 3, 5), (5, 12, 11)),
+                             H=3, D=64, split=(22, 20, 22), dtype="f32", seed=20655 + 8),
+    # a mixed batch at 14B width: 720p and 480p clips of 81, 49 and 33 frames plus a still image
+    "varlen_14b": dict(kind="varlen", grids=((13, 30, 52), (21, 45, 80), (1, 45, 80), (21, 30, 52), (9, 45, 80),
+                                             (13, 30, 52), (21, 30, 52)),
+                       H=40, D=128, split=(44, 42, 42), dtype="bf16", seed=20655 + 9),
 }
 
 
@@ -59,6 +69,15 @@ def self_attn_inputs(cfg, seed=None, gain=1.0, dtype=None):
     seed = cfg["seed"] if seed is None else seed
     dtype = cfg["dtype"] if dtype is None else dtype
     return tuple(normal(shape, seed, s, dtype, gain if s < 2 else 1.0) for s in range(3))
+
+
+def varlen_attn_inputs(cfg, seed=None, dtype=None):
+    """q, k, v of shape [sum of T*Hg*Wg over cfg["grids"], H, D], requests back to back."""
+    n = sum(t * h * w for t, h, w in cfg["grids"])
+    shape = (n, cfg["H"], cfg["D"])
+    seed = cfg["seed"] if seed is None else seed
+    dtype = cfg["dtype"] if dtype is None else dtype
+    return tuple(normal(shape, seed, s, dtype) for s in range(3))
 
 
 def cross_attn_inputs(cfg, seed=None, dtype=None):

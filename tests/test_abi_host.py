@@ -137,6 +137,44 @@ def test_cross_attn_rejects_bad_arguments():
     assert B.dit_last_hip_error() == ""
 
 
+def varlen_params(grids=((2, 3, 4), (1, 5, 5)), H=2, D=128, split=(44, 42, 42), flags=0):
+    arr = (B.dit_grid * max(len(grids), 1))(*[B.dit_grid(*g) for g in grids])
+    s = B.dit_strides(0, H * D, D)
+    p = B.dit_varlen_attn_params(len(grids), H, D, ctypes.cast(arr, ctypes.POINTER(B.dit_grid)), 0, 0, 0,
+                                 split[0], split[1], split[2], 10000.0, 0.0, B.DIT_BF16, B.DIT_BF16, flags,
+                                 s, s, s, s)
+    p._keep = arr
+    return p
+
+
+def call_varlen(p, q=FAKE, ws=0x10000, ws_bytes=1 << 40):
+    return B.lib().dit_attn_varlen_forward(q, FAKE, FAKE, FAKE, None, ctypes.byref(p), ws, ws_bytes, None)
+
+
+def test_varlen_workspace_and_rejections():
+    tile = 36 * 1024
+    grids = ((2, 3, 4), (1, 5, 5), (3, 9, 9))  # 24, 25, 243 tokens -> 1 + 1 + 4 key tiles
+    p = varlen_params(grids, H=3)
+    table = 3 * 22 + 9 * 21 + 9 * 21  # longest extent per axis x pairs per axis
+    assert B.dit_attn_varlen_workspace_bytes(p) == up(table * 8) + up(6 * 3 * tile)
+    assert call_varlen(p, ws_bytes=B.dit_attn_varlen_workspace_bytes(p) - 1) == B.DIT_ERR_WORKSPACE
+    assert call_varlen(p, q=0) == B.DIT_ERR_INVALID_ARG
+    assert call_varlen(varlen_params(((2, 0, 4),))) == B.DIT_ERR_INVALID_ARG
+    assert call_varlen(varlen_params(())) == B.DIT_ERR_INVALID_ARG
+    assert call_varlen(varlen_params(((1, 1, 1),) * (B.DIT_MAX_REQUESTS + 1))) == B.DIT_ERR_UNSUPPORTED
+    assert B.dit_attn_varlen_workspace_bytes(varlen_params(((1, 1, 1),) * B.DIT_MAX_REQUESTS)) > 0
+    assert call_varlen(varlen_params(((256, 256, 256), (1, 1, 1)))) == B.DIT_ERR_UNSUPPORTED  # > 2^24 tokens
+    assert call_varlen(varlen_params(split=(44, 42, 40))) == B.DIT_ERR_INVALID_ARG
+    for f in (B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16, B.DIT_FLAG_WIDE_QTILE, B.DIT_FLAG_SIMPLE_SCHEDULE):
+        assert call_varlen(varlen_params(flags=f)) == B.DIT_ERR_UNSUPPORTED
+    p = varlen_params()
+    p.grids = None
+    assert call_varlen(p) == B.DIT_ERR_INVALID_ARG
+    p = varlen_params()
+    p.sk.token = 2 * 128 + 4
+    assert call_varlen(p) == B.DIT_ERR_ALIGNMENT
+
+
 def test_python_wrappers_refuse_host_tensors():
     import torch
 

@@ -374,3 +374,39 @@ def test_decoupled_cross_attention_pins(rng):
     np.testing.assert_allclose(o0[0], np.broadcast_to(want, o0[0].shape), atol=1e-14)
     # it is NOT the joint softmax in general
     assert np.max(np.abs(out[0] - joint[0])) > 1e-2
+
+
+def test_packed_requests_equal_block_diagonal_attention(rng):
+    """Packed requests: attention over ALL packed tokens with a block-diagonal mask (a token sees
+    its own request only) and per-request positions, written out with numpy on complex pairs."""
+    grids = [(2, 2, 3), (1, 1, 1), (1, 3, 2), (2, 1, 2)]
+    D, H, split, base, scale = 8, 2, (4, 2, 2), 100.0, 0.3
+    N = sum(int(np.prod(g)) for g in grids)
+    q, k, v = (rng.standard_normal((N, H, D)) for _ in range(3))
+    out, lse = oracle.self_attn_packed(q, k, v, grids, split, origin=(1, 2, 3), base=base, scale=scale, want_lse=True)
+    # positions and request ids of the packed tokens
+    pos, rid = [], []
+    for i, (T, Hg, Wg) in enumerate(grids):
+        for t in range(T):
+            for h in range(Hg):
+                for w in range(Wg):
+                    pos.append((1 + t, 2 + h, 3 + w))
+                    rid.append(i)
+    pos, rid = np.array(pos, dtype=np.float64), np.array(rid)
+    omega = np.concatenate([base ** (-2.0 * np.arange(split[a] // 2) / split[a]) for a in range(3)])
+    axis = np.concatenate([np.full(split[a] // 2, a) for a in range(3)])
+    phase = np.exp(1j * pos[:, axis] * omega[None, :])  # [N, D/2]
+    for h in range(H):
+        zq = (q[:, h, 0::2] + 1j * q[:, h, 1::2]) * phase
+        zk = (k[:, h, 0::2] + 1j * k[:, h, 1::2]) * phase
+        s = scale * (zq @ zk.conj().T).real
+        s[rid[:, None] != rid[None, :]] = -np.inf
+        mx = s.max(axis=1, keepdims=True)
+        e = np.exp(s - mx)
+        z = e.sum(axis=1, keepdims=True)
+        np.testing.assert_allclose(out[:, h], (e / z) @ v[:, h], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse[h], (mx + np.log(z))[:, 0], rtol=0, atol=1e-12)
+    # one request alone is the plain call
+    one = oracle.self_attn_packed(q[:12], k[:12], v[:12], grids[:1], split, base=base, scale=scale)
+    np.testing.assert_array_equal(one, oracle.self_attn(q[None, :12], k[None, :12], v[None, :12], grids[0], split,
+                                                        base=base, scale=scale)[0])
