@@ -107,7 +107,7 @@ def test_full_size_mixed_batch_sampled_rows():
 
     cfg = wl.CONFIGS["varlen_14b"]
     q, k, v = wl.varlen_attn_inputs(cfg)
-    out = run_varlen(cfg, q, k, v)
+    out = run_varlen(cfg, q, k, v, out_dtype=torch.float32)
     n0 = 0
     worst = 0.0
     for i, g in enumerate(cfg["grids"]):
@@ -116,6 +116,6 @@ def test_full_size_mixed_batch_sampled_rows():
         sl = slice(n0, n0 + L)
         ref = oracle.self_attn(q[None, sl], k[None, sl], v[None, sl], g, cfg["split"], rows=rows)[0]
         got = to_f64(out[torch.from_numpy(n0 + np.asarray(rows, dtype=np.int64)).cuda()])
-        worst = max(worst, compare(got, ref, bf16_out=True, what="varlen_14b request %d %s" % (i, (g,))))
+        worst = max(worst, compare(got, ref, what="varlen_14b request %d %s" % (i, (g,))))
         n0 += L
     print("varlen_14b worst max|err|/RMS = %.3e" % worst)
