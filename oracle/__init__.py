@@ -9,6 +9,9 @@ from .dit_oracle import (  # noqa: F401
     cross_attn_decoupled,
     self_attn_packed,
     num_threads,
+    qk_rmsnorm,
+    self_attn_normed,
+    as_f64,
     rope3d,
     self_attn,
     token_positions,

@@ -111,6 +111,41 @@ def self_attn(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, scale=0.0, r
     return res[0] if len(res) == 1 else res
 
 
+def as_f64(a):
+    """uint16 bf16 bit patterns, float32 or float64 -> float64 values."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def qk_rmsnorm(x, gamma=None, eps=1e-6, mode="head"):
+    """Root-mean-square normalisation of query or key rows before the rotation.
+
+    x: [..., H, D].  mode "head": the mean square runs over the D channels of each head;
+    mode "token": over all H*D channels of the token.  y = x * gamma / sqrt(mean(x^2) + eps),
+    gamma: [H, D] (or None = 1).  Returns float64.
+    """
+    x = as_f64(x)
+    if mode == "head":
+        ms = np.mean(x * x, axis=-1, keepdims=True)
+    elif mode == "token":
+        ms = np.mean(x * x, axis=(-2, -1), keepdims=True)
+    else:
+        raise ValueError(mode)
+    y = x / np.sqrt(ms + eps)
+    if gamma is not None:
+        y = y * np.asarray(gamma, dtype=np.float64).reshape(x.shape[-2:])
+    return y
+
+
+def self_attn_normed(q, k, v, grid, split, q_gamma=None, k_gamma=None, eps=1e-6, mode="head", **kw):
+    """Self-attention whose q and k rows are RMS-normalised (qk_rmsnorm) before the rotation:
+    the definition written out as normalise, then self_attn on the float64 results."""
+    return self_attn(qk_rmsnorm(q, q_gamma, eps, mode), qk_rmsnorm(k, k_gamma, eps, mode), as_f64(v), grid, split,
+                     **kw)
+
+
 def self_attn_packed(q, k, v, grids, split, origin=(0, 0, 0), base=10000.0, scale=0.0, want_lse=False):
     """Self-attention of several requests packed along the token axis: q, k, v [sum L_i, H, D],
     request i on its own grid grids[i] = (T, Hg, Wg) with L_i = T*Hg*Wg tokens.  Requests do not

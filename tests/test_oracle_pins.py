@@ -410,3 +410,55 @@ def test_packed_requests_equal_block_diagonal_attention(rng):
     one = oracle.self_attn_packed(q[:12], k[:12], v[:12], grids[:1], split, base=base, scale=scale)
     np.testing.assert_array_equal(one, oracle.self_attn(q[None, :12], k[None, :12], v[None, :12], grids[0], split,
                                                         base=base, scale=scale)[0])
+
+
+def test_qk_rmsnorm_pins(rng):
+    # worked example by hand: x = (3, 4): mean square 12.5, y = x / sqrt(12.5)
+    y = oracle.qk_rmsnorm(np.array([[[3.0, 4.0]]]), eps=0.0)
+    np.testing.assert_allclose(y[0, 0], [0.848528137423857, 1.131370849898476], rtol=0, atol=1e-15)
+    # with eps: x = (1, 1, 1, 1), eps = 3 -> 1 / sqrt(1 + 3) = 0.5; gamma scales channel-wise
+    y = oracle.qk_rmsnorm(np.ones((1, 1, 4)), gamma=np.array([[1.0, 2.0, -1.0, 0.0]]), eps=3.0)
+    np.testing.assert_allclose(y[0, 0], [0.5, 1.0, -0.5, 0.0], rtol=0, atol=1e-15)
+    # zero rows stay zero (no division by zero with eps > 0)
+    assert np.all(oracle.qk_rmsnorm(np.zeros((2, 3, 8)), eps=1e-6) == 0.0)
+    x = rng.standard_normal((5, 3, 16)) * 7.0
+    g = rng.standard_normal((3, 16))
+    for mode in ("head", "token"):
+        y = oracle.qk_rmsnorm(x, eps=0.0, mode=mode)
+        ax = -1 if mode == "head" else (-2, -1)
+        np.testing.assert_allclose(np.mean(y * y, axis=ax), 1.0, rtol=1e-13)           # unit mean square
+        np.testing.assert_allclose(oracle.qk_rmsnorm(-3.5 * x, eps=0.0, mode=mode), -y, rtol=1e-13)  # scale-free
+        np.testing.assert_allclose(oracle.qk_rmsnorm(x, g, 0.0, mode), y * g, rtol=1e-13)
+    # "token" mode is "head" mode on the flattened row, and both agree for one head
+    np.testing.assert_allclose(oracle.qk_rmsnorm(x, g, 1e-3, "token").reshape(5, 1, 48),
+                               oracle.qk_rmsnorm(x.reshape(5, 1, 48), g.reshape(1, 48), 1e-3, "head"), rtol=1e-14)
+    # library routine on the same numbers
+    import torch
+
+    t = torch.nn.functional.rms_norm(torch.from_numpy(x), (16,), torch.from_numpy(g[1]), eps=1e-5).numpy()
+    np.testing.assert_allclose(oracle.qk_rmsnorm(x, np.broadcast_to(g[1], (3, 16)), 1e-5, "head"), t, rtol=1e-12)
+    # bf16 bit patterns are decoded exactly: 0x3FC0 = 1.5, 0xC000 = -2.0
+    np.testing.assert_array_equal(oracle.as_f64(np.array([0x3FC0, 0xC000, 0x0000], dtype=np.uint16)), [1.5, -2.0, 0.0])
+
+
+def test_normed_attention_pins(rng):
+    """Normalise-then-attend: with gamma = 1 and eps = 0 the scores depend on directions only, so
+    scaling q rows and k rows by arbitrary positive factors changes nothing; and a brute-force
+    evaluation on pre-normalised rows agrees."""
+    grid, D, H = (2, 2, 3), 8, 2
+    L = 12
+    q, k, v = (rng.standard_normal((1, L, H, D)) for _ in range(3))
+    a = oracle.self_attn_normed(q, k, v, grid, SPLITS[D], eps=0.0)
+    fq = rng.uniform(0.1, 9.0, size=(1, L, H, 1))
+    fk = rng.uniform(0.1, 9.0, size=(1, L, H, 1))
+    b = oracle.self_attn_normed(q * fq, k * fk, v, grid, SPLITS[D], eps=0.0)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-12)
+    g = rng.standard_normal((H, D))
+    c = oracle.self_attn_normed(q, k, v, grid, SPLITS[D], q_gamma=g, k_gamma=2 * g, eps=1e-2, mode="token")
+    for h in range(H):
+        msq = np.mean(q[0] ** 2, axis=(1, 2))[:, None]
+        msk = np.mean(k[0] ** 2, axis=(1, 2))[:, None]
+        qn = q[0, :, h] / np.sqrt(msq + 1e-2) * g[h]
+        kn = k[0, :, h] / np.sqrt(msk + 1e-2) * 2 * g[h]
+        ref, _, _ = brute_self_attn(qn, kn, v[0, :, h], grid, SPLITS[D])
+        np.testing.assert_allclose(c[0, :, h], ref, rtol=0, atol=1e-12)
