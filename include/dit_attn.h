@@ -90,6 +90,26 @@ typedef struct {
 } dit_strides;
 
 /*
+ * Optional RMS normalisation of the q and k rows, applied in fp32 before the rotation (the
+ * per-block q/k normalisation of the DiT, fused so that normalised q and k never travel through
+ * memory):   y[c] = x[c] * gamma[c] / sqrt(mean(x^2) + eps).
+ * DIT_NORM_HEAD: the mean runs over the D channels of each head.
+ * DIT_NORM_TOKEN: over all H*D channels of the token (one more memory-bound pass over q and k
+ * computes the per-token factor into workspace).
+ * q_gamma, k_gamma: DEVICE fp32 arrays of H*D weights, head-major, 16-byte aligned; NULL = all 1.
+ * eps >= 0.  A zero-initialised struct switches the normalisation off.  Not available with
+ * DIT_FLAG_KV_FUSED (DIT_ERR_UNSUPPORTED).
+ */
+typedef enum { DIT_NORM_NONE = 0, DIT_NORM_HEAD = 1, DIT_NORM_TOKEN = 2 } dit_norm_mode;
+
+typedef struct {
+    int32_t mode; /* dit_norm_mode */
+    float eps;
+    const float *q_gamma;
+    const float *k_gamma;
+} dit_qk_norm;
+
+/*
  * Self-attention over the L = T*Hg*Wg tokens of a latent grid, no mask.
  * Token n (row-major, w fastest) sits at integer position
  *     (t, h, w) = (t0 + n / (Hg*Wg), h0 + (n / Wg) % Hg, w0 + n % Wg).
@@ -111,6 +131,7 @@ typedef struct {
     int32_t out_dtype;     /* dit_dtype of out */
     uint32_t flags;        /* DIT_FLAG_* */
     dit_strides sq, sk, sv, so;
+    dit_qk_norm norm;      /* zero = off */
 } dit_self_attn_params;
 
 /* Bytes of workspace dit_attn_forward needs for these params (0 on invalid params). */
@@ -147,6 +168,7 @@ typedef struct {
     uint32_t flags;
     int32_t Lk_split; /* 0: joint softmax; else first key of the second conditioning sequence */
     dit_strides sq, sk, sv, so;
+    dit_qk_norm norm; /* zero = off */
 } dit_cross_attn_params;
 
 size_t dit_cross_attn_workspace_bytes(const dit_cross_attn_params *p);
@@ -187,6 +209,7 @@ typedef struct {
     int32_t in_dtype, out_dtype;
     uint32_t flags;
     dit_strides sq, sk, sv, so;
+    dit_qk_norm norm; /* zero = off */
 } dit_varlen_attn_params;
 
 size_t dit_attn_varlen_workspace_bytes(const dit_varlen_attn_params *p);

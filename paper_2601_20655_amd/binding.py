@@ -51,6 +51,16 @@ class dit_strides(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int64), ("token", ctypes.c_int64), ("head", ctypes.c_int64)]
 
 
+DIT_NORM_NONE = 0
+DIT_NORM_HEAD = 1
+DIT_NORM_TOKEN = 2
+
+
+class dit_qk_norm(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("eps", ctypes.c_float),
+                ("q_gamma", ctypes.c_void_p), ("k_gamma", ctypes.c_void_p)]
+
+
 class dit_self_attn_params(ctypes.Structure):
     _fields_ = [
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
@@ -61,6 +71,7 @@ class dit_self_attn_params(ctypes.Structure):
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("flags", ctypes.c_uint32),
         ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
+        ("norm", dit_qk_norm),
     ]
 
 
@@ -72,6 +83,7 @@ class dit_cross_attn_params(ctypes.Structure):
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("flags", ctypes.c_uint32), ("Lk_split", ctypes.c_int32),
         ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
+        ("norm", dit_qk_norm),
     ]
 
 
@@ -92,6 +104,7 @@ class dit_varlen_attn_params(ctypes.Structure):
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("flags", ctypes.c_uint32),
         ("sq", dit_strides), ("sk", dit_strides), ("sv", dit_strides), ("so", dit_strides),
+        ("norm", dit_qk_norm),
     ]
 
 
@@ -182,18 +195,35 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def self_attn_params(q, k, v, out, grid, split, origin=(0, 0, 0), rope_base=10000.0, scale=0.0, flags=0):
+def qk_norm(norm, H, D):
+    """norm: None, or (mode, eps, q_gamma, k_gamma) with mode "head" / "token" and the weights
+    device float32 tensors of H*D elements (or None)."""
+    if norm is None:
+        return dit_qk_norm()
+    import torch
+
+    mode, eps, gq, gk = norm
+    ptrs = []
+    for g in (gq, gk):
+        if g is not None and (not g.is_cuda or g.dtype != torch.float32 or g.numel() != H * D or not g.is_contiguous()):
+            raise ValueError("normalisation weights must be dense float32 device tensors of H*D elements")
+        ptrs.append(g.data_ptr() if g is not None else None)
+    return dit_qk_norm({"head": DIT_NORM_HEAD, "token": DIT_NORM_TOKEN}[mode], eps, ptrs[0], ptrs[1])
+
+
+def self_attn_params(q, k, v, out, grid, split, origin=(0, 0, 0), rope_base=10000.0, scale=0.0, flags=0,
+                     norm=None):
     B, L, H, D = q.shape
     return dit_self_attn_params(
         B, H, D, grid[0], grid[1], grid[2], origin[0], origin[1], origin[2], split[0], split[1], split[2],
         rope_base, scale, _dtype_code(q), _dtype_code(out), flags,
-        _strides(q), _strides(k), _strides(v), _strides(out))
+        _strides(q), _strides(k), _strides(v), _strides(out), qk_norm(norm, H, D))
 
 
-def cross_attn_params(q, k, v, out, scale=0.0, flags=0, split=0):
+def cross_attn_params(q, k, v, out, scale=0.0, flags=0, split=0, norm=None):
     B, Lq, H, D = q.shape
     return dit_cross_attn_params(B, H, D, Lq, k.shape[1], scale, _dtype_code(q), _dtype_code(out), flags, split,
-                                 _strides(q), _strides(k), _strides(v), _strides(out))
+                                 _strides(q), _strides(k), _strides(v), _strides(out), qk_norm(norm, H, D))
 
 
 def _strides3(t):
@@ -203,14 +233,15 @@ def _strides3(t):
     return dit_strides(0, t.stride(0), t.stride(1))
 
 
-def varlen_attn_params(q, k, v, out, grids, split, origin=(0, 0, 0), rope_base=10000.0, scale=0.0, flags=0):
+def varlen_attn_params(q, k, v, out, grids, split, origin=(0, 0, 0), rope_base=10000.0, scale=0.0, flags=0,
+                       norm=None):
     """grids: sequence of (T, Hg, Wg).  The returned struct keeps the host grid array alive."""
     N, H, D = q.shape
     arr = (dit_grid * max(len(grids), 1))(*[dit_grid(*g) for g in grids])
     p = dit_varlen_attn_params(
         len(grids), H, D, ctypes.cast(arr, ctypes.POINTER(dit_grid)), origin[0], origin[1], origin[2],
         split[0], split[1], split[2], rope_base, scale, _dtype_code(q), _dtype_code(out), flags,
-        _strides3(q), _strides3(k), _strides3(v), _strides3(out))
+        _strides3(q), _strides3(k), _strides3(v), _strides3(out), qk_norm(norm, H, D))
     p._grids_keepalive = arr
     return p
 
@@ -234,8 +265,9 @@ def _workspace(nbytes, device):
 
 
 def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0), rope_base=10000.0,
-                     scale=0.0, flags=0, out_dtype=None, workspace=None, stream=None, want_lse=False):
+                     scale=0.0, flags=0, out_dtype=None, workspace=None, stream=None, want_lse=False, norm=None):
     """Self-attention with 3-axis RoPE on device tensors q, k, v of shape [B, L, H, D].
+    norm: None or (mode, eps, q_gamma, k_gamma), see qk_norm.
 
     Allocates `out` (and `lse`, `workspace`) with torch when not given; returns out, or
     (out, lse) when an lse buffer is requested.  Asynchronous on the stream.
@@ -249,7 +281,7 @@ def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0),
         out = torch.empty((B, L, H, D), dtype=out_dtype or q.dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty((B, H, L), dtype=torch.float32, device=q.device)
-    p = self_attn_params(q, k, v, out, grid, split, origin, rope_base, scale, flags)
+    p = self_attn_params(q, k, v, out, grid, split, origin, rope_base, scale, flags, norm)
     need = dit_attn_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)
@@ -263,7 +295,7 @@ def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0),
 
 
 def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0, flags=0, out_dtype=None,
-                           workspace=None, stream=None, want_lse=False, split=0):
+                           workspace=None, stream=None, want_lse=False, split=0, norm=None):
     """Cross-attention: q [B, Lq, H, D]; k, v [B, Lk, H, D]; kv_valid uint8 [B, Lk] or None.
     split > 0 selects the decoupled form (separate softmax over keys [0, split) and [split, Lk))."""
     import torch
@@ -278,7 +310,7 @@ def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0
     if kv_valid is not None:
         if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, k.shape[1]):
             raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
-    p = cross_attn_params(q, k, v, out, scale, flags, split)
+    p = cross_attn_params(q, k, v, out, scale, flags, split, norm)
     need = dit_cross_attn_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)
@@ -293,7 +325,8 @@ def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0
 
 
 def dit_attn_varlen_forward(q, k, v, grids, split, out=None, lse=None, origin=(0, 0, 0), rope_base=10000.0,
-                            scale=0.0, flags=0, out_dtype=None, workspace=None, stream=None, want_lse=False):
+                            scale=0.0, flags=0, out_dtype=None, workspace=None, stream=None, want_lse=False,
+                            norm=None):
     """Self-attention of several requests packed along the token axis: q, k, v [sum L_i, H, D],
     grids = [(T, Hg, Wg), ...] with L_i = T*Hg*Wg.  Returns out (and lse [H, sum L_i] if asked)."""
     import torch
@@ -307,7 +340,7 @@ def dit_attn_varlen_forward(q, k, v, grids, split, out=None, lse=None, origin=(0
         out = torch.empty((N, H, D), dtype=out_dtype or q.dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty((H, N), dtype=torch.float32, device=q.device)
-    p = varlen_attn_params(q, k, v, out, grids, split, origin, rope_base, scale, flags)
+    p = varlen_attn_params(q, k, v, out, grids, split, origin, rope_base, scale, flags, norm)
     need = dit_attn_varlen_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)

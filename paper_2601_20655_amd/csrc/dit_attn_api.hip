@@ -111,12 +111,56 @@ bool strides_ok(const dit_strides& s, int32_t B, int32_t H, int32_t D) {
     return s.batch >= 0;
 }
 
+// eps >= 0, a known mode; the channel weights are read as float4
+dit_status norm_ok(const dit_qk_norm& n) {
+    if (n.mode != DIT_NORM_NONE && n.mode != DIT_NORM_HEAD && n.mode != DIT_NORM_TOKEN) return DIT_ERR_INVALID_ARG;
+    if (n.mode == DIT_NORM_NONE) return DIT_OK;
+    if (!(n.eps >= 0.f) || !isfinite(n.eps)) return DIT_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(n.q_gamma) | reinterpret_cast<uintptr_t>(n.k_gamma)) & 15u)
+        return DIT_ERR_ALIGNMENT;
+    return DIT_OK;
+}
+
+// Workspace tail for the per-token multipliers of q and k rows (TOKEN mode only).
+size_t rstd_bytes(const dit_qk_norm& n, int64_t q_rows, int64_t k_rows) {
+    if (n.mode != DIT_NORM_TOKEN) return 0;
+    return round_up((size_t)q_rows * sizeof(float), kAlign) + round_up((size_t)k_rows * sizeof(float), kAlign);
+}
+
+// Fills the normalisation arguments of both kernels; in TOKEN mode launches the two statistics passes.
+dit_status setup_norm(const dit_qk_norm& n, const void* q, const void* k, const dit_strides& sq, const dit_strides& sk,
+                      int B, int Lq, int Lk, int H, int D, int in_f32, uint8_t* rstd_ws, dit::NormArgs* qn,
+                      dit::NormArgs* kn, hipStream_t s) {
+    memset(qn, 0, sizeof(*qn));
+    memset(kn, 0, sizeof(*kn));
+    if (n.mode == DIT_NORM_NONE) return DIT_OK;
+    qn->mode = kn->mode = n.mode;
+    qn->eps = kn->eps = n.eps;
+    qn->gamma = n.q_gamma;
+    kn->gamma = n.k_gamma;
+    if (n.mode == DIT_NORM_TOKEN) {
+        float* rq = reinterpret_cast<float*>(rstd_ws);
+        float* rk = reinterpret_cast<float*>(rstd_ws + round_up((size_t)B * Lq * sizeof(float), kAlign));
+        dit::RstdArgs ra;
+        ra.x = q; ra.rstd = rq; ra.s_b = sq.batch; ra.s_t = sq.token; ra.s_h = sq.head;
+        ra.B = B; ra.L = Lq; ra.H = H; ra.D = D; ra.in_f32 = in_f32; ra.eps = n.eps;
+        hipError_t e = dit::launch_token_rstd(ra, s);
+        if (e != hipSuccess) return hip_fail(e, "token_rstd_kernel");
+        ra.x = k; ra.rstd = rk; ra.s_b = sk.batch; ra.s_t = sk.token; ra.s_h = sk.head; ra.L = Lk;
+        e = dit::launch_token_rstd(ra, s);
+        if (e != hipSuccess) return hip_fail(e, "token_rstd_kernel");
+        qn->rstd = rq;
+        kn->rstd = rk;
+    }
+    return DIT_OK;
+}
+
 struct SelfPlan {
     Flags fl;
     int64_t L;
     int nKT, nQT;
     int table_entries;
-    size_t tab_off, tiles_off, total;
+    size_t tab_off, tiles_off, rstd_off, total;
 };
 
 dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
@@ -130,6 +174,8 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
     if (!dtype_ok(p->in_dtype) || !dtype_ok(p->out_dtype)) return DIT_ERR_INVALID_ARG;
     dit_status st = parse_flags(p->flags, &pl->fl);
     if (st != DIT_OK) return st;
+    if ((st = norm_ok(p->norm)) != DIT_OK) return st;
+    if (pl->fl.fused && p->norm.mode != DIT_NORM_NONE) return DIT_ERR_UNSUPPORTED;
     const int64_t L = (int64_t)p->T * p->Hg * p->Wg;
     if (L > (1 << 24)) return DIT_ERR_UNSUPPORTED;  // token indices are 32-bit with room for tile padding
     if ((int64_t)p->B * p->H > (1 << 20)) return DIT_ERR_UNSUPPORTED;
@@ -158,7 +204,8 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
     pl->tab_off = 0;
     pl->tiles_off = round_up((size_t)pl->table_entries * sizeof(float2), kAlign);
     size_t tiles = pl->fl.fused ? 0 : (size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D);
-    pl->total = pl->tiles_off + round_up(tiles, kAlign);
+    pl->rstd_off = pl->tiles_off + round_up(tiles, kAlign);
+    pl->total = pl->rstd_off + rstd_bytes(p->norm, (int64_t)p->B * L, (int64_t)p->B * L);
     if (pl->total == 0) pl->total = kAlign;
     return DIT_OK;
 }
@@ -168,7 +215,7 @@ struct VarlenPlan {
     dit::VarlenTable vt;
     int maxT, maxHg, maxWg;
     int table_entries;
-    size_t tab_off, tiles_off, total;
+    size_t tab_off, tiles_off, rstd_off, total;
 };
 
 dit_status plan_varlen(const dit_varlen_attn_params* p, VarlenPlan* pl) {
@@ -183,6 +230,7 @@ dit_status plan_varlen(const dit_varlen_attn_params* p, VarlenPlan* pl) {
     if (!dtype_ok(p->in_dtype) || !dtype_ok(p->out_dtype)) return DIT_ERR_INVALID_ARG;
     dit_status st = parse_flags(p->flags, &pl->fl);
     if (st != DIT_OK) return st;
+    if ((st = norm_ok(p->norm)) != DIT_OK) return st;
     // only the pipelined kernel with pre-packed tiles and 32 rows per wavefront has this form
     if (pl->fl.fused || pl->fl.simple || pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
     if (p->H > (1 << 16)) return DIT_ERR_UNSUPPORTED;
@@ -251,7 +299,8 @@ dit_status plan_varlen(const dit_varlen_attn_params* p, VarlenPlan* pl) {
     pl->table_entries = pl->maxT * (p->d_t / 2) + pl->maxHg * (p->d_h / 2) + pl->maxWg * (p->d_w / 2);
     pl->tab_off = 0;
     pl->tiles_off = round_up((size_t)pl->table_entries * sizeof(float2), kAlign);
-    pl->total = pl->tiles_off + round_up((size_t)tile0 * p->H * dit::tile_bytes(p->D), kAlign);
+    pl->rstd_off = pl->tiles_off + round_up((size_t)tile0 * p->H * dit::tile_bytes(p->D), kAlign);
+    pl->total = pl->rstd_off + rstd_bytes(p->norm, total, total);
     return DIT_OK;
 }
 
@@ -259,7 +308,7 @@ struct CrossPlan {
     Flags fl;
     int nKT, nQT;
     int split, nTA;  // decoupled form: first key of the second sequence, tiles of the first (0, 0: joint)
-    size_t mask_off, list_off, count_off, count_a_off, tiles_off, total;
+    size_t mask_off, list_off, count_off, count_a_off, tiles_off, rstd_off, total;
 };
 
 dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
@@ -271,6 +320,7 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     dit_status st = parse_flags(p->flags, &pl->fl);
     if (st != DIT_OK) return st;
     if (pl->fl.fused) return DIT_ERR_UNSUPPORTED;
+    if ((st = norm_ok(p->norm)) != DIT_OK) return st;
     if (p->Lq > (1 << 24) || p->Lk > (1 << 24) || (int64_t)p->B * p->H > (1 << 20)) return DIT_ERR_UNSUPPORTED;
     if (!strides_ok(p->sq, p->B, p->H, p->D) || !strides_ok(p->sk, p->B, p->H, p->D) ||
         !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
@@ -298,7 +348,8 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     pl->count_off = pl->list_off + round_up((size_t)p->B * pl->nKT * sizeof(int), kAlign);
     pl->count_a_off = pl->count_off + round_up((size_t)p->B * sizeof(int), kAlign);
     pl->tiles_off = pl->count_a_off + round_up((size_t)p->B * sizeof(int), kAlign);
-    pl->total = pl->tiles_off + round_up((size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D), kAlign);
+    pl->rstd_off = pl->tiles_off + round_up((size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D), kAlign);
+    pl->total = pl->rstd_off + rstd_bytes(p->norm, (int64_t)p->B * p->Lq, (int64_t)p->B * p->Lk);
     return DIT_OK;
 }
 
@@ -350,9 +401,15 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
 
     const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
 
+    dit::NormArgs qn, kn;
+    st = setup_norm(p->norm, q, k, p->sq, p->sk, p->B, (int)pl.L, (int)pl.L, p->H, p->D, p->in_dtype == DIT_F32,
+                    ws + pl.rstd_off, &qn, &kn, s);
+    if (st != DIT_OK) return st;
+
     if (!pl.fl.fused) {
         dit::PackArgs pa;
         memset(&pa, 0, sizeof(pa));
+        pa.kn = kn;
         pa.k = k; pa.v = v; pa.valid = nullptr;
         pa.tiles = ws + pl.tiles_off;
         pa.tile_mask = nullptr;
@@ -381,6 +438,7 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
     aa.so_b = p->so.batch; aa.so_t = p->so.token; aa.so_h = p->so.head;
     aa.rg = rg;
     aa.qscale = scale * dit::kLog2e;
+    aa.qn = qn;
     return run_attn(aa, p->D, pl.fl, pl.fl.fused, s);
 }
 
@@ -403,8 +461,14 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
 
+    dit::NormArgs qn, kn;
+    st = setup_norm(p->norm, q, k, p->sq, p->sk, p->B, p->Lq, p->Lk, p->H, p->D, p->in_dtype == DIT_F32,
+                    ws + pl.rstd_off, &qn, &kn, s);
+    if (st != DIT_OK) return st;
+
     dit::PackArgs pa;
     memset(&pa, 0, sizeof(pa));
+    pa.kn = kn;
     pa.k = k; pa.v = v; pa.valid = kv_valid;
     pa.tiles = ws + pl.tiles_off;
     pa.tile_mask = reinterpret_cast<uint64_t*>(ws + pl.mask_off);
@@ -437,6 +501,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     aa.sq_b = p->sq.batch; aa.sq_t = p->sq.token; aa.sq_h = p->sq.head;
     aa.so_b = p->so.batch; aa.so_t = p->so.token; aa.so_h = p->so.head;
     aa.qscale = scale * dit::kLog2e;
+    aa.qn = qn;
     return run_attn(aa, p->D, pl.fl, false, s);
 }
 
@@ -480,8 +545,16 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
 
     const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
 
+    dit::NormArgs qn, kn;
+    dit_strides sq1 = p->sq, sk1 = p->sk;
+    sq1.batch = sk1.batch = 0;
+    st = setup_norm(p->norm, q, k, sq1, sk1, 1, pl.vt.total_tokens, pl.vt.total_tokens, p->H, p->D,
+                    p->in_dtype == DIT_F32, ws + pl.rstd_off, &qn, &kn, s);
+    if (st != DIT_OK) return st;
+
     dit::PackArgs pa;
     memset(&pa, 0, sizeof(pa));
+    pa.kn = kn;
     pa.k = k; pa.v = v;
     pa.tiles = ws + pl.tiles_off;
     pa.tab = ta.tab;
@@ -505,6 +578,7 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     aa.so_t = p->so.token; aa.so_h = p->so.head;
     aa.rg = rg;
     aa.qscale = scale * dit::kLog2e;
+    aa.qn = qn;
 
     const bool timed = g_ev_before && g_ev_after;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
@@ -533,6 +607,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 105; }
+int dit_attn_version(void) { return 106; }
 
 }  // extern "C"

@@ -83,6 +83,38 @@ __device__ __forceinline__ void load8(const void* base, int64_t off, int in_f32,
     }
 }
 
+// Multiplier 1/sqrt(mean(x^2) + eps) of one q row.  The row's D channels are read by the lane
+// pair (lane, lane ^ 32), lane half `half` taking chunks 2*ks + half; `base` is the element
+// offset of the row's head, `stat` the row's index in the per-token table (mode 2).
+template <int D>
+__device__ __forceinline__ float q_row_rstd(const NormArgs& n, const void* q, int64_t base, int in_f32, int half,
+                                            int64_t stat) {
+    if (n.mode == 2) return n.rstd[stat];
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+        float x[8];
+        load8(q, base + 8 * (2 * ks + half), in_f32, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+    }
+    ss += __shfl_xor(ss, 32);
+    return 1.0f / sqrtf(ss * (1.0f / D) + n.eps);
+}
+
+// x[0..8) = channels [8c, 8c+8) of head h: times the row multiplier and the channel weights
+__device__ __forceinline__ void norm8(float x[8], const NormArgs& n, float rs, int h, int D, int c) {
+    if (n.gamma) {
+        const float4* g = reinterpret_cast<const float4*>(n.gamma + (int64_t)h * D + 8 * c);
+        const float4 g0 = g[0], g1 = g[1];
+        x[0] *= rs * g0.x; x[1] *= rs * g0.y; x[2] *= rs * g0.z; x[3] *= rs * g0.w;
+        x[4] *= rs * g1.x; x[5] *= rs * g1.y; x[6] *= rs * g1.z; x[7] *= rs * g1.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= rs;
+    }
+}
+
 // Token index -> position indices along (t, h, w), counted from the grid origin.
 __device__ __forceinline__ void token_pos(int n, const RopeGeom& rg, int& pt, int& ph, int& pw) {
     const int hw = rg.Hg * rg.Wg;

@@ -182,11 +182,14 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
         const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
         int pt = 0, ph = 0, pw = 0;
         if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
+        float rs = 1.f;
+        if (a.qn.mode) rs = q_row_rstd<D>(a.qn, a.q, base, a.in_f32, half, (int64_t)b * a.Lq + qr);
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             const int c = 2 * ks + half;
             float x[8];
             load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.qn.mode) norm8(x, a.qn, rs, h, D, c);
             if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] *= a.qscale;

@@ -72,6 +72,7 @@ struct PipeView {
     const uint8_t* tiles;  // tile images of this (sequence, head)
     int64_t q_off, o_off;  // element offsets of row 0 of this (sequence, head) in q / out
     int64_t lse_off;       // index of row 0 in lse
+    int64_t stat_off;      // index of row 0 in the per-token normalisation table
     int Hg, Wg;            // latent grid of this sequence
 };
 
@@ -410,11 +411,14 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
         int pt = 0, ph = 0, pw = 0;
         if (a.tab) token_pos(qr, rg, pt, ph, pw);
+        float rs = 1.f;
+        if (a.qn.mode) rs = q_row_rstd<D>(a.qn, a.q, base, a.in_f32, half, pv.stat_off + qr);
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             const int c = 2 * ks + half;
             float x[8];
             load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.qn.mode) norm8(x, a.qn, rs, pv.h, D, c);
             if (a.tab) rope8(x, c, rg, a.tab, pt, ph, pw);
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
@@ -504,6 +508,7 @@ __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel
     pv.q_off = (int64_t)pv.b * a.sq_b + (int64_t)pv.h * a.sq_h;
     pv.o_off = (int64_t)pv.b * a.so_b + (int64_t)pv.h * a.so_h;
     pv.lse_off = ((int64_t)pv.b * a.H + pv.h) * a.Lq;
+    pv.stat_off = (int64_t)pv.b * a.Lq;
     pv.Hg = a.rg.Hg;
     pv.Wg = a.rg.Wg;
     attn_pipe_body<D, QB, QK_OP, PV_OP, NW, LISTED>(a, pv);
@@ -538,6 +543,7 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_fwd_pipe_varlen_kernel(const 
     pv.q_off = (int64_t)rq.tok0 * a.sq_t + (int64_t)pv.h * a.sq_h;
     pv.o_off = (int64_t)rq.tok0 * a.so_t + (int64_t)pv.h * a.so_h;
     pv.lse_off = (int64_t)pv.h * vt.total_tokens + rq.tok0;
+    pv.stat_off = rq.tok0;
     pv.Hg = rq.Hg;
     pv.Wg = rq.Wg;
     attn_pipe_body<D, 1, QK_OP, PV_OP, NW, false>(a, pv);

@@ -37,6 +37,24 @@ struct RopeGeom {
     int Hg, Wg;  // latent grid height and width (token -> (t,h,w) decode)
 };
 
+// RMS normalisation of q or k rows ahead of the rotation: y = x * gamma / sqrt(mean(x^2) + eps).
+struct NormArgs {
+    int mode;            // 0 off; 1 mean over the D channels of the head; 2 over all H*D channels of the token
+    float eps;
+    const float* gamma;  // nullable [H*D]
+    const float* rstd;   // mode 2: 1/sqrt(mean + eps) per token row, filled by launch_token_rstd
+};
+
+// per-token 1/sqrt(mean over H*D channels + eps)
+struct RstdArgs {
+    const void* x;
+    float* rstd;  // [B*L]
+    int64_t s_b, s_t, s_h;
+    int B, L, H, D;
+    int in_f32;
+    float eps;
+};
+
 struct TableArgs {
     float2* tab;
     int n[3];       // positions per axis (T, Hg, Wg)
@@ -61,6 +79,7 @@ struct PackArgs {
     int in_f32;
     int64_t sk_b, sk_t, sk_h, sv_b, sv_t, sv_h;
     RopeGeom rg;
+    NormArgs kn;  // normalisation of k rows (rstd indexed by b*Lk + key, packed requests: by token)
 };
 
 struct AttnArgs {
@@ -82,6 +101,7 @@ struct AttnArgs {
     int64_t sq_b, sq_t, sq_h, so_b, so_t, so_h;
     RopeGeom rg;
     float qscale;  // softmax scale * log2(e), folded into q'
+    NormArgs qn;   // normalisation of q rows (rstd indexed by b*Lq + row, packed requests: by token)
 };
 
 // Several requests with their own latent grids packed back to back along the token axis
@@ -106,6 +126,7 @@ struct VarlenTable {
 };
 
 hipError_t launch_rope_table(const TableArgs& a, hipStream_t s);
+hipError_t launch_token_rstd(const RstdArgs& a, hipStream_t s);
 hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, hipStream_t s);
 hipError_t launch_attn_pipe_varlen(const AttnArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, int nw,
                                    hipStream_t s);

@@ -29,12 +29,44 @@ hipError_t launch_rope_table(const TableArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+// One workgroup per token: 1/sqrt(mean of x^2 over all H*D channels + eps).
+__global__ void __launch_bounds__(256) token_rstd_kernel(const RstdArgs a) {
+    __shared__ float part[4];
+    const int64_t row = blockIdx.x;
+    const int b = (int)(row / a.L), n = (int)(row - (int64_t)b * a.L);
+    const int cpr = a.D / 8, chunks = a.H * cpr;
+    const int64_t base = (int64_t)b * a.s_b + (int64_t)n * a.s_t;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < chunks; i += 256) {
+        const int h = i / cpr, c = i - h * cpr;
+        float x[8];
+        load8(a.x, base + (int64_t)h * a.s_h + 8 * c, a.in_f32, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) ss += __shfl_xor(ss, m);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+        a.rstd[row] = 1.0f / sqrtf(tot / (float)(a.H * a.D) + a.eps);
+    }
+}
+
+hipError_t launch_token_rstd(const RstdArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(token_rstd_kernel, dim3((unsigned)((int64_t)a.B * a.L)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 // What one workgroup packs: 64 keys of one (batch or request, head).
 struct PackTile {
     uint8_t* dst;        // tile image
     int64_t k_off, v_off;  // element offset of key 0 of this sequence for this head
     int key0, key_end;   // keys [key0, key0 + 64) clipped to key_end
     RopeGeom rg;         // with this sequence's grid
+    int h;               // head (channel weights of the normalisation)
+    int64_t stat_off;    // index of key 0 in the per-token normalisation table
 };
 
 template <int D, int QK_OP, int PV_OP>
@@ -57,6 +89,22 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
         if (key < t.key_end) {
             load8(a.k, t.k_off + (int64_t)key * a.sk_t + 8 * c, a.in_f32, xk);
             load8(a.v, t.v_off + (int64_t)key * a.sv_t + 8 * c, a.in_f32, xv);
+        }
+        if (a.kn.mode) {  // the CPR neighbouring lanes that share a row add up its squares
+            float rs;
+            if (a.kn.mode == 2) {
+                rs = key < t.key_end ? a.kn.rstd[t.stat_off + key] : 0.f;
+            } else {
+                float ss = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = fmaf(xk[e], xk[e], ss);
+#pragma unroll
+                for (int m = 1; m < CPR; m <<= 1) ss += __shfl_xor(ss, m);
+                rs = 1.0f / sqrtf(ss * (1.0f / D) + a.kn.eps);
+            }
+            if (key < t.key_end) norm8(xk, a.kn, rs, t.h, D, c);
+        }
+        if (key < t.key_end) {
             if (a.tab) {
                 int pt, ph, pw;
                 token_pos(key, t.rg, pt, ph, pw);
@@ -104,6 +152,8 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     t.key0 = second ? a.split + (j - a.nTA) * kBK : j * kBK;
     t.key_end = (a.split > 0 && !second) ? a.split : a.Lk;
     t.rg = a.rg;
+    t.h = h;
+    t.stat_off = (int64_t)b * a.Lk;
     pack_tile<D, QK_OP, PV_OP>(a, t, vs);
 
     if (a.tile_mask && h == 0 && tid < 64) {
@@ -134,6 +184,8 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_varlen_kernel(const PackA
     t.rg = a.rg;
     t.rg.Hg = q.Hg;
     t.rg.Wg = q.Wg;
+    t.h = h;
+    t.stat_off = q.tok0;
     pack_tile<D, QK_OP, PV_OP>(a, t, vs);
 }
 

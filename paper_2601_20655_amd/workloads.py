@@ -80,6 +80,14 @@ def varlen_attn_inputs(cfg, seed=None, dtype=None):
     return tuple(normal(shape, seed, s, dtype) for s in range(3))
 
 
+def norm_weights(cfg, seed=None):
+    """Channel weights of the q and k normalisation layers, [H, D] float32 each, 1 + 0.25 N(0,1)
+    (trained weights of such layers sit around one)."""
+    seed = cfg["seed"] if seed is None else seed
+    shape = (cfg["H"], cfg["D"])
+    return tuple((1.0 + 0.25 * normal(shape, seed, s, "f32")).astype(np.float32) for s in (7, 8))
+
+
 def cross_attn_inputs(cfg, seed=None, dtype=None):
     """q [B,Lq,H,D], k, v [B,Lk,H,D], kv_valid [B,Lk] uint8, text_len [B].
 

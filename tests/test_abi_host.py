@@ -137,6 +137,37 @@ def test_cross_attn_rejects_bad_arguments():
     assert B.dit_last_hip_error() == ""
 
 
+def test_qk_norm_arguments():
+    L, H = 24, 2
+    base = B.dit_attn_workspace_bytes(self_params())
+    p = self_params()
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, 1e-6, None, None)
+    assert B.dit_attn_workspace_bytes(p) == base                    # per-head statistics need no table
+    p.norm.mode = B.DIT_NORM_TOKEN
+    assert B.dit_attn_workspace_bytes(p) == base + 2 * up(4 * L)    # one fp32 factor per q row and per k row
+    p.norm.mode = 3
+    assert call_self(p) == B.DIT_ERR_INVALID_ARG
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, -1.0, None, None)
+    assert call_self(p) == B.DIT_ERR_INVALID_ARG
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, float("nan"), None, None)
+    assert call_self(p) == B.DIT_ERR_INVALID_ARG
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, 1e-6, 0x20004, None)
+    assert call_self(p) == B.DIT_ERR_ALIGNMENT
+    p = self_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, 1e-6, None, None)
+    assert call_self(p) == B.DIT_ERR_UNSUPPORTED
+    c = cross_params()
+    cbase = B.dit_cross_attn_workspace_bytes(c)
+    c.norm = B.dit_qk_norm(B.DIT_NORM_TOKEN, 1e-6, None, None)
+    assert B.dit_cross_attn_workspace_bytes(c) == cbase + up(4 * 2 * 100) + up(4 * 2 * 769)
+    c.norm.mode = -1
+    assert call_cross(c) == B.DIT_ERR_INVALID_ARG
+    v = varlen_params()
+    vbase = B.dit_attn_varlen_workspace_bytes(v)
+    v.norm = B.dit_qk_norm(B.DIT_NORM_TOKEN, 0.0, None, None)
+    assert B.dit_attn_varlen_workspace_bytes(v) == vbase + 2 * up(4 * 49)
+
+
 def varlen_params(grids=((2, 3, 4), (1, 5, 5)), H=2, D=128, split=(44, 42, 42), flags=0):
     arr = (B.dit_grid * max(len(grids), 1))(*[B.dit_grid(*g) for g in grids])
     s = B.dit_strides(0, H * D, D)
