@@ -58,6 +58,105 @@ class HipEvents:
             self.hip.hipEventDestroy(b)
 
 
+def time_calls(B, torch, call, steps, warmup):
+    """Warm up, then time `steps` calls of call() (one forward through the C ABI each): wall time
+    per call bracketed by synchronisations, and the attention kernel's own time from HIP events."""
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    ev = HipEvents(steps)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        B.dit_attn_set_timing_events(*ev.pairs[i])
+        call()
+        B.dit_attn_set_timing_events(None, None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = ev.elapsed_ms()
+    ev.close()
+    return (t1 - t0) * 1e3 / steps, sum(kern) / len(kern)
+
+
+def other_workload(args):
+    """Secondary timing lines (not the headline metric): the other shapes and entry points, each as
+    one JSON line of the same layout with its own metric name."""
+    import numpy as np
+    import torch
+
+    from paper_2601_20655_amd import binding as B
+    from paper_2601_20655_amd import workloads as wl
+
+    B.lib()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cfg = wl.CONFIGS[args.workload]
+    stream = torch.cuda.current_stream()
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+
+    H, D = cfg["H"], cfg["D"]
+    if cfg["kind"] == "self":
+        q, k, v = (dev(a) for a in wl.self_attn_inputs(cfg))
+        out = torch.empty_like(q)
+        ws = torch.empty(B.dit_attn_workspace_bytes(B.self_attn_params(q, k, v, out, cfg["grid"], cfg["split"],
+                                                                        flags=args.flags)),
+                         dtype=torch.uint8, device="cuda")
+        L = q.shape[1]
+        flops = 4.0 * cfg["B"] * H * L * L * D
+        what = "self-attention, grid %dx%dx%d = %d tokens, %d heads, d%d" % (cfg["grid"] + (L, H, D))
+        kernel = "attn_fwd_pipe_kernel"
+
+        def call():
+            B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
+                               stream=stream)
+    elif cfg["kind"] == "varlen":
+        q, k, v = (dev(a) for a in wl.varlen_attn_inputs(cfg))
+        out = torch.empty_like(q)
+        grids = list(cfg["grids"])
+        ws = torch.empty(B.dit_attn_varlen_workspace_bytes(B.varlen_attn_params(q, k, v, out, grids, cfg["split"],
+                                                                                 flags=args.flags)),
+                         dtype=torch.uint8, device="cuda")
+        flops = sum(4.0 * H * D * float(t * h * w) ** 2 for t, h, w in grids)
+        what = "self-attention over %d packed requests (%d tokens), %d heads, d%d" % (len(grids), q.shape[0], H, D)
+        kernel = "attn_fwd_pipe_varlen_kernel"
+
+        def call():
+            B.dit_attn_varlen_forward(q, k, v, grids, cfg["split"], out=out, flags=args.flags, workspace=ws,
+                                      stream=stream)
+    else:
+        qn, kn, vn, valid, text_len = wl.cross_attn_inputs(cfg)
+        q, k, v = dev(qn), dev(kn), dev(vn)
+        vd = torch.from_numpy(valid).cuda()
+        out = torch.empty_like(q)
+        split = cfg["n_text"] if args.decoupled else 0
+        ws = torch.empty(B.dit_cross_attn_workspace_bytes(B.cross_attn_params(q, k, v, out, flags=args.flags,
+                                                                               split=split)),
+                         dtype=torch.uint8, device="cuda")
+        Lq = q.shape[1]
+        flops = 4.0 * H * Lq * D * float(valid.sum())  # keys that attend; padded keys are skipped, not computed
+        what = "%s cross-attention, B=%d, %d queries x (512 text masked to %s + 257 image) keys, %d heads, d%d" % (
+            "decoupled" if split else "joint", cfg["B"], Lq, list(map(int, text_len)), H, D)
+        kernel = "attn_fwd_kernel"
+
+        def call():
+            B.dit_cross_attn_forward(q, k, v, vd, out=out, flags=args.flags, workspace=ws, stream=stream, split=split)
+
+    ms, kern_ms = time_calls(B, torch, call, args.steps, args.warmup)
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "attention TFLOP/s, %s" % args.workload + (" (decoupled)" if args.decoupled else ""),
+        "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16" if not (args.flags & B.DIT_FLAG_QK_BF16) else "bf16",
+        "data": "synthetic",
+        "config": {"workload": what, "flags": args.flags, "attn_kernel_ms": round(kern_ms, 4), "flops_per_step": flops},
+        "roofline": {"kernel": kernel, "bound": "mfma", "achieved": round(achieved, 2),
+                     "peak": PEAK_TFLOPS_16BIT_DENSE, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_TFLOPS_16BIT_DENSE, 4), "traffic": None},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,10 +167,16 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the timed region, so that a "
                          "counter run (FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
+    ap.add_argument("--workload", default="step",
+                    help="'step' (default: the headline metric) or one of the other shapes for a secondary "
+                         "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b")
+    ap.add_argument("--decoupled", action="store_true", help="cross_14b: one softmax per conditioning sequence")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all heads of one request on one MI355X, no "
                  "collectives); --gpus %d is not supported" % args.gpus)
+    if args.workload != "step":
+        return other_workload(args)
 
     import numpy as np
     import torch
