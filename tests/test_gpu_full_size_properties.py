@@ -1,0 +1,97 @@
+"""Properties that hold at any size, checked on EVERY output row at the full 32,760-token x
+40-head shape in the launch configuration the benchmark times (the oracle covers sampled rows of
+the same shape in test_gpu_self_attn.py / test_gpu_cross_attn.py).  The expected values here are
+mathematical identities, not outputs of any implementation."""
+import numpy as np
+import pytest
+
+from paper_2601_20655_amd import binding as B
+from paper_2601_20655_amd import workloads as wl
+from gpu_util import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_constant_values_come_back_for_every_row():
+    """If every key carries the same value vector c[h, :], any softmax returns c: all 512 key tiles
+    of all rows must have been weighted and normalised (a dropped or doubled tile, a wrong tail
+    mask or a wrong row sum shows as a deviation proportional to |c|)."""
+    import torch
+
+    cfg = wl.CONFIGS["dit_14b"]
+    q, k, _ = wl.self_attn_inputs(cfg)
+    H, D = cfg["H"], cfg["D"]
+    c = wl.bf16_bits_to_f32(wl.normal((H, D), cfg["seed"], 5, "bf16"))
+    cd = torch.from_numpy(c).cuda()
+    qd, kd = to_dev(q), to_dev(k)
+    vd = cd.to(torch.bfloat16)[None, None].expand(1, qd.shape[1], H, D).contiguous()
+    out = B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    # probabilities are rounded to 11 significant bits and summed in the same rounded form
+    err = (out[0] - cd[None]).abs().max().item()
+    print("constant V, all rows: max|out - c| = %.3e (max|c| = %.2f)" % (err, float(np.abs(c).max())))
+    assert err <= 1e-4 * float(np.abs(c).max())
+
+
+def test_attention_mass_sums_to_one_for_every_row():
+    """V = one-hot of (key index mod D): channel d of the output is the attention mass on keys
+    congruent to d, so each output row sums to one."""
+    import torch
+
+    cfg = wl.CONFIGS["dit_14b"]
+    q, k, _ = wl.self_attn_inputs(cfg)
+    H, D = cfg["H"], cfg["D"]
+    qd, kd = to_dev(q), to_dev(k)
+    L = qd.shape[1]
+    onehot = torch.nn.functional.one_hot(torch.arange(L, device="cuda") % D, D).to(torch.bfloat16)
+    vd = onehot[None, :, None, :].expand(1, L, H, D).contiguous()
+    out = B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    s = out.double().sum(dim=-1)
+    dev = (s - 1.0).abs().max().item()
+    print("one-hot V, all rows: max|sum - 1| = %.3e; min output %.3e" % (dev, out.min().item()))
+    assert dev <= 1e-4 and out.min().item() >= 0.0
+
+
+def test_moving_the_origin_changes_nothing():
+    """The rotation makes scores depend on position differences only, so a common offset on all
+    positions leaves the result unchanged up to the rounding of the rotated operands: every row of
+    every head, offset (5, 7, 11), against the parity bar on the difference of two roundings."""
+    import torch
+
+    cfg = wl.CONFIGS["dit_14b"]
+    q, k, v = (to_dev(a) for a in wl.self_attn_inputs(cfg))
+    a = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32)
+    b = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32, origin=(5, 7, 11))
+    torch.cuda.synchronize()
+    rms = a.double().pow(2).mean().sqrt().item()
+    diff = (a - b).abs().max().item()
+    print("origin shift, all rows: max|a - b| / RMS = %.3e" % (diff / rms))
+    assert 0.0 < diff <= 2 * 2e-2 * rms  # not bit-identical (other angles), yet the same attention
+
+
+def test_cross_attention_ignores_padded_keys_for_every_row():
+    """cross_14b at full size: overwriting the padded keys and values with large numbers changes
+    no output bit, and constant values on the valid keys come back for every row."""
+    import torch
+
+    cfg = wl.CONFIGS["cross_14b"]
+    q, k, v, valid, _ = wl.cross_attn_inputs(cfg)
+    qd, kd, vd, md = to_dev(q), to_dev(k), to_dev(v), to_dev(valid)
+    base = B.dit_cross_attn_forward(qd, kd, vd, md)
+    pad = (md == 0)[:, :, None, None]
+    k2 = torch.where(pad, torch.full_like(kd, 3.0e4), kd)
+    v2 = torch.where(pad, torch.full_like(vd, -3.0e4), vd)
+    loud = B.dit_cross_attn_forward(qd, k2, v2, md)
+    torch.cuda.synchronize()
+    assert torch.equal(base.view(torch.int16), loud.view(torch.int16))
+    H, D = cfg["H"], cfg["D"]
+    c = torch.from_numpy(wl.bf16_bits_to_f32(wl.normal((H, D), cfg["seed"], 5, "bf16"))).cuda()
+    vc = torch.where(pad, torch.full_like(vd, -3.0e4), c.to(torch.bfloat16)[None, None].expand_as(vd))
+    for split in (0, cfg["n_text"]):
+        out = B.dit_cross_attn_forward(qd, kd, vc, md, out_dtype=torch.float32, split=split)
+        torch.cuda.synchronize()
+        want = c[None, None] * (2.0 if split else 1.0)  # two softmaxes, each returns c
+        err = (out - want).abs().max().item()
+        print("cross constant V (split=%d), all rows: max|out - c| = %.3e" % (split, err))
+        assert err <= 1e-4 * c.abs().max().item()
