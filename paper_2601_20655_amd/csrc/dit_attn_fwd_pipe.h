@@ -15,6 +15,8 @@
 // per-score subtraction disappears from the vector ALU.  When a row's maximum has to move (rare,
 // thresholded), the accumulator, the row sum and the pending score tile are shifted together.
 #pragma once
+#include <type_traits>
+
 #include "dit_attn_fwd.h"
 
 // Schedule constants of the pipelined kernel (overridable at build time for tuning sweeps).
@@ -31,11 +33,8 @@
 #ifndef DIT_PIPE_DMA_DUTY
 #define DIT_PIPE_DMA_DUTY 0  // 8-wavefront workgroups: wavefronts 0-3 / 4-7 take turns streaming the whole tile pair
 #endif
-#ifndef DIT_PIPE_KSTAGES
-#define DIT_PIPE_KSTAGES 2  // K' buffers in LDS; 3 (where they fit) streams a tile one iteration earlier: measured 2-5 % slower
-#endif
-#ifndef DIT_PIPE_KPREFETCH
-#define DIT_PIPE_KPREFETCH 1  // with three K' buffers: read the next tile's first fragments ahead of the barrier
+#ifndef DIT_PIPE_STAGGER
+#define DIT_PIPE_STAGGER 1  // 8-wavefront workgroups: wavefronts 4-7 run half an iteration behind wavefronts 0-3
 #endif
 #ifndef DIT_PIPE_BALANCED
 #define DIT_PIPE_BALANCED 1  // move 6 of the 16 softmax slices from part A into part B (32-row wavefronts, d128)
@@ -70,15 +69,15 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     return r;
 }
 
-// K' buffers in LDS: DIT_PIPE_KSTAGES, but never three unless the workgroups of a CU (one of 8
-// wavefronts, two of 4) then still fit its 160 KiB.
-template <int D, int NW>
-constexpr int pipe_k_stages() {
-    return (5 * TileGeom<D>::PART_KIB * (NW == 8 ? 1 : 2) <= 160) ? DIT_PIPE_KSTAGES : 2;
-}
+// Staggered form (8 wavefronts, one workgroup per CU): the two wavefronts of a SIMD run half an
+// iteration apart, so one of them has matrix work while the other goes through the scalar end of
+// its iteration; a V^T tile is then read in two consecutive barrier intervals and needs three
+// buffers.
+template <int NW>
+constexpr bool pipe_staggered() { return NW == 8 && DIT_PIPE_STAGGER; }
 template <int D, int NW>
 constexpr int pipe_lds_bytes() {
-    return (pipe_k_stages<D, NW>() + 2) * TileGeom<D>::PART_KIB * 1024;
+    return (2 + (pipe_staggered<NW>() ? 3 : 2)) * TileGeom<D>::PART_KIB * 1024;
 }
 
 // The sequence one workgroup works on: which query tile of which (sequence, head), and where that
@@ -104,14 +103,12 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     constexpr int NI = G::PART_KIB / NW;  // full rounds of wavefront-wide 1 KiB loads per tile part
     static_assert(G::PART_KIB - NW * NI == 2, "two odd pieces per tile part");
 
-    // K' tiles sit in KST LDS buffers, V^T tiles in two.  With three K' buffers a tile is resident one
-    // whole iteration before its scores are computed, so its first operand fragments can be read
-    // ahead of the end-of-iteration barrier instead of after it.
-    constexpr int KST = pipe_k_stages<D, NW>();
+    constexpr bool STAG = pipe_staggered<NW>();
+    constexpr int VST = STAG ? 3 : 2;  // V^T buffers
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS map: K buffers, then V buffers 0/1
+    // LDS map: K buffers 0/1, then the V buffers
     uint8_t* const kbuf = smem;
-    uint8_t* const vbuf = smem + KST * G::K_BYTES;
+    uint8_t* const vbuf = smem + 2 * G::K_BYTES;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -305,34 +302,37 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
     // tile-streaming loads: spread over part A when they all fit before its end, else up front
-    constexpr int DSTEP = (DIT_PIPE_DSTEP > 0 && DIT_PIPE_DSTEP * (NDMA - 1) < NA && !(NW == 8 && DIT_PIPE_DMA_DUTY))
+    constexpr int DSTEP = (DIT_PIPE_DSTEP > 0 && DIT_PIPE_DSTEP * (NDMA - 1) < NA && !(NW == 8 && DIT_PIPE_DMA_DUTY) && !STAG)
                               ? DIT_PIPE_DSTEP : 0;
     constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4;
 
-    // Fragments 0..LA-1 of the K' tile the next iteration multiplies, read before the barrier (KST == 3).
-    constexpr bool KPRE = KST == 3 && DIT_PIPE_KPREFETCH;
-    u32x4 kpre[KPRE ? LA : 1];
-    auto next_slot = [](int s) { return s + 1 == KST ? 0 : s + 1; };
+    // Wavefronts of the late half (staggered form) pass the workgroup barrier between the two parts
+    // of an iteration, the others at its end; both issue their tile loads right after their barrier.
+    const bool late = STAG && wave >= NW / 2;
+    auto next_vslot = [](int s) { return s + 1 == VST ? 0 : s + 1; };
+    // loads of barrier interval j: K'(j + 2) over K'(j), V^T(j + 1) into the buffer after V^T(j)'s
+    auto dma_interval = [&](int j, int vs) { dma_tiles(j + 2, j & 1, j + 1, next_vslot(vs)); };
 
-    // s = j % KST: K'(j + KST) streams into buffer s, K'(j + 1) sits in the next one.
-    auto iteration = [&](f32x16 (&Sc)[2][QB], f32x16 (&Sn)[2][QB], int j, int s) {
-        const int kcur = next_slot(s);
-        const uint8_t* kt = kbuf + kcur * G::K_BYTES + kread_off;
-        const uint8_t* vt = vbuf + (j & 1) * G::V_BYTES + vread_off;
+    // vs = j % VST, the buffer V^T(j) sits in
+    // LATE (a compile-time tag) selects where the barrier sits; each half runs its own copy of the
+    // loop so that an iteration stays one straight-line block.
+    auto iteration = [&](auto late_tag, f32x16 (&Sc)[2][QB], f32x16 (&Sn)[2][QB], int j, int vs) {
+        constexpr bool LATE = decltype(late_tag)::value;
+        const uint8_t* kt = kbuf + ((j + 1) & 1) * G::K_BYTES + kread_off;
+        const uint8_t* vt = vbuf + vs * G::V_BYTES + vread_off;
         auto kfrag = [&](int f) { return *reinterpret_cast<const u32x4*>(kt + (f & 1) * 32 * G::KROW + (f >> 1) * 32); };
         auto vfrag = [&](int g) { return *reinterpret_cast<const u32x4*>(vt + (g % NDB) * 32 * G::VROW + (g / NDB) * 32); };
 
         // ---- part A: S(j+1) on MFMA, P(j) and row sums on VALU ----
         u32x4 kf[2 * NKS], vf[4 * NDB];
 #pragma unroll
-        for (int f = 0; f < LA; ++f) {
-            if constexpr (KPRE) kf[f] = kpre[f];
-            else kf[f] = kfrag(f);
-        }
-        if constexpr (NW == 8 && DIT_PIPE_DMA_DUTY) {
-            dma_tiles_duty(j, j + KST, s, j + 1, (j + 1) & 1);
+        for (int f = 0; f < LA; ++f) kf[f] = kfrag(f);
+        if constexpr (STAG) {
+            if constexpr (!LATE) dma_interval(j, vs);
+        } else if constexpr (NW == 8 && DIT_PIPE_DMA_DUTY) {
+            dma_tiles_duty(j, j + 2, j & 1, j + 1, (j + 1) & 1);
         } else if constexpr (DSTEP == 0) {
-            dma_tiles(j + KST, s, j + 1, (j + 1) & 1);
+            dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
         }
 
         uint32_t Pd[QB][16];
@@ -361,7 +361,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             // the last steps of part A fetch the first V^T fragments of part B
             if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
             if constexpr (DSTEP > 0) {
-                if (t % DSTEP == 0 && t / DSTEP < NDMA) dma_piece(t / DSTEP, j + KST, s, j + 1, (j + 1) & 1);
+                if (t % DSTEP == 0 && t / DSTEP < NDMA) dma_piece(t / DSTEP, j + 2, j & 1, j + 1, next_vslot(vs));
             }
             Sn[kb][qb] = mfma32<QK_OP>(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb]);
             if constexpr (BAL) {
@@ -375,6 +375,14 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
                     pack_slice(c);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        if constexpr (LATE) {  // the late half's barrier; its loads for the next interval follow at once
+            dma_wait_and_sync();
+            // (unconditional, to keep the iteration one block: past the end the last tile is
+            // fetched again into buffers nobody reads, and awaited before the wavefront leaves)
+            dma_interval(j + 1, next_vslot(vs));
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -416,14 +424,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         for (int qb = 0; qb < QB; ++qb)
             mx_new[qb] = max_across_halves(fmaxf(max3(pm[qb][0], pm[qb][1], pm[qb][2]), pm[qb][3]));
         bool need = any_row_needs_shift();
-        if constexpr (KPRE) {
-            // K'(j + 2) landed an iteration ago: its first fragments travel while the workgroup gathers
-            const uint8_t* kn = kbuf + next_slot(kcur) * G::K_BYTES + kread_off;
-#pragma unroll
-            for (int f = 0; f < LA; ++f)
-                kpre[f] = *reinterpret_cast<const u32x4*>(kn + (f & 1) * 32 * G::KROW + (f >> 1) * 32);
-        }
-        dma_wait_and_sync();
+        if constexpr (!LATE) dma_wait_and_sync();
         // rare paths, outside the pipelined block
         const uint64_t mnext = mask_of(j + 1);
         if (mnext != ~0ull) {
@@ -439,7 +440,6 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     if (n_steps > 0) {
         dma_tiles(0, 0, 0, 0);
         dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
-        if constexpr (KST == 3) dma_tiles(2, 2, 0, 1);
     }
 
     // ---- Q: load, rotate, fold scale*log2(e), round once, keep as B operands ----
@@ -470,13 +470,10 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     dma_wait_and_sync();
     f32x16 S0[2][QB], S1[2][QB];
     qk_tile(S0, 0);
-    if constexpr (KPRE) {
-        const uint8_t* kn = kbuf + G::K_BYTES + kread_off;
-#pragma unroll
-        for (int f = 0; f < LA; ++f)
-            kpre[f] = *reinterpret_cast<const u32x4*>(kn + (f & 1) * 32 * G::KROW + (f >> 1) * 32);
+    __syncthreads();  // every wavefront has read K'(0) before iteration 0 streams K'(2) over it
+    if constexpr (STAG) {
+        if (late) dma_interval(0, 0);
     }
-    __syncthreads();  // every wavefront has read K'(0) before iteration 0 streams the next tile over it
     if (mask_of(0) != ~0ull) mask_apply(S0, mask_of(0));
     row_max(S0);  // finite: every listed tile holds at least one valid key
 #pragma unroll
@@ -490,14 +487,22 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         }
     }
 
-    int j = 0, slot = 0;
-    for (; j + 1 < n_steps; j += 2) {
-        iteration(S0, S1, j, slot);
-        slot = next_slot(slot);
-        iteration(S1, S0, j + 1, slot);
-        slot = next_slot(slot);
+    auto key_loop = [&](auto late_tag) {
+        int j = 0, vs = 0;
+        for (; j + 1 < n_steps; j += 2) {
+            iteration(late_tag, S0, S1, j, vs);
+            vs = next_vslot(vs);
+            iteration(late_tag, S1, S0, j + 1, vs);
+            vs = next_vslot(vs);
+        }
+        if (j < n_steps) iteration(late_tag, S0, S1, j, vs);
+    };
+    if (late) {
+        key_loop(std::true_type{});
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        key_loop(std::false_type{});
     }
-    if (j < n_steps) iteration(S0, S1, j, slot);
     }
 
     // ---- epilogue ----
