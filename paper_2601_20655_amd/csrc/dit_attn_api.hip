@@ -200,6 +200,7 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
     const int bq = 32 * pl->fl.nw * pl->fl.qb;
     pl->nQT = (int)((L + bq - 1) / bq);
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
+    if ((int64_t)pl->nKT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;  // one pre-pack workgroup each
     pl->table_entries = p->T * (p->d_t / 2) + p->Hg * (p->d_h / 2) + p->Wg * (p->d_w / 2);
     pl->tab_off = 0;
     pl->tiles_off = round_up((size_t)pl->table_entries * sizeof(float2), kAlign);
@@ -342,6 +343,7 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     const int bq = 32 * pl->fl.nw * pl->fl.qb;
     pl->nQT = (p->Lq + bq - 1) / bq;
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
+    if ((int64_t)pl->nKT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
     // workspace: per-tile key masks, compacted list of non-empty tiles, their count, tile images
     pl->mask_off = 0;
     pl->list_off = round_up((size_t)p->B * pl->nKT * sizeof(uint64_t), kAlign);

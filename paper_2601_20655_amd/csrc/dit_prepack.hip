@@ -142,7 +142,8 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     using G = TileGeom<D>;
     __shared__ __attribute__((aligned(16))) uint16_t vs[kBK * (D + 2)];
     const int tid = threadIdx.x;
-    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // heads vary fastest: neighbouring workgroups read neighbouring 256-byte pieces of the same 64 tokens
+    const int h = blockIdx.x % a.H, jb = blockIdx.x / a.H, j = jb % a.nKT, b = jb / a.nKT;
     PackTile t;
     t.dst = a.tiles + ((size_t)(b * a.H + h) * a.nKT + j) * G::TILE_BYTES;
     t.k_off = (int64_t)b * a.sk_b + (int64_t)h * a.sk_h;
@@ -170,7 +171,7 @@ template <int D, int QK_OP, int PV_OP>
 __global__ void __launch_bounds__(kThreads) kv_prepack_varlen_kernel(const PackArgs a, const VarlenTable vt) {
     using G = TileGeom<D>;
     __shared__ __attribute__((aligned(16))) uint16_t vs[kBK * (D + 2)];
-    const int gj = blockIdx.x, h = blockIdx.y;
+    const int h = blockIdx.x % a.H, gj = blockIdx.x / a.H;
     int r = 0;
     while (r + 1 < vt.n && gj >= vt.r[r + 1].tile0) ++r;
     const ReqDesc& q = vt.r[r];
@@ -218,14 +219,14 @@ hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s) {
 
 template <int D, int QK_OP, int PV_OP>
 static hipError_t launch_prepack_inst(const PackArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL((kv_prepack_kernel<D, QK_OP, PV_OP>), dim3(a.nKT, a.H, a.B), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((kv_prepack_kernel<D, QK_OP, PV_OP>), dim3((unsigned)((int64_t)a.H * a.nKT * a.B)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, hipStream_t s) {
 #define DIT_PACKV_CASE(DD, QK, PV)                                                                        \
     if (D == DD && qk_op == QK && pv_op == PV) {                                                           \
-        hipLaunchKernelGGL((kv_prepack_varlen_kernel<DD, QK, PV>), dim3(vt.total_tiles, a.H), dim3(kThreads), 0, \
+        hipLaunchKernelGGL((kv_prepack_varlen_kernel<DD, QK, PV>), dim3((unsigned)((int64_t)a.H * vt.total_tiles)), dim3(kThreads), 0, \
                            s, a, vt);                                                                      \
         return hipGetLastError();                                                                          \
     }
