@@ -8,7 +8,10 @@ explicit normalised-exponential loop in Python floats / numpy longdouble.
 """
 import cmath
 import itertools
+import json
 import math
+import os
+import sys
 
 import numpy as np
 import pytest
@@ -462,3 +465,52 @@ def test_normed_attention_pins(rng):
         kn = k[0, :, h] / np.sqrt(msk + 1e-2) * 2 * g[h]
         ref, _, _ = brute_self_attn(qn, kn, v[0, :, h], grid, SPLITS[D])
         np.testing.assert_allclose(c[0, :, h], ref, rtol=0, atol=1e-12)
+
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def test_hand_worked_cases_from_golden_folder():
+    """Cases with exact, pencil-and-paper expected values (derivations in the fixture)."""
+    cases = json.load(open(os.path.join(GOLDEN, "hand_worked_cases.json")))
+    for name, c in cases.items():
+        if c["kind"] in ("cross", "decoupled"):
+            q = np.array(c["q"], dtype=np.float64)[None, :, None, :]
+            k = np.array(c["k"], dtype=np.float64)[None, :, None, :]
+            v = np.array(c["v"], dtype=np.float64)[None, :, None, :]
+            valid = np.array(c["valid"], dtype=np.uint8)[None]
+            if c["kind"] == "cross":
+                out, lse = oracle.cross_attn(q, k, v, valid, scale=c["scale"], want_lse=True)
+                np.testing.assert_allclose(lse[0, 0], c["lse"], rtol=0, atol=1e-14, err_msg=name)
+            else:
+                out = oracle.cross_attn_decoupled(q, k, v, c["split"], valid, scale=c["scale"])
+            np.testing.assert_allclose(out[0, :, 0], c["out"], rtol=0, atol=1e-15, err_msg=name)
+        elif c["kind"] == "packed":
+            q, k, v = (np.array(c[n], dtype=np.float64)[:, None, :] for n in ("q", "k", "v"))
+            out = oracle.self_attn_packed(q, k, v, [tuple(g) for g in c["grids"]], tuple(c["split"]))
+            np.testing.assert_allclose(out[:, 0], c["out"], rtol=0, atol=1e-15, err_msg=name)
+        elif c["kind"] == "rmsnorm":
+            x = np.array(c["x"], dtype=np.float64)[None, None, :]
+            for cc in c["cases"]:
+                g = None if cc["gamma"] is None else np.array(cc["gamma"])[None]
+                y = oracle.qk_rmsnorm(x, g, cc["eps"], "head")
+                np.testing.assert_allclose(y[0, 0], cc["y"], rtol=0, atol=2e-16, err_msg=name)
+        else:
+            raise AssertionError("unknown case kind in %s" % name)
+
+
+def test_oracle_matches_its_stored_regression_values():
+    """The stored file was written by tests/golden/make_golden.py from the oracle alone; a change
+    of the oracle's arithmetic shows up here first."""
+    sys.path.insert(0, GOLDEN)
+    import make_golden
+
+    stored = [l.rstrip("\n") for l in open(os.path.join(GOLDEN, "oracle_tiny_regression.txt")) if not l.startswith("#")]
+    now = make_golden.values()
+    assert len(stored) == len(now)
+    for a, b in zip(stored, now):
+        ta, tb = a.split(), b.split()
+        assert ta[:4] == tb[:4]
+        fa = np.array([float(x) for x in ta if "e" in x and x[0] in "-0123456789"])
+        fb = np.array([float(x) for x in tb if "e" in x and x[0] in "-0123456789"])
+        np.testing.assert_allclose(fa, fb, rtol=1e-12, atol=1e-15)
