@@ -165,6 +165,25 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
     const int tail = a.Lk - (a.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
     auto tile_of = [&](int j) -> int { return tlist ? tlist[j] : j; };
 
+    // ---- Q rows are requested first (16-bit inputs: raw, converted below): they come from HBM and
+    // need nothing but the workgroup's coordinates, while the first tile needs the tile list ----
+    u32x4 Qf[QB][NKS];
+    u32x4 qraw[QB][NKS];
+    int qrow[QB];
+    int64_t qbase[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
+        const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
+        qbase[qb] = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        if (!a.in_f32) {
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                qraw[qb][ks] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + qbase[qb] +
+                                                              8 * (2 * ks + half));
+        }
+    }
+
     // the first tile is on its way while the Q prologue waits for its own loads
     int tile = 0;
     if (n_steps > 0) {
@@ -172,14 +191,11 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
         issue_loads(tile);
     }
 
-    // ---- Q prologue: load, rotate, fold scale*log2(e), round once, keep as B operands ----
-    u32x4 Qf[QB][NKS];
-    int qrow[QB];
+    // ---- Q prologue: rotate, fold scale*log2(e), round once, keep as B operands ----
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
         const int qr = qrow[qb] < a.Lq ? qrow[qb] : a.Lq - 1;
-        const int64_t base = (int64_t)b * a.sq_b + (int64_t)qr * a.sq_t + (int64_t)h * a.sq_h;
+        const int64_t base = qbase[qb];
         int pt = 0, ph = 0, pw = 0;
         if (a.tab) token_pos(qr, a.rg, pt, ph, pw);
         float rs = 1.f;
@@ -188,7 +204,8 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
         for (int ks = 0; ks < NKS; ++ks) {
             const int c = 2 * ks + half;
             float x[8];
-            load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.in_f32) load8(a.q, base + 8 * c, 1, x);
+            else widen8(qraw[qb][ks], x);
             if (a.qn.mode) norm8(x, a.qn, rs, h, D, c);
             if (a.tab) rope8(x, c, a.rg, a.tab, pt, ph, pw);
 #pragma unroll
