@@ -27,12 +27,6 @@
 #define DIT_PIPE_PRE 4  // exp slices issued before the first MFMA of an iteration (covers LDS latency)
 #endif
 
-#ifndef DIT_PIPE_DSTEP
-#define DIT_PIPE_DSTEP 0  // one tile-streaming load every this many MFMA steps of part A; 0 (all up front) measured best
-#endif
-#ifndef DIT_PIPE_DMA_DUTY
-#define DIT_PIPE_DMA_DUTY 0  // 8-wavefront workgroups: wavefronts 0-3 / 4-7 take turns streaming the whole tile pair
-#endif
 #ifndef DIT_PIPE_STAGGER
 #define DIT_PIPE_STAGGER 1  // 8-wavefront workgroups: wavefronts 4-7 run half an iteration behind wavefronts 0-3
 #endif
@@ -144,8 +138,8 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
     };
     // One tile pair = NDMA loads per wavefront: pieces 2i (K part) and 2i+1 (V part) for i < NI, then
-    // the odd piece.  dma_piece(i, ...) issues load i alone, so the loads can either go out together
-    // at the top of an iteration or be spread over part A (DIT_PIPE_DSTEP).
+    // the odd piece.  They go out together right after a barrier: spreading them over part A, or
+    // letting the two halves of the workgroup take turns, measured within 1 %.
     constexpr int NDMA = 2 * NI + 1;
     auto dma_piece = [&](int i, int tk, int kb_, int tv, int vb_) {
         tk = tile_of(tk);
@@ -170,29 +164,6 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) dma_piece(i, tk, kb_, tv, vb_);
-    };
-    // Duty form for 8 wavefronts: one wavefront per SIMD (0-3 on even steps, 4-7 on odd steps)
-    // streams the whole tile pair, 9 loads each at d128, while its SIMD neighbour keeps the
-    // matrix pipe busy.
-    auto dma_tiles_duty = [&](int j, int tk, int kb_, int tv, int vb_) {
-        if ((wave >> 2) != (j & 1)) return;
-        tk = tile_of(tk);
-        tv = tile_of(tv);
-        const uint8_t* ksrc = tiles + (size_t)tk * G::TILE_BYTES;
-        const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
-        uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
-        uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
-        const int w4 = wave & 3;
-#pragma unroll
-        for (int i = 0; i < G::PART_KIB / 4; ++i) {
-            const int c = (w4 + 4 * i) * 1024;
-            __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
-        }
-        const int c = (4 * (G::PART_KIB / 4) + (w4 & 1)) * 1024;
-        const uint8_t* osrc = w4 < 2 ? ksrc : vsrc;
-        uint8_t* odst = w4 < 2 ? kdst : vdst;
-        __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
     };
     auto dma_wait_and_sync = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -301,9 +272,6 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     constexpr int PRE = DIT_PIPE_PRE;        // exp slices issued before the first MFMA, covering LDS latency
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
-    // tile-streaming loads: spread over part A when they all fit before its end, else up front
-    constexpr int DSTEP = (DIT_PIPE_DSTEP > 0 && DIT_PIPE_DSTEP * (NDMA - 1) < NA && !(NW == 8 && DIT_PIPE_DMA_DUTY) && !STAG)
-                              ? DIT_PIPE_DSTEP : 0;
     constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4;
 
     // Wavefronts of the late half (staggered form) pass the workgroup barrier between the two parts
@@ -327,13 +295,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         u32x4 kf[2 * NKS], vf[4 * NDB];
 #pragma unroll
         for (int f = 0; f < LA; ++f) kf[f] = kfrag(f);
-        if constexpr (STAG) {
-            if constexpr (!LATE) dma_interval(j, vs);
-        } else if constexpr (NW == 8 && DIT_PIPE_DMA_DUTY) {
-            dma_tiles_duty(j, j + 2, j & 1, j + 1, (j + 1) & 1);
-        } else if constexpr (DSTEP == 0) {
-            dma_tiles(j + 2, j & 1, j + 1, (j + 1) & 1);
-        }
+        if constexpr (!LATE) dma_interval(j, vs);
 
         uint32_t Pd[QB][16];
         float ls[QB][2];
@@ -360,9 +322,6 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             if (qb == 0 && f + LA < 2 * NKS) kf[f + LA] = kfrag(f + LA);
             // the last steps of part A fetch the first V^T fragments of part B
             if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
-            if constexpr (DSTEP > 0) {
-                if (t % DSTEP == 0 && t / DSTEP < NDMA) dma_piece(t / DSTEP, j + 2, j & 1, j + 1, next_vslot(vs));
-            }
             Sn[kb][qb] = mfma32<QK_OP>(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb]);
             if constexpr (BAL) {
                 if (bal_a_exp(t) >= 0) exp_slice(bal_a_exp(t));
