@@ -81,7 +81,8 @@ enum {
     DIT_FLAG_SMALL_WORKGROUP = 1u << 9,
     /* Cross-attention runs the plain kernel by default: with a dozen key tiles per query tile its
      * shorter prologue beats the pipelined kernel's better steady state (measured).  This flag
-     * selects the pipelined kernel there too.  No effect on self-attention. */
+     * selects the pipelined kernel there too (at most 64 key tiles, i.e. Lk <= 4096 for the joint
+     * form, else DIT_ERR_UNSUPPORTED).  No effect on self-attention. */
     DIT_FLAG_PIPELINED_SCHEDULE = 1u << 10
 };
 

@@ -332,6 +332,8 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     pl->nKT = pl->nTA + (p->Lk - pl->split + dit::kBK - 1) / dit::kBK;
     if (pl->split > 0 && (pl->fl.pipelined || pl->fl.qb == 2)) return DIT_ERR_UNSUPPORTED;
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
+    // the pipelined kernel keeps the list of non-empty tiles in the 64 lanes of a wavefront
+    if (pl->fl.pipelined && pl->nKT > 64) return DIT_ERR_UNSUPPORTED;
     if (!pl->fl.pipelined) pl->fl.simple = true;  // cross-attention default: the plain kernel
     if (pl->fl.simple || pl->fl.qb == 2) {
         pl->fl.nw = 4;

@@ -122,19 +122,32 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     const uint8_t* const tiles = pv.tiles;  // wavefront-uniform
     const uint32_t lane_off = lane * 16;
     // The loop runs over "steps"; step j works on tile tile_of(j).  Without a list that is tile j.
-    const int* const tlist = LISTED ? a.tile_list + (size_t)b * pv.nKT : nullptr;
-    const uint64_t* const tmask = LISTED ? a.tile_mask + (size_t)b * pv.nKT : nullptr;
+    // With a list (at most 64 entries, checked by the host), lane i of every wavefront keeps entry i
+    // and its key mask in registers and a step reads them with v_readlane: no memory operation in
+    // the loop, whose waits on LDS operand reads would otherwise have to drain scalar loads too.
     const int n_steps = LISTED ? a.tile_count[b] : pv.nKT;
     const int last = n_steps - 1;
     const int tail = pv.Lk - (pv.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
+    int v_tile = 0;
+    uint32_t v_mask_lo = ~0u, v_mask_hi = ~0u;
+    if constexpr (LISTED) {
+        if (lane < n_steps) {
+            v_tile = a.tile_list[(size_t)b * pv.nKT + lane];
+            const uint64_t m = a.tile_mask[(size_t)b * pv.nKT + v_tile];
+            v_mask_lo = (uint32_t)m;
+            v_mask_hi = (uint32_t)(m >> 32);
+        }
+    }
     auto tile_of = [&](int j) -> int {
         j = j < last ? j : last;  // past the end: the last tile again (fetched into a buffer nobody reads)
-        if constexpr (LISTED) return tlist[j];
+        if constexpr (LISTED) return __builtin_amdgcn_readlane(v_tile, j);
         return j;
     };
     auto mask_of = [&](int j) -> uint64_t {
         if (j > last) return ~0ull;
-        if constexpr (LISTED) return tmask[tlist[j]];
+        if constexpr (LISTED)
+            return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)v_mask_hi, j) << 32) |
+                   (uint32_t)__builtin_amdgcn_readlane((int)v_mask_lo, j);
         return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
     };
     // One tile pair = NDMA loads per wavefront: pieces 2i (K part) and 2i+1 (V part) for i < NI, then

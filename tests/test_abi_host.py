@@ -116,6 +116,10 @@ def test_self_attn_rejects_bad_arguments():
 
 
 def test_cross_attn_rejects_bad_arguments():
+    # the pipelined form keeps its tile list in the 64 lanes of a wavefront
+    assert call_cross(cross_params(Lk=4097, flags=B.DIT_FLAG_PIPELINED_SCHEDULE)) == B.DIT_ERR_UNSUPPORTED
+    assert B.dit_cross_attn_workspace_bytes(cross_params(Lk=4096, flags=B.DIT_FLAG_PIPELINED_SCHEDULE)) > 0
+    assert B.dit_cross_attn_workspace_bytes(cross_params(Lk=4097)) > 0
     assert call_cross(cross_params(Lk=0)) == B.DIT_ERR_INVALID_ARG
     assert call_cross(cross_params(D=32)) == B.DIT_ERR_UNSUPPORTED
     assert call_cross(cross_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)) == B.DIT_ERR_UNSUPPORTED
