@@ -113,8 +113,24 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     rg.Hg = pv.Hg;
     rg.Wg = pv.Wg;
 
-    u32x4 Qf[QB][NKS];  // filled after the first tiles have been requested
+    // Query rows (16-bit inputs) are requested before anything else: they come from HBM and need
+    // only the workgroup's coordinates, while the first tiles wait for the tile list.  They are
+    // converted into Qf after the first tiles have been requested.
+    u32x4 Qf[QB][NKS];
+    u32x4 qraw[QB][NKS];
     int qrow[QB];
+    if (!a.in_f32) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const int row = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
+            const int qr = row < pv.Lq ? row : pv.Lq - 1;
+            const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                qraw[qb][ks] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + base +
+                                                              8 * (2 * ks + half));
+        }
+    }
 
     // ---- tile streaming.  A tile part is PART_KIB pieces of 1 KiB (64 lanes x 16 bytes).  Wavefront
     // w moves pieces w, w+NW, ... of both parts; the two odd pieces of the K part go to wavefronts
@@ -414,7 +430,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
     }
 
-    // ---- Q: load, rotate, fold scale*log2(e), round once, keep as B operands ----
+    // ---- Q: rotate, fold scale*log2(e), round once, keep as B operands ----
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         qrow[qb] = qt * BQ + wave * (32 * QB) + qb * 32 + l32;
@@ -428,7 +444,8 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         for (int ks = 0; ks < NKS; ++ks) {
             const int c = 2 * ks + half;
             float x[8];
-            load8(a.q, base + 8 * c, a.in_f32, x);
+            if (a.in_f32) load8(a.q, base + 8 * c, 1, x);
+            else widen8(qraw[qb][ks], x);
             if (a.qn.mode) norm8(x, a.qn, rs, pv.h, D, c);
             if (a.tab) rope8(x, c, rg, a.tab, pt, ph, pw);
 #pragma unroll
