@@ -119,3 +119,18 @@ def test_full_size_mixed_batch_sampled_rows():
         worst = max(worst, compare(got, ref, what="varlen_14b request %d %s" % (i, (g,))))
         n0 += L
     print("varlen_14b worst max|err|/RMS = %.3e" % worst)
+
+
+def test_sixty_four_small_requests_odd_head_count():
+    """The request table at its limit (64 entries) with 5 heads, so that the per-XCD queues get
+    unequal numbers of (request, head) pairs and some workgroups find their queue empty; grids
+    from 1 to 150 tokens, d64, fp32 inputs."""
+    import torch
+
+    grids = [(1 + k % 3, 1 + k % 5, 1 + (7 * k) % 10) for k in range(64)]
+    cfg = dict(kind="varlen", grids=grids, H=5, D=64, split=(22, 20, 22), dtype="f32", seed=777)
+    q, k, v = wl.varlen_attn_inputs(cfg)
+    ref = oracle.self_attn_packed(q, k, v, grids, cfg["split"])
+    for flags in sorted(SHAPES.values()):
+        out = run_varlen(cfg, q, k, v, flags=flags, out_dtype=torch.float32)
+        compare_per_request(to_f64(out), ref, grids, "64 requests flags=%d" % flags)
