@@ -218,3 +218,28 @@ def test_python_wrappers_refuse_host_tensors():
         B.dit_attn_forward(q, q, q, (2, 3, 4), (44, 42, 42))
     with pytest.raises(ValueError):
         B.dit_cross_attn_forward(q, q, q)
+
+
+@pytest.mark.parametrize("compiler,std", [("gcc", "-std=c99"), ("gcc", "-std=c11"), ("g++", "-std=c++11")])
+def test_public_header_is_plain_c(compiler, std, tmp_path):
+    """The boundary is a C ABI: the header must compile on its own as C99, C11 and C++ with no
+    HIP or torch header in sight, and the structs must have the layout the Python binding mirrors."""
+    import shutil
+    import subprocess
+
+    if shutil.which(compiler) is None:
+        pytest.skip(compiler + " not found")
+    src = tmp_path / ("t.c" if compiler == "gcc" else "t.cpp")
+    src.write_text(
+        '#include "dit_attn.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        '  printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(dit_strides), sizeof(dit_qk_norm), sizeof(dit_self_attn_params),\n'
+        "         sizeof(dit_cross_attn_params), sizeof(dit_varlen_attn_params), sizeof(dit_grid));\n"
+        "  return 0;\n}\n")
+    exe = str(tmp_path / "t")
+    subprocess.check_call([compiler, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", exe])
+    sizes = [int(x) for x in subprocess.check_output([exe]).split()]
+    assert sizes == [ctypes.sizeof(B.dit_strides), ctypes.sizeof(B.dit_qk_norm), ctypes.sizeof(B.dit_self_attn_params),
+                     ctypes.sizeof(B.dit_cross_attn_params), ctypes.sizeof(B.dit_varlen_attn_params),
+                     ctypes.sizeof(B.dit_grid)]
