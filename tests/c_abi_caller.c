@@ -1,0 +1,177 @@
+/* A C99 caller of the library's C ABI, with no Python and no C++ in between: device buffers from the
+ * HIP runtime's C API, one self-attention and one masked cross-attention through include/dit_attn.h,
+ * results compared with the CPU oracle (oracle/dit_oracle.c, linked in) to the parity bar.
+ * Built by paper_2601_20655_amd/build.py (build_c_caller), run by tests/test_gpu_c_caller.py. */
+#define __HIP_PLATFORM_AMD__ 1
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "dit_attn.h"
+
+int oracle_self_attn(const void *q, const void *k, const void *v, int32_t dtype, int32_t B, int32_t H,
+                     int32_t D, const int32_t grid[3], const int32_t origin[3], const int32_t split[3],
+                     double base, double scale, const int64_t *rows, int64_t n_rows, double *out,
+                     double *lse, double *probs, int32_t pb, int32_t ph);
+int oracle_cross_attn(const void *q, const void *k, const void *v, const uint8_t *kv_valid, int32_t dtype,
+                      int32_t B, int32_t H, int32_t D, int64_t Lq, int64_t Lk, double scale,
+                      const int64_t *rows, int64_t n_rows, double *out, double *lse, double *probs,
+                      int32_t pb, int32_t ph);
+
+#define CHECK_HIP(x)                                                                  \
+    do {                                                                              \
+        hipError_t e_ = (x);                                                          \
+        if (e_ != hipSuccess) {                                                       \
+            fprintf(stderr, "%s failed: %s\n", #x, hipGetErrorString(e_));            \
+            return 2;                                                                 \
+        }                                                                             \
+    } while (0)
+
+static uint64_t rng_state = 0x2601206550ull;
+static float gauss(void)
+{ /* sum of 12 uniforms - 6: close enough to N(0,1) for a stand-in activation */
+    float s = 0.f;
+    for (int i = 0; i < 12; ++i) {
+        rng_state = rng_state * 6364136223846793005ull + 1442695040888963407ull;
+        s += (float)(rng_state >> 40) / 16777216.0f;
+    }
+    return s - 6.0f;
+}
+
+static uint16_t *make_bf16(size_t n)
+{
+    uint16_t *p = (uint16_t *)malloc(n * 2);
+    for (size_t i = 0; i < n; ++i) {
+        float f = gauss();
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        u += 0x7fffu + ((u >> 16) & 1u); /* nearest even */
+        p[i] = (uint16_t)(u >> 16);
+    }
+    return p;
+}
+
+static void *to_device(const void *h, size_t bytes)
+{
+    void *d = NULL;
+    if (hipMalloc(&d, bytes) != hipSuccess) return NULL;
+    if (h && hipMemcpy(d, h, bytes, hipMemcpyHostToDevice) != hipSuccess) return NULL;
+    return d;
+}
+
+/* max |gpu - ref| / RMS(ref) */
+static double rel_err(const float *gpu, const double *ref, size_t n)
+{
+    double ss = 0, mx = 0;
+    for (size_t i = 0; i < n; ++i) {
+        ss += ref[i] * ref[i];
+        double e = fabs((double)gpu[i] - ref[i]);
+        if (e > mx) mx = e;
+    }
+    return mx / sqrt(ss / (double)n);
+}
+
+int main(void)
+{
+    int n_dev = 0;
+    CHECK_HIP(hipGetDeviceCount(&n_dev));
+    if (n_dev < 1) {
+        fprintf(stderr, "no GPU\n");
+        return 2;
+    }
+    printf("libdit_attn version %d\n", dit_attn_version());
+
+    /* ---- self-attention: grid 3 x 7 x 19 = 399 tokens, 2 heads, d128 ---- */
+    {
+        const int32_t B = 1, H = 2, D = 128, grid[3] = {3, 7, 19}, origin[3] = {0, 0, 0}, split[3] = {44, 42, 42};
+        const int64_t L = 399;
+        const size_t n = (size_t)B * L * H * D;
+        uint16_t *q = make_bf16(n), *k = make_bf16(n), *v = make_bf16(n);
+        void *dq = to_device(q, n * 2), *dk = to_device(k, n * 2), *dv = to_device(v, n * 2);
+        void *dout = to_device(NULL, n * 4);
+        if (!dq || !dk || !dv || !dout) return 2;
+
+        dit_self_attn_params p;
+        memset(&p, 0, sizeof(p));
+        p.B = B; p.H = H; p.D = D;
+        p.T = grid[0]; p.Hg = grid[1]; p.Wg = grid[2];
+        p.d_t = split[0]; p.d_h = split[1]; p.d_w = split[2];
+        p.rope_base = 10000.0f;
+        p.in_dtype = DIT_BF16; p.out_dtype = DIT_F32;
+        dit_strides s = {(int64_t)L * H * D, (int64_t)H * D, D};
+        p.sq = p.sk = p.sv = p.so = s;
+        size_t ws_bytes = dit_attn_workspace_bytes(&p);
+        void *ws = to_device(NULL, ws_bytes);
+        if (!ws_bytes || !ws) return 2;
+        dit_status st = dit_attn_forward(dq, dk, dv, dout, NULL, &p, ws, ws_bytes, NULL);
+        if (st != DIT_OK) {
+            fprintf(stderr, "dit_attn_forward: %s %s\n", dit_strerror(st), dit_last_hip_error());
+            return 1;
+        }
+        CHECK_HIP(hipDeviceSynchronize());
+        float *out = (float *)malloc(n * 4);
+        CHECK_HIP(hipMemcpy(out, dout, n * 4, hipMemcpyDeviceToHost));
+
+        int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * L);
+        for (int64_t i = 0; i < L; ++i) rows[i] = i;
+        double *ref = (double *)malloc(n * 8);
+        if (oracle_self_attn(q, k, v, 0, B, H, D, grid, origin, split, 10000.0, 0.0, rows, L, ref, NULL, NULL, 0, 0))
+            return 1;
+        double e = rel_err(out, ref, n);
+        printf("self-attention  max|err|/RMS = %.3e\n", e);
+        if (!(e < 2e-2)) return 1;
+        /* a bad call is refused before anything is launched */
+        p.d_w = 40;
+        if (dit_attn_forward(dq, dk, dv, dout, NULL, &p, ws, ws_bytes, NULL) != DIT_ERR_INVALID_ARG) return 1;
+        hipFree(dq); hipFree(dk); hipFree(dv); hipFree(dout); hipFree(ws);
+        free(q); free(k); free(v); free(out); free(rows); free(ref);
+    }
+
+    /* ---- cross-attention: 2 requests x 200 queries x 129 keys (96 text, padded, + 33 image) ---- */
+    {
+        const int32_t B = 2, H = 2, D = 128;
+        const int64_t Lq = 200, Lk = 129;
+        const size_t nq = (size_t)B * Lq * H * D, nk = (size_t)B * Lk * H * D;
+        uint16_t *q = make_bf16(nq), *k = make_bf16(nk), *v = make_bf16(nk);
+        uint8_t *valid = (uint8_t *)malloc((size_t)B * Lk);
+        const int text_len[2] = {37, 96};
+        for (int b = 0; b < B; ++b)
+            for (int m = 0; m < Lk; ++m) valid[b * Lk + m] = (uint8_t)(m < text_len[b] || m >= 96);
+        void *dq = to_device(q, nq * 2), *dk = to_device(k, nk * 2), *dv = to_device(v, nk * 2);
+        void *dvalid = to_device(valid, (size_t)B * Lk), *dout = to_device(NULL, nq * 4);
+        if (!dq || !dk || !dv || !dvalid || !dout) return 2;
+
+        dit_cross_attn_params p;
+        memset(&p, 0, sizeof(p));
+        p.B = B; p.H = H; p.D = D; p.Lq = (int32_t)Lq; p.Lk = (int32_t)Lk;
+        p.in_dtype = DIT_BF16; p.out_dtype = DIT_F32;
+        dit_strides sq = {Lq * H * D, (int64_t)H * D, D}, sk = {Lk * H * D, (int64_t)H * D, D};
+        p.sq = p.so = sq;
+        p.sk = p.sv = sk;
+        size_t ws_bytes = dit_cross_attn_workspace_bytes(&p);
+        void *ws = to_device(NULL, ws_bytes);
+        if (!ws_bytes || !ws) return 2;
+        dit_status st = dit_cross_attn_forward(dq, dk, dv, (const uint8_t *)dvalid, dout, NULL, &p, ws, ws_bytes, NULL);
+        if (st != DIT_OK) {
+            fprintf(stderr, "dit_cross_attn_forward: %s %s\n", dit_strerror(st), dit_last_hip_error());
+            return 1;
+        }
+        CHECK_HIP(hipDeviceSynchronize());
+        float *out = (float *)malloc(nq * 4);
+        CHECK_HIP(hipMemcpy(out, dout, nq * 4, hipMemcpyDeviceToHost));
+        int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * Lq);
+        for (int64_t i = 0; i < Lq; ++i) rows[i] = i;
+        double *ref = (double *)malloc(nq * 8);
+        if (oracle_cross_attn(q, k, v, valid, 0, B, H, D, Lq, Lk, 0.0, rows, Lq, ref, NULL, NULL, 0, 0)) return 1;
+        double e = rel_err(out, ref, nq);
+        printf("cross-attention max|err|/RMS = %.3e\n", e);
+        if (!(e < 2e-2)) return 1;
+        hipFree(dq); hipFree(dk); hipFree(dv); hipFree(dvalid); hipFree(dout); hipFree(ws);
+        free(q); free(k); free(v); free(valid); free(out); free(rows); free(ref);
+    }
+    printf("c caller ok\n");
+    return 0;
+}
