@@ -138,22 +138,14 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     const uint8_t* const tiles = pv.tiles;  // wavefront-uniform
     const uint32_t lane_off = lane * 16;
     // The loop runs over "steps"; step j works on tile tile_of(j).  Without a list that is tile j.
-    // With a list (at most 64 entries, checked by the host), lane i of every wavefront keeps entry i
-    // and its key mask in registers and a step reads them with v_readlane: no memory operation in
+    // With a list (at most 64 tiles, checked by the host), lane i of every wavefront keeps list entry i
+    // and the key mask of tile i in registers and a step reads them with v_readlane: no memory operation in
     // the loop, whose waits on LDS operand reads would otherwise have to drain scalar loads too.
     const int n_steps = LISTED ? a.tile_count[b] : pv.nKT;
     const int last = n_steps - 1;
     const int tail = pv.Lk - (pv.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
-    int v_tile = 0;
+    int v_tile = 0;  // filled in the prologue, after the first tiles have been requested
     uint32_t v_mask_lo = ~0u, v_mask_hi = ~0u;
-    if constexpr (LISTED) {
-        if (lane < n_steps) {
-            v_tile = a.tile_list[(size_t)b * pv.nKT + lane];
-            const uint64_t m = a.tile_mask[(size_t)b * pv.nKT + v_tile];
-            v_mask_lo = (uint32_t)m;
-            v_mask_hi = (uint32_t)(m >> 32);
-        }
-    }
     auto tile_of = [&](int j) -> int {
         j = j < last ? j : last;  // past the end: the last tile again (fetched into a buffer nobody reads)
         if constexpr (LISTED) return __builtin_amdgcn_readlane(v_tile, j);
@@ -161,18 +153,19 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     };
     auto mask_of = [&](int j) -> uint64_t {
         if (j > last) return ~0ull;
-        if constexpr (LISTED)
-            return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)v_mask_hi, j) << 32) |
-                   (uint32_t)__builtin_amdgcn_readlane((int)v_mask_lo, j);
+        if constexpr (LISTED) {
+            const int t = __builtin_amdgcn_readlane(v_tile, j);
+            return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)v_mask_hi, t) << 32) |
+                   (uint32_t)__builtin_amdgcn_readlane((int)v_mask_lo, t);
+        }
         return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
     };
     // One tile pair = NDMA loads per wavefront: pieces 2i (K part) and 2i+1 (V part) for i < NI, then
     // the odd piece.  They go out together right after a barrier: spreading them over part A, or
     // letting the two halves of the workgroup take turns, measured within 1 %.
     constexpr int NDMA = 2 * NI + 1;
+    // (tk, tv: tile numbers, already looked up)
     auto dma_piece = [&](int i, int tk, int kb_, int tv, int vb_) {
-        tk = tile_of(tk);
-        tv = tile_of(tv);
         const uint8_t* ksrc = tiles + (size_t)tk * G::TILE_BYTES;
         const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
         uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
@@ -308,7 +301,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     const bool late = STAG && wave >= NW / 2;
     auto next_vslot = [](int s) { return s + 1 == VST ? 0 : s + 1; };
     // loads of barrier interval j: K'(j + 2) over K'(j), V^T(j + 1) into the buffer after V^T(j)'s
-    auto dma_interval = [&](int j, int vs) { dma_tiles(j + 2, j & 1, j + 1, next_vslot(vs)); };
+    auto dma_interval = [&](int j, int vs) { dma_tiles(tile_of(j + 2), j & 1, tile_of(j + 1), next_vslot(vs)); };
 
     // vs = j % VST, the buffer V^T(j) sits in
     // LATE (a compile-time tag) selects where the barrier sits; each half runs its own copy of the
@@ -426,8 +419,25 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
 
     // ---- prologue: tiles 0 (K, V) and 1 (K) start streaming, then Q is loaded while they fly ----
     if (n_steps > 0) {
-        dma_tiles(0, 0, 0, 0);
-        dma_tiles(1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
+        // the first two tile numbers come by scalar loads, which do not queue behind the query rows
+        int t0 = 0, t1 = last > 0 ? 1 : 0;
+        if constexpr (LISTED) {
+            const int* tl = a.tile_list + (size_t)b * pv.nKT;
+            t0 = tl[0];
+            t1 = tl[t1];
+        }
+        dma_tiles(t0, 0, t0, 0);
+        dma_tiles(t1, 1, t0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
+    }
+    if constexpr (LISTED) {
+        // lane i: list entry i, and the key mask of TILE i (looked up by tile number, so that the
+        // two loads do not depend on each other)
+        if (lane < n_steps) v_tile = a.tile_list[(size_t)b * pv.nKT + lane];
+        if (lane < pv.nKT) {
+            const uint64_t m = a.tile_mask[(size_t)b * pv.nKT + lane];
+            v_mask_lo = (uint32_t)m;
+            v_mask_hi = (uint32_t)(m >> 32);
+        }
     }
 
     // ---- Q: rotate, fold scale*log2(e), round once, keep as B operands ----
