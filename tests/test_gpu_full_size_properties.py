@@ -70,6 +70,28 @@ def test_moving_the_origin_changes_nothing():
     assert 0.0 < diff <= 2 * 2e-2 * rms  # not bit-identical (other angles), yet the same attention
 
 
+def test_two_schedules_agree_on_every_row():
+    """The pipelined 8-wavefront kernel (default) and the plain one-tile-at-a-time kernel share the
+    arithmetic but not the schedule, the tile transport, the rescale bookkeeping or the workgroup
+    shape; at the full shape they must agree on every one of the 168 M outputs to well within the
+    parity bar (each is held to the oracle on sampled rows elsewhere)."""
+    import torch
+
+    cfg = wl.CONFIGS["dit_14b"]
+    q, k, v = (to_dev(a) for a in wl.self_attn_inputs(cfg))
+    a = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32)
+    b = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32,
+                           flags=B.DIT_FLAG_SIMPLE_SCHEDULE)
+    c = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32,
+                           flags=B.DIT_FLAG_SMALL_WORKGROUP)
+    torch.cuda.synchronize()
+    rms = a.double().pow(2).mean().sqrt().item()
+    for name, other in (("plain", b), ("4-wavefront", c)):
+        diff = (a - other).abs().max().item()
+        print("default vs %s kernel, all rows: max|a - b| / RMS = %.3e" % (name, diff / rms))
+        assert diff <= 2e-3 * rms
+
+
 def test_cross_attention_ignores_padded_keys_for_every_row():
     """cross_14b at full size: overwriting the padded keys and values with large numbers changes
     no output bit, and constant values on the valid keys come back for every row."""
