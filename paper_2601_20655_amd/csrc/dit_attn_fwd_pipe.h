@@ -30,6 +30,9 @@
 #ifndef DIT_PIPE_STAGGER
 #define DIT_PIPE_STAGGER 1  // 8-wavefront workgroups: wavefronts 4-7 run half an iteration behind wavefronts 0-3
 #endif
+#ifndef DIT_PIPE_PRIO
+#define DIT_PIPE_PRIO 1  // staggered form: wavefront priority raised during part A (1), part B (2), never (0)
+#endif
 #ifndef DIT_PIPE_BALANCED
 #define DIT_PIPE_BALANCED 1  // move 6 of the 16 softmax slices from part A into part B (32-row wavefronts, d128)
 #endif
@@ -313,6 +316,12 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         auto kfrag = [&](int f) { return *reinterpret_cast<const u32x4*>(kt + (f & 1) * 32 * G::KROW + (f >> 1) * 32); };
         auto vfrag = [&](int g) { return *reinterpret_cast<const u32x4*>(vt + (g % NDB) * 32 * G::VROW + (g / NDB) * 32); };
 
+        // The two wavefronts of a SIMD are in different parts at any time (staggered form); the
+        // issue arbiter otherwise favours the older wavefront throughout, which then idles at the
+        // barrier while the younger one finishes alone.  Raising the priority in one part makes
+        // the preference alternate.
+        if constexpr (STAG && DIT_PIPE_PRIO == 1) __builtin_amdgcn_s_setprio(1);
+        if constexpr (STAG && DIT_PIPE_PRIO == 2) __builtin_amdgcn_s_setprio(0);
         // ---- part A: S(j+1) on MFMA, P(j) and row sums on VALU ----
         u32x4 kf[2 * NKS], vf[4 * NDB];
 #pragma unroll
@@ -367,6 +376,8 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             __builtin_amdgcn_sched_barrier(0);
         }
 
+        if constexpr (STAG && DIT_PIPE_PRIO == 1) __builtin_amdgcn_s_setprio(0);
+        if constexpr (STAG && DIT_PIPE_PRIO == 2) __builtin_amdgcn_s_setprio(1);
         // ---- part B: O += V^T(j) P(j) on MFMA, row maxima of S(j+1) on VALU ----
         float pm[QB][4];
 #pragma unroll
