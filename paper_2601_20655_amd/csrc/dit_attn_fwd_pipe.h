@@ -298,6 +298,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
     constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4;
+    constexpr bool COPY = QB == 2;
 
     // Wavefronts of the late half (staggered form) pass the workgroup barrier between the two parts
     // of an iteration, the others at its end; both issue their tile loads right after their barrier.
@@ -384,9 +385,17 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int e = 0; e < 4; ++e) pm[qb][e] = -INFINITY;
+        // COPY (64 rows per wavefront): the score MFMAs always write Sn, which then sits in the
+        // accumulation registers; the maxima are taken while the values are copied into Sc, the
+        // vector-ALU side's buffer, whose previous contents part A has consumed by now.
         auto max_slice = [&](int c) {
             const int qv = c / 16, i = c % 16;
-            pm[qv][i & 3] = max3(pm[qv][i & 3], Sn[i / 8][qv][(2 * i) % 16], Sn[i / 8][qv][(2 * i + 1) % 16]);
+            const float s0 = Sn[i / 8][qv][(2 * i) % 16], s1 = Sn[i / 8][qv][(2 * i + 1) % 16];
+            if constexpr (COPY) {
+                Sc[i / 8][qv][(2 * i) % 16] = s0;
+                Sc[i / 8][qv][(2 * i + 1) % 16] = s1;
+            }
+            pm[qv][i & 3] = max3(pm[qv][i & 3], s0, s1);
         };
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
@@ -418,14 +427,15 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         bool need = any_row_needs_shift();
         if constexpr (!LATE) dma_wait_and_sync();
         // rare paths, outside the pipelined block
+        f32x16 (&Sp)[2][QB] = COPY ? Sc : Sn;  // the pending scores of tile j + 1
         const uint64_t mnext = mask_of(j + 1);
         if (mnext != ~0ull) {
-            mask_apply(Sn, mnext);
-            row_max(Sn);
+            mask_apply(Sp, mnext);
+            row_max(Sp);
             need = any_row_needs_shift();
         }
-        // after the last tile Sn holds scores of a stale buffer: never let them touch the state
-        if (need && j < last) shift_rows(Sn);
+        // after the last tile these are scores of a stale buffer: never let them touch the state
+        if (need && j < last) shift_rows(Sp);
     };
 
     // ---- prologue: tiles 0 (K, V) and 1 (K) start streaming, then Q is loaded while they fly ----
@@ -499,13 +509,20 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
 
     auto key_loop = [&](auto late_tag) {
         int j = 0, vs = 0;
-        for (; j + 1 < n_steps; j += 2) {
-            iteration(late_tag, S0, S1, j, vs);
-            vs = next_vslot(vs);
-            iteration(late_tag, S1, S0, j + 1, vs);
-            vs = next_vslot(vs);
+        if constexpr (COPY) {
+            for (; j < n_steps; ++j) {
+                iteration(late_tag, S0, S1, j, vs);
+                vs = next_vslot(vs);
+            }
+        } else {
+            for (; j + 1 < n_steps; j += 2) {
+                iteration(late_tag, S0, S1, j, vs);
+                vs = next_vslot(vs);
+                iteration(late_tag, S1, S0, j + 1, vs);
+                vs = next_vslot(vs);
+            }
+            if (j < n_steps) iteration(late_tag, S0, S1, j, vs);
         }
-        if (j < n_steps) iteration(late_tag, S0, S1, j, vs);
     };
     if (late) {
         key_loop(std::true_type{});
