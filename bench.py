@@ -25,7 +25,7 @@ PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
 # HBM bytes per launch of the self-attention kernel at the dit_14b shape, default flags, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
 # keyed by library version: a library whose kernel has changed since reports null.
-TRAFFIC_BYTES_BY_VERSION = {109: 4.01e9}
+TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9}
 
 
 class HipEvents:
