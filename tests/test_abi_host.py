@@ -243,3 +243,14 @@ def test_public_header_is_plain_c(compiler, std, tmp_path):
     assert sizes == [ctypes.sizeof(B.dit_strides), ctypes.sizeof(B.dit_qk_norm), ctypes.sizeof(B.dit_self_attn_params),
                      ctypes.sizeof(B.dit_cross_attn_params), ctypes.sizeof(B.dit_varlen_attn_params),
                      ctypes.sizeof(B.dit_grid)]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more exits with a message instead of a number."""
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
+                       stderr=subprocess.PIPE, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
