@@ -83,7 +83,17 @@ enum {
      * shorter prologue beats the pipelined kernel's better steady state (measured).  This flag
      * selects the pipelined kernel there too (at most 64 key tiles, i.e. Lk <= 4096 for the joint
      * form, else DIT_ERR_UNSUPPORTED).  No effect on self-attention. */
-    DIT_FLAG_PIPELINED_SCHEDULE = 1u << 10
+    DIT_FLAG_PIPELINED_SCHEDULE = 1u << 10,
+    /* The workspace still holds the rotated, pre-packed K'/V^T tile images (and the rotation table,
+     * the key tile lists and masks) that an earlier forward call of the SAME entry point wrote for the
+     * same k, v, kv_valid, shapes, grid(s), origin, rope_base, norm (mode, eps, k_gamma), key split and
+     * operand-type flags; that call must precede this one in stream order.  The key-side passes are
+     * skipped: k, v and kv_valid are not read and may be NULL.  q, scale, q_gamma, the output and the
+     * schedule flags may differ from call to call.  This is the K/V cache of a denoising loop: the
+     * conditioning keys and values of cross-attention are the same at every step, and a caller that
+     * evaluates several query sets against one K, V pays for one pre-pack.  Nothing records what the
+     * workspace holds: the caller vouches for it.  Not with DIT_FLAG_KV_FUSED (DIT_ERR_INVALID_ARG). */
+    DIT_FLAG_KV_RESIDENT = 1u << 11
 };
 
 typedef struct {

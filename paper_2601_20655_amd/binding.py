@@ -32,6 +32,7 @@ DIT_FLAG_SIMPLE_SCHEDULE = 1 << 7
 DIT_FLAG_BIG_WORKGROUP = 1 << 8
 DIT_FLAG_SMALL_WORKGROUP = 1 << 9
 DIT_FLAG_PIPELINED_SCHEDULE = 1 << 10
+DIT_FLAG_KV_RESIDENT = 1 << 11
 
 EXPORTS = (
     "dit_attn_workspace_bytes",

@@ -53,7 +53,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Flags {
     int qk_op, pv_op, qb, nw;
-    bool fused, simple, pipelined;
+    bool fused, simple, pipelined, resident;
 };
 
 // Resolve flag bits into operand types and staging mode.
@@ -61,7 +61,7 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
                            DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
                            DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP | DIT_FLAG_SMALL_WORKGROUP |
-                           DIT_FLAG_PIPELINED_SCHEDULE;
+                           DIT_FLAG_PIPELINED_SCHEDULE | DIT_FLAG_KV_RESIDENT;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
@@ -69,6 +69,8 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     out->qk_op = (f & DIT_FLAG_QK_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->pv_op = (f & DIT_FLAG_PV_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
+    out->resident = (f & DIT_FLAG_KV_RESIDENT) != 0;
+    if (out->resident && out->fused) return DIT_ERR_INVALID_ARG;  // FUSED keeps nothing to reuse
     out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
     if ((f & DIT_FLAG_SIMPLE_SCHEDULE) && (f & DIT_FLAG_PIPELINED_SCHEDULE)) return DIT_ERR_INVALID_ARG;
     out->simple = (f & DIT_FLAG_SIMPLE_SCHEDULE) != 0;
@@ -130,7 +132,7 @@ size_t rstd_bytes(const dit_qk_norm& n, int64_t q_rows, int64_t k_rows) {
 // Fills the normalisation arguments of both kernels; in TOKEN mode launches the two statistics passes.
 dit_status setup_norm(const dit_qk_norm& n, const void* q, const void* k, const dit_strides& sq, const dit_strides& sk,
                       int B, int Lq, int Lk, int H, int D, int in_f32, uint8_t* rstd_ws, dit::NormArgs* qn,
-                      dit::NormArgs* kn, hipStream_t s) {
+                      dit::NormArgs* kn, bool k_resident, hipStream_t s) {
     memset(qn, 0, sizeof(*qn));
     memset(kn, 0, sizeof(*kn));
     if (n.mode == DIT_NORM_NONE) return DIT_OK;
@@ -146,9 +148,11 @@ dit_status setup_norm(const dit_qk_norm& n, const void* q, const void* k, const 
         ra.B = B; ra.L = Lq; ra.H = H; ra.D = D; ra.in_f32 = in_f32; ra.eps = n.eps;
         hipError_t e = dit::launch_token_rstd(ra, s);
         if (e != hipSuccess) return hip_fail(e, "token_rstd_kernel");
-        ra.x = k; ra.rstd = rk; ra.s_b = sk.batch; ra.s_t = sk.token; ra.s_h = sk.head; ra.L = Lk;
-        e = dit::launch_token_rstd(ra, s);
-        if (e != hipSuccess) return hip_fail(e, "token_rstd_kernel");
+        if (!k_resident) {  // the key rows' factors only feed the pre-pack pass
+            ra.x = k; ra.rstd = rk; ra.s_b = sk.batch; ra.s_t = sk.token; ra.s_h = sk.head; ra.L = Lk;
+            e = dit::launch_token_rstd(ra, s);
+            if (e != hipSuccess) return hip_fail(e, "token_rstd_kernel");
+        }
         qn->rstd = rq;
         kn->rstd = rk;
     }
@@ -377,9 +381,10 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
     SelfPlan pl;
     dit_status st = plan_self(p, &pl);
     if (st != DIT_OK) return st;
-    if (!q || !k || !v || !out) return DIT_ERR_INVALID_ARG;
-    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(k, p->sk, p->in_dtype) ||
-        !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
+    if (!q || !out) return DIT_ERR_INVALID_ARG;
+    if (!pl.fl.resident && (!k || !v)) return DIT_ERR_INVALID_ARG;
+    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(out, p->so, p->out_dtype)) return DIT_ERR_ALIGNMENT;
+    if (!pl.fl.resident && (!aligned16(k, p->sk, p->in_dtype) || !aligned16(v, p->sv, p->in_dtype)))
         return DIT_ERR_ALIGNMENT;
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
@@ -400,17 +405,20 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
     ta.rg = rg;
     ta.base = (double)p->rope_base;
     ta.total = pl.table_entries;
-    hipError_t e = dit::launch_rope_table(ta, s);
-    if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+    hipError_t e = hipSuccess;
+    if (!pl.fl.resident) {
+        e = dit::launch_rope_table(ta, s);
+        if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+    }
 
     const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
 
     dit::NormArgs qn, kn;
     st = setup_norm(p->norm, q, k, p->sq, p->sk, p->B, (int)pl.L, (int)pl.L, p->H, p->D, p->in_dtype == DIT_F32,
-                    ws + pl.rstd_off, &qn, &kn, s);
+                    ws + pl.rstd_off, &qn, &kn, pl.fl.resident, s);
     if (st != DIT_OK) return st;
 
-    if (!pl.fl.fused) {
+    if (!pl.fl.fused && !pl.fl.resident) {
         dit::PackArgs pa;
         memset(&pa, 0, sizeof(pa));
         pa.kn = kn;
@@ -452,9 +460,10 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     CrossPlan pl;
     dit_status st = plan_cross(p, &pl);
     if (st != DIT_OK) return st;
-    if (!q || !k || !v || !out) return DIT_ERR_INVALID_ARG;
-    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(k, p->sk, p->in_dtype) ||
-        !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
+    if (!q || !out) return DIT_ERR_INVALID_ARG;
+    if (!pl.fl.resident && (!k || !v)) return DIT_ERR_INVALID_ARG;
+    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(out, p->so, p->out_dtype)) return DIT_ERR_ALIGNMENT;
+    if (!pl.fl.resident && (!aligned16(k, p->sk, p->in_dtype) || !aligned16(v, p->sv, p->in_dtype)))
         return DIT_ERR_ALIGNMENT;
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
     if (lse && pl.split > 0) return DIT_ERR_UNSUPPORTED;  // two softmaxes have no single log-sum-exp
@@ -467,7 +476,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
 
     dit::NormArgs qn, kn;
     st = setup_norm(p->norm, q, k, p->sq, p->sk, p->B, p->Lq, p->Lk, p->H, p->D, p->in_dtype == DIT_F32,
-                    ws + pl.rstd_off, &qn, &kn, s);
+                    ws + pl.rstd_off, &qn, &kn, pl.fl.resident, s);
     if (st != DIT_OK) return st;
 
     dit::PackArgs pa;
@@ -486,10 +495,12 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.in_f32 = p->in_dtype == DIT_F32;
     pa.sk_b = p->sk.batch; pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
     pa.sv_b = p->sv.batch; pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
-    hipError_t e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
-    if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
-    e = dit::launch_tile_compact(pa, s);
-    if (e != hipSuccess) return hip_fail(e, "tile_compact_kernel");
+    if (!pl.fl.resident) {
+        hipError_t e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
+        if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
+        e = dit::launch_tile_compact(pa, s);
+        if (e != hipSuccess) return hip_fail(e, "tile_compact_kernel");
+    }
 
     dit::AttnArgs aa;
     memset(&aa, 0, sizeof(aa));
@@ -520,9 +531,10 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     VarlenPlan pl;
     dit_status st = plan_varlen(p, &pl);
     if (st != DIT_OK) return st;
-    if (!q || !k || !v || !out) return DIT_ERR_INVALID_ARG;
-    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(k, p->sk, p->in_dtype) ||
-        !aligned16(v, p->sv, p->in_dtype) || !aligned16(out, p->so, p->out_dtype))
+    if (!q || !out) return DIT_ERR_INVALID_ARG;
+    if (!pl.fl.resident && (!k || !v)) return DIT_ERR_INVALID_ARG;
+    if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(out, p->so, p->out_dtype)) return DIT_ERR_ALIGNMENT;
+    if (!pl.fl.resident && (!aligned16(k, p->sk, p->in_dtype) || !aligned16(v, p->sv, p->in_dtype)))
         return DIT_ERR_ALIGNMENT;
     if (lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) return DIT_ERR_ALIGNMENT;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
@@ -544,8 +556,11 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     ta.rg = rg;
     ta.base = (double)p->rope_base;
     ta.total = pl.table_entries;
-    hipError_t e = dit::launch_rope_table(ta, s);
-    if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+    hipError_t e = hipSuccess;
+    if (!pl.fl.resident) {
+        e = dit::launch_rope_table(ta, s);
+        if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+    }
 
     const float scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
 
@@ -553,7 +568,7 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     dit_strides sq1 = p->sq, sk1 = p->sk;
     sq1.batch = sk1.batch = 0;
     st = setup_norm(p->norm, q, k, sq1, sk1, 1, pl.vt.total_tokens, pl.vt.total_tokens, p->H, p->D,
-                    p->in_dtype == DIT_F32, ws + pl.rstd_off, &qn, &kn, s);
+                    p->in_dtype == DIT_F32, ws + pl.rstd_off, &qn, &kn, pl.fl.resident, s);
     if (st != DIT_OK) return st;
 
     dit::PackArgs pa;
@@ -567,8 +582,10 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
     pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
     pa.rg = rg;
-    e = dit::launch_prepack_varlen(pa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
-    if (e != hipSuccess) return hip_fail(e, "kv_prepack_varlen_kernel");
+    if (!pl.fl.resident) {
+        e = dit::launch_prepack_varlen(pa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
+        if (e != hipSuccess) return hip_fail(e, "kv_prepack_varlen_kernel");
+    }
 
     dit::AttnArgs aa;
     memset(&aa, 0, sizeof(aa));
@@ -611,6 +628,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 110; }
+int dit_attn_version(void) { return 111; }
 
 }  // extern "C"

@@ -94,6 +94,7 @@ def test_self_attn_rejects_bad_arguments():
     assert call_self(self_params(flags=B.DIT_FLAG_QK_BF16 | B.DIT_FLAG_QK_F16)) == B.DIT_ERR_INVALID_ARG
     assert call_self(self_params(flags=B.DIT_FLAG_KV_PREPACK | B.DIT_FLAG_KV_FUSED)) == B.DIT_ERR_INVALID_ARG
     assert call_self(self_params(flags=1 << 20)) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(flags=B.DIT_FLAG_KV_RESIDENT | B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)) == B.DIT_ERR_INVALID_ARG
     assert call_self(self_params(flags=B.DIT_FLAG_WIDE_QTILE | B.DIT_FLAG_BIG_WORKGROUP)) == B.DIT_ERR_UNSUPPORTED
     assert call_self(self_params(flags=B.DIT_FLAG_SMALL_WORKGROUP | B.DIT_FLAG_BIG_WORKGROUP)) == B.DIT_ERR_INVALID_ARG
     # fused staging needs bf16 inputs, bf16 PV operands, head_dim 128
