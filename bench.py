@@ -26,7 +26,8 @@ PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
 # keyed by library version: a library whose kernel has changed since reports null.
 # (111 added a host-side flag only; its kernels are those of 110.)
-TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9}
+# (112 added the 8-bit score path as separate instantiations; the default kernel's code is byte-identical.)
+TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9}
 
 
 class HipEvents:

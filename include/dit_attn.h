@@ -93,7 +93,17 @@ enum {
      * conditioning keys and values of cross-attention are the same at every step, and a caller that
      * evaluates several query sets against one K, V pays for one pre-pack.  Nothing records what the
      * workspace holds: the caller vouches for it.  Not with DIT_FLAG_KV_FUSED (DIT_ERR_INVALID_ARG). */
-    DIT_FLAG_KV_RESIDENT = 1u << 11
+    DIT_FLAG_KV_RESIDENT = 1u << 11,
+    /* Score product on 8-bit operands: q' and k' are rounded to e4m3 (4 significant bits), each row
+     * with its own power-of-two factor that the matrix instruction applies; P and V keep their 16-bit
+     * types and everything else stays fp32.  The matrix pipe runs this product at twice the 16-bit
+     * rate and reads half the K' bytes.  THE ERROR IS TEN TIMES THAT OF THE 16-BIT PATH and does not
+     * meet its contract: with unit-variance inputs expect an RMS error near 3e-2 x output RMS and a
+     * largest error near 0.2 x output RMS.  Self-attention entry points only (dit_attn_forward with the
+     * pipelined 32-rows-per-wavefront kernel, dit_attn_varlen_forward); excludes QK_BF16 / QK_F16
+     * (DIT_ERR_INVALID_ARG) and KV_FUSED, SIMPLE_SCHEDULE, WIDE_QTILE, cross-attention
+     * (DIT_ERR_UNSUPPORTED).  Never selected by default. */
+    DIT_FLAG_QK_FP8 = 1u << 12
 };
 
 typedef struct {

@@ -33,6 +33,7 @@ DIT_FLAG_BIG_WORKGROUP = 1 << 8
 DIT_FLAG_SMALL_WORKGROUP = 1 << 9
 DIT_FLAG_PIPELINED_SCHEDULE = 1 << 10
 DIT_FLAG_KV_RESIDENT = 1 << 11
+DIT_FLAG_QK_FP8 = 1 << 12
 
 EXPORTS = (
     "dit_attn_workspace_bytes",

@@ -17,9 +17,12 @@ hipError_t launch_attn_pipe_d128_qb1(const AttnArgs&, int, int, int, hipStream_t
 hipError_t launch_attn_pipe_d128_qb2(const AttnArgs&, int, int, int, hipStream_t);
 hipError_t launch_attn_pipe_d64_qb1(const AttnArgs&, int, int, int, hipStream_t);
 hipError_t launch_attn_pipe_d64_qb2(const AttnArgs&, int, int, int, hipStream_t);
+hipError_t launch_attn_pipe_fp8(const AttnArgs&, int D, int pv_op, int nw, hipStream_t);
+hipError_t launch_attn_pipe_varlen_fp8(const AttnArgs&, const VarlenTable&, int D, int pv_op, int nw, hipStream_t);
 
 // Software-pipelined kernel: pre-packed tiles, no key mask beyond the ragged tail.
 hipError_t launch_attn_pipe(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, int nw, hipStream_t s) {
+    if (qk_op == OP_FP8) return qb == 1 ? launch_attn_pipe_fp8(a, D, pv_op, nw, s) : hipErrorInvalidValue;
     if (D == 128 && qb == 1) return launch_attn_pipe_d128_qb1(a, qk_op, pv_op, nw, s);
     if (D == 128 && qb == 2) return launch_attn_pipe_d128_qb2(a, qk_op, pv_op, nw, s);
     if (D == 64 && qb == 1) return launch_attn_pipe_d64_qb1(a, qk_op, pv_op, nw, s);
@@ -61,12 +64,13 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
                            DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
                            DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP | DIT_FLAG_SMALL_WORKGROUP |
-                           DIT_FLAG_PIPELINED_SCHEDULE | DIT_FLAG_KV_RESIDENT;
+                           DIT_FLAG_PIPELINED_SCHEDULE | DIT_FLAG_KV_RESIDENT | DIT_FLAG_QK_FP8;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_KV_PREPACK) && (f & DIT_FLAG_KV_FUSED)) return DIT_ERR_INVALID_ARG;
-    out->qk_op = (f & DIT_FLAG_QK_BF16) ? dit::OP_BF16 : dit::OP_F16;
+    if ((f & DIT_FLAG_QK_FP8) && (f & (DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16))) return DIT_ERR_INVALID_ARG;
+    out->qk_op = (f & DIT_FLAG_QK_FP8) ? dit::OP_FP8 : (f & DIT_FLAG_QK_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->pv_op = (f & DIT_FLAG_PV_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
     out->resident = (f & DIT_FLAG_KV_RESIDENT) != 0;
@@ -195,6 +199,8 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
     pl->L = L;
     pl->nKT = (int)((L + dit::kBK - 1) / dit::kBK);
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;  // would need 512 registers x 512 lanes
+    // 8-bit score operands exist in the pipelined 32-rows-per-wavefront kernel only
+    if (pl->fl.qk_op == dit::OP_FP8 && (pl->fl.fused || pl->fl.simple || pl->fl.qb == 2)) return DIT_ERR_UNSUPPORTED;
     if (pl->fl.fused || pl->fl.simple || pl->fl.qb == 2) {
         pl->fl.nw = 4;  // only the pipelined 32-rows-per-wavefront kernel has the 8-wavefront form
     } else if (pl->fl.nw == 0) {
@@ -334,6 +340,7 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     pl->split = (p->Lk_split == p->Lk) ? 0 : p->Lk_split;  // a split at either end is the joint softmax
     pl->nTA = (pl->split + dit::kBK - 1) / dit::kBK;
     pl->nKT = pl->nTA + (p->Lk - pl->split + dit::kBK - 1) / dit::kBK;
+    if (pl->fl.qk_op == dit::OP_FP8) return DIT_ERR_UNSUPPORTED;  // self-attention only
     if (pl->split > 0 && (pl->fl.pipelined || pl->fl.qb == 2)) return DIT_ERR_UNSUPPORTED;
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
     // the pipelined kernel keeps the list of non-empty tiles in the 64 lanes of a wavefront
@@ -603,7 +610,9 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
 
     const bool timed = g_ev_before && g_ev_after;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
-    e = dit::launch_attn_pipe_varlen(aa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, pl.fl.nw, s);
+    e = pl.fl.qk_op == dit::OP_FP8
+            ? dit::launch_attn_pipe_varlen_fp8(aa, pl.vt, p->D, pl.fl.pv_op, pl.fl.nw, s)
+            : dit::launch_attn_pipe_varlen(aa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, pl.fl.nw, s);
     if (e != hipSuccess) return hip_fail(e, "attention kernel");
     if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     return DIT_OK;
@@ -628,6 +637,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 111; }
+int dit_attn_version(void) { return 112; }
 
 }  // extern "C"

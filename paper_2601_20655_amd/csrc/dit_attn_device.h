@@ -61,6 +61,36 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
     }
 }
 
+// ---- 8-bit (OCP e4m3) score operands ----
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+// Exponent e such that amax * 2^e lies in [128, 256), inside e4m3's normal range (largest finite
+// value 448); 0 for an all-zero row.  Clamped so that 127 - e stays a valid 8-bit scale code.
+__device__ __forceinline__ int fp8_row_exponent(float amax) {
+    const int be = (int)((__float_as_uint(amax) >> 23) & 255u);  // amax in [2^(be-127), 2^(be-126))
+    if (be == 0) return 0;
+    const int e = 134 - be;
+    return e > 100 ? 100 : (e < -100 ? -100 : e);
+}
+__device__ __forceinline__ float pow2i(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }
+
+// Eight fp32 values -> eight e4m3 bytes (round to nearest even), byte i = x[i].
+__device__ __forceinline__ uint2 pack8_fp8(const float x[8]) {
+    int lo = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], 0, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], lo, true);
+    int hi = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], 0, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], hi, true);
+    return make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
+// D(32x32, fp32) += 2^(sa-127) A(32x64, e4m3) * 2^(sb-127) B(64x32, e4m3).  Lane l supplies 32
+// contraction indices of row (l % 32) of A and of column (l % 32) of B, the same 32 indices on
+// both sides (group l / 32); sa and sb are the lane's own 8-bit scale codes for that row resp.
+// column, and the two lanes of a row must carry the same code.  Result layout as mfma32.
+__device__ __forceinline__ f32x16 mfma32_fp8(i32x8 a, i32x8 b, f32x16 c, int sa, int sb) {
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, sa, 0, sb);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 

@@ -94,9 +94,15 @@ struct PipeView {
 template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
 __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView& pv) {
     using G = TileGeom<D>;
-    constexpr int NKS = D / 16;
+    // FP8: the score product runs on 8-bit (e4m3) operands, 64 channels per MFMA instead of 16, with one
+    // power-of-two factor per q' row and per k' row that the MFMA applies itself
+    constexpr bool FP8 = QK_OP == OP_FP8;
+    constexpr int NKS = FP8 ? D / 64 : D / 16;  // MFMAs of one score chain
+    constexpr int NQC = D / 16;                 // 16-byte chunks of a q row each lane of a pair reads
     constexpr int NDB = D / 32;
     constexpr int BQ = NW * QB * 32;
+    static_assert(!FP8 || QB == 1, "8-bit score operands: 32 rows per wavefront only");
+    using QFrag = std::conditional_t<FP8, i32x8, u32x4>;
     constexpr int NI = G::PART_KIB / NW;  // full rounds of wavefront-wide 1 KiB loads per tile part
     static_assert(G::PART_KIB - NW * NI == 2, "two odd pieces per tile part");
 
@@ -119,8 +125,9 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     // Query rows (16-bit inputs) are requested before anything else: they come from HBM and need
     // only the workgroup's coordinates, while the first tiles wait for the tile list.  They are
     // converted into Qf after the first tiles have been requested.
-    u32x4 Qf[QB][NKS];
-    u32x4 qraw[QB][NKS];
+    QFrag Qf[QB][NKS];
+    int q_code[QB];  // FP8: 8-bit scale code of the lane's q' row
+    u32x4 qraw[QB][NQC];
     int qrow[QB];
     if (!a.in_f32) {
 #pragma unroll
@@ -129,7 +136,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             const int qr = row < pv.Lq ? row : pv.Lq - 1;
             const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks)
+            for (int ks = 0; ks < NQC; ++ks)
                 qraw[qb][ks] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + base +
                                                               8 * (2 * ks + half));
         }
@@ -209,8 +216,25 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             for (int r = 0; r < 16; ++r) O[db][qb][r] = 0.f;
     }
 
-    const int kread_off = l32 * G::KROW + half * 16;
+    const int kread_off = FP8 ? l32 * G::KROW8 + half * 32 : l32 * G::KROW + half * 16;
     const int vread_off = l32 * G::VROW + half * 16;
+    // A operand of score MFMA f (key block f & 1, contraction step f >> 1) of the tile at kt
+    auto k_operand = [&](const uint8_t* kt, int f) {
+        if constexpr (FP8) {
+            const uint8_t* p = kt + (f & 1) * 32 * G::KROW8 + (f >> 1) * 64;
+            const u32x4 lo = *reinterpret_cast<const u32x4*>(p), hi = *reinterpret_cast<const u32x4*>(p + 16);
+            const i32x8 r = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+            return r;
+        } else {
+            return *reinterpret_cast<const u32x4*>(kt + (f & 1) * 32 * G::KROW + (f >> 1) * 32);
+        }
+    };
+    // FP8: scale code of the lane's key row in key block kb of the tile in K buffer buf
+    auto k_code = [&](int buf, int kb) -> int { return kbuf[buf * G::K_BYTES + G::KSCALE_OFF + kb * 32 + l32]; };
+    auto score_mfma = [&](const auto& ka, const QFrag& qf, const f32x16& acc, int kcode, int qcode) {
+        if constexpr (FP8) return mfma32_fp8(ka, qf, acc, kcode, qcode);
+        else return mfma32<QK_OP>(ka, qf, acc);
+    };
     // S^T of one tile: two 32-key blocks per query block
     auto qk_tile = [&](f32x16 (&S)[2][QB], int buf) {
         const uint8_t* kt = kbuf + buf * G::K_BYTES + kread_off;
@@ -220,13 +244,18 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) S[kb][qb][r] = 0.f;
+        int kc[2] = {0, 0};
+        if constexpr (FP8) {
+            kc[0] = k_code(buf, 0);
+            kc[1] = k_code(buf, 1);
+        }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const u32x4 ka = *reinterpret_cast<const u32x4*>(kt + kb * 32 * G::KROW + ks * 32);
+                const auto ka = k_operand(kt, 2 * ks + kb);
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) S[kb][qb] = mfma32<QK_OP>(ka, Qf[qb][ks], S[kb][qb]);
+                for (int qb = 0; qb < QB; ++qb) S[kb][qb] = score_mfma(ka, Qf[qb][ks], S[kb][qb], kc[kb], q_code[qb]);
             }
         }
     };
@@ -296,8 +325,9 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     constexpr int CPA = NCH / NA, CPB = NCH / NB;
     constexpr int PRE = DIT_PIPE_PRE;        // exp slices issued before the first MFMA, covering LDS latency
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
-    static_assert(LA <= 2 * NKS && LA <= 4 * NDB && LA * QB <= NA, "lookahead too deep");
-    constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4;
+    constexpr int LAK = FP8 ? 2 * NKS : LA;  // FP8: a tile's few (32-byte) K' operands are all read up front
+    static_assert(LAK <= 2 * NKS && LA <= 4 * NDB && LAK * QB <= NA, "lookahead too deep");
+    constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4 && !FP8;
     constexpr bool COPY = QB == 2;
 
     // Wavefronts of the late half (staggered form) pass the workgroup barrier between the two parts
@@ -314,7 +344,7 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         constexpr bool LATE = decltype(late_tag)::value;
         const uint8_t* kt = kbuf + ((j + 1) & 1) * G::K_BYTES + kread_off;
         const uint8_t* vt = vbuf + vs * G::V_BYTES + vread_off;
-        auto kfrag = [&](int f) { return *reinterpret_cast<const u32x4*>(kt + (f & 1) * 32 * G::KROW + (f >> 1) * 32); };
+        auto kfrag = [&](int f) { return k_operand(kt, f); };
         auto vfrag = [&](int g) { return *reinterpret_cast<const u32x4*>(vt + (g % NDB) * 32 * G::VROW + (g / NDB) * 32); };
 
         // The two wavefronts of a SIMD are in different parts at any time (staggered form); the
@@ -324,9 +354,15 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         if constexpr (STAG && DIT_PIPE_PRIO == 1) __builtin_amdgcn_s_setprio(1);
         if constexpr (STAG && DIT_PIPE_PRIO == 2) __builtin_amdgcn_s_setprio(0);
         // ---- part A: S(j+1) on MFMA, P(j) and row sums on VALU ----
-        u32x4 kf[2 * NKS], vf[4 * NDB];
+        decltype(k_operand(kt, 0)) kf[2 * NKS];
+        u32x4 vf[4 * NDB];
 #pragma unroll
-        for (int f = 0; f < LA; ++f) kf[f] = kfrag(f);
+        for (int f = 0; f < LAK; ++f) kf[f] = kfrag(f);
+        int kc[2] = {0, 0};
+        if constexpr (FP8) {
+            kc[0] = k_code((j + 1) & 1, 0);
+            kc[1] = k_code((j + 1) & 1, 1);
+        }
         if constexpr (!LATE) dma_interval(j, vs);
 
         uint32_t Pd[QB][16];
@@ -351,10 +387,15 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
 #pragma unroll
         for (int t = 0; t < NA; ++t) {
             const int f = t / QB, qb = t % QB, ks = f >> 1, kb = f & 1;
-            if (qb == 0 && f + LA < 2 * NKS) kf[f + LA] = kfrag(f + LA);
+            if (qb == 0 && f + LAK < 2 * NKS) kf[f + LAK] = kfrag(f + LAK);
             // the last steps of part A fetch the first V^T fragments of part B
-            if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
-            Sn[kb][qb] = mfma32<QK_OP>(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb]);
+            if constexpr (FP8) {  // (fewer steps than fragments: spread evenly)
+#pragma unroll
+                for (int g = t * LA / NA; g < (t + 1) * LA / NA; ++g) vf[g] = vfrag(g);
+            } else {
+                if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
+            }
+            Sn[kb][qb] = score_mfma(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb], kc[kb], q_code[qb]);
             if constexpr (BAL) {
                 if (bal_a_exp(t) >= 0) exp_slice(bal_a_exp(t));
                 if (bal_a_pack(t) >= 0) pack_slice(bal_a_pack(t));
@@ -471,8 +512,10 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         if (a.tab) token_pos(qr, rg, pt, ph, pw);
         float rs = 1.f;
         if (a.qn.mode) rs = q_row_rstd<D>(a.qn, a.q, base, a.in_f32, half, pv.stat_off + qr);
+        float xq[FP8 ? NQC : 1][8];  // FP8: the whole row is needed before its factor is known
+        float am = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
+        for (int ks = 0; ks < NQC; ++ks) {
             const int c = 2 * ks + half;
             float x[8];
             if (a.in_f32) load8(a.q, base + 8 * c, 1, x);
@@ -481,7 +524,31 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             if (a.tab) rope8(x, c, rg, a.tab, pt, ph, pw);
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
-            Qf[qb][ks] = pack8<QK_OP>(x);
+            if constexpr (FP8) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    xq[ks][e] = x[e];
+                    am = fmaxf(am, fabsf(x[e]));
+                }
+            } else {
+                Qf[qb][ks] = pack8<QK_OP>(x);
+            }
+        }
+        q_code[qb] = 0;
+        if constexpr (FP8) {
+            am = fmaxf(am, __shfl_xor(am, 32));
+            const int ex = fp8_row_exponent(am);
+            const float sc = pow2i(ex);
+            q_code[qb] = 127 - ex;
+            // chunk 2*ks + half of the row -> contraction step ks / 4, bytes 8*(ks % 4).. of the lane's 32
+#pragma unroll
+            for (int ks = 0; ks < NQC; ++ks) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xq[ks][e] *= sc;
+                const uint2 w = pack8_fp8(xq[ks]);
+                Qf[qb][ks / 4][2 * (ks % 4)] = (int)w.x;
+                Qf[qb][ks / 4][2 * (ks % 4) + 1] = (int)w.y;
+            }
         }
     }
 

@@ -9,7 +9,7 @@ constexpr int kBK = 64;         // keys per K/V tile
 constexpr int kThreads = 256;   // four wavefronts per workgroup
 constexpr float kLog2e = 1.4426950408889634f;
 
-enum OperandType { OP_BF16 = 0, OP_F16 = 1 };
+enum OperandType { OP_BF16 = 0, OP_F16 = 1, OP_FP8 = 2 };  // OP_FP8 (e4m3): score operands only
 
 // One K/V tile as it sits in LDS (and, pre-packed, in workspace): 64 rows of K' followed by
 // D rows of V^T.  Rows carry 16 bytes of padding so that the 16-byte operand reads of 16
@@ -25,6 +25,12 @@ struct TileGeom {
     static constexpr int V_BYTES = PART_KIB * 1024;  // >= D * VROW
     static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
     static_assert(kBK * KROW <= K_BYTES && D * VROW <= V_BYTES && PART_KIB % 4 == 2, "tile part sizes");
+    // 8-bit (e4m3) score operands: the K part starts with 64 rows of D bytes (same padding rule)
+    // followed by one byte per key, 127 - e, where the row was multiplied by 2^e before rounding;
+    // the rest of the part is unused.
+    static constexpr int KROW8 = D + 16;
+    static constexpr int KSCALE_OFF = kBK * KROW8;
+    static_assert(KSCALE_OFF + kBK <= K_BYTES, "8-bit K' rows and their scales fit the K part");
 };
 
 inline size_t tile_bytes(int D) { return D == 128 ? TileGeom<128>::TILE_BYTES : TileGeom<64>::TILE_BYTES; }

@@ -111,7 +111,25 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
                 rope8(xk, c, t.rg, a.tab, pt, ph, pw);
             }
         }
-        *reinterpret_cast<u32x4*>(t.dst + r * G::KROW + c * 16) = pack8<QK_OP>(xk);
+        if constexpr (QK_OP == OP_FP8) {
+            // one power-of-two factor per key row brings its largest magnitude into [128, 256)
+            float am = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) am = fmaxf(am, fabsf(xk[e]));
+#pragma unroll
+            for (int m = 1; m < CPR; m <<= 1) am = fmaxf(am, __shfl_xor(am, m));
+            const int ex = fp8_row_exponent(am);
+            const float sc = pow2i(ex);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xk[e] *= sc;
+            // chunk c = channels [8c, 8c+8) goes where the lane that multiplies it against the same
+            // channels of q' finds it: contraction step c / 8, lane half c % 2, slot (c / 2) % 4
+            const int off = (c >> 3) * 64 + (c & 1) * 32 + ((c >> 1) & 3) * 8;
+            *reinterpret_cast<uint2*>(t.dst + r * G::KROW8 + off) = pack8_fp8(xk);
+            if (c == 0) t.dst[G::KSCALE_OFF + r] = (uint8_t)(127 - ex);
+        } else {
+            *reinterpret_cast<u32x4*>(t.dst + r * G::KROW + c * 16) = pack8<QK_OP>(xk);
+        }
         const u32x4 pv = pack8<PV_OP>(xv);
         uint32_t* row = reinterpret_cast<uint32_t*>(vs + r * VS + 8 * c);
         row[0] = pv.x; row[1] = pv.y; row[2] = pv.z; row[3] = pv.w;
@@ -238,6 +256,10 @@ hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D
     DIT_PACKV_CASE(64, OP_F16, OP_BF16)
     DIT_PACKV_CASE(64, OP_BF16, OP_F16)
     DIT_PACKV_CASE(64, OP_BF16, OP_BF16)
+    DIT_PACKV_CASE(128, OP_FP8, OP_F16)
+    DIT_PACKV_CASE(128, OP_FP8, OP_BF16)
+    DIT_PACKV_CASE(64, OP_FP8, OP_F16)
+    DIT_PACKV_CASE(64, OP_FP8, OP_BF16)
 #undef DIT_PACKV_CASE
     return hipErrorInvalidValue;
 }
@@ -253,6 +275,10 @@ hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStr
     DIT_PACK_CASE(64, OP_F16, OP_BF16)
     DIT_PACK_CASE(64, OP_BF16, OP_F16)
     DIT_PACK_CASE(64, OP_BF16, OP_BF16)
+    DIT_PACK_CASE(128, OP_FP8, OP_F16)
+    DIT_PACK_CASE(128, OP_FP8, OP_BF16)
+    DIT_PACK_CASE(64, OP_FP8, OP_F16)
+    DIT_PACK_CASE(64, OP_FP8, OP_BF16)
 #undef DIT_PACK_CASE
     return hipErrorInvalidValue;
 }

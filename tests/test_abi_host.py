@@ -95,6 +95,11 @@ def test_self_attn_rejects_bad_arguments():
     assert call_self(self_params(flags=B.DIT_FLAG_KV_PREPACK | B.DIT_FLAG_KV_FUSED)) == B.DIT_ERR_INVALID_ARG
     assert call_self(self_params(flags=1 << 20)) == B.DIT_ERR_INVALID_ARG
     assert call_self(self_params(flags=B.DIT_FLAG_KV_RESIDENT | B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)) == B.DIT_ERR_INVALID_ARG
+    # 8-bit score operands: not together with a 16-bit choice, and only in the pipelined 32-row kernel
+    assert call_self(self_params(flags=B.DIT_FLAG_QK_FP8 | B.DIT_FLAG_QK_F16)) == B.DIT_ERR_INVALID_ARG
+    assert call_self(self_params(flags=B.DIT_FLAG_QK_FP8 | B.DIT_FLAG_QK_BF16)) == B.DIT_ERR_INVALID_ARG
+    for other in (B.DIT_FLAG_SIMPLE_SCHEDULE, B.DIT_FLAG_WIDE_QTILE, B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16):
+        assert call_self(self_params(flags=B.DIT_FLAG_QK_FP8 | other)) == B.DIT_ERR_UNSUPPORTED
     assert call_self(self_params(flags=B.DIT_FLAG_WIDE_QTILE | B.DIT_FLAG_BIG_WORKGROUP)) == B.DIT_ERR_UNSUPPORTED
     assert call_self(self_params(flags=B.DIT_FLAG_SMALL_WORKGROUP | B.DIT_FLAG_BIG_WORKGROUP)) == B.DIT_ERR_INVALID_ARG
     # fused staging needs bf16 inputs, bf16 PV operands, head_dim 128
@@ -124,6 +129,7 @@ def test_cross_attn_rejects_bad_arguments():
     assert call_cross(cross_params(Lk=0)) == B.DIT_ERR_INVALID_ARG
     assert call_cross(cross_params(D=32)) == B.DIT_ERR_UNSUPPORTED
     assert call_cross(cross_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)) == B.DIT_ERR_UNSUPPORTED
+    assert call_cross(cross_params(flags=B.DIT_FLAG_QK_FP8)) == B.DIT_ERR_UNSUPPORTED
     assert call_cross(cross_params(), v=0) == B.DIT_ERR_INVALID_ARG
     assert call_cross(cross_params(split=770)) == B.DIT_ERR_INVALID_ARG
     assert call_cross(cross_params(split=-1)) == B.DIT_ERR_INVALID_ARG

@@ -1,0 +1,166 @@
+"""GPU checks of the 8-bit score path (DIT_FLAG_QK_FP8) against the CPU fp64 oracle.
+
+This path does NOT meet the 16-bit parity bar and is never the default.  Its own contract follows
+from the arithmetic: q' and k' are rounded to e4m3 (3 stored mantissa bits, round to nearest), a
+relative error of RMS d = 2^-4 / sqrt(3) * 0.7355 = 2.65e-2 per element (0.7355: the mean of 1/x^2
+over a log-uniform mantissa x in [1, 2), square-rooted).  A score s = scale * sum_c q_c k_c then
+carries an error of standard deviation scale * d * sqrt(2 * sum_c (q_c k_c)^2) = d * sqrt(2) * sigma_s
+where sigma_s is the standard deviation of the scores themselves (for independent channels), i.e.
+3.75e-2 for unit-variance scores.  To first order the output moves by sum_j p_j e_j (v_j - o), so for
+value rows that are independent of the scores the RMS output error is that same 3.75e-2 * sigma_s
+times the output RMS.  The tests allow 1.35x that for the RMS error, 16x for the largest element,
+and demand at least 0.4x: a result as exact as the 16-bit path would mean the flag was ignored.
+A short sequence has few keys per row and an output RMS close to that of v itself, while a row whose
+mass sits on two or three keys moves by (score error) x (distance between their value rows): there
+the largest error is bounded against the RMS of v instead, |err| <= 8 x 3.75e-2 x sigma_s x RMS(v).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2601_20655_amd import binding as B
+from paper_2601_20655_amd import workloads as wl
+from gpu_util import to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+FP8 = B.DIT_FLAG_QK_FP8
+D_REL = 2.0 ** -4 / np.sqrt(3.0) * 0.7355       # RMS relative rounding error of an e4m3 operand
+PREDICTED = D_REL * np.sqrt(2.0)                 # RMS output error / output RMS at unit score spread
+SHAPES = {"auto": 0, "4w": B.DIT_FLAG_SMALL_WORKGROUP, "8w": B.DIT_FLAG_BIG_WORKGROUP}
+
+
+def check(gpu, ref, sigma_s=1.0, what="", rms_bound=True, v=None):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape and np.all(np.isfinite(gpu)), what
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    err = gpu - ref
+    e_rms, e_max = float(np.sqrt(np.mean(err * err))) / rms, float(np.abs(err).max()) / rms
+    print("%s: RMS err %.3e, max err %.3e (x output RMS); predicted RMS %.3e" % (what, e_rms, e_max,
+                                                                                PREDICTED * sigma_s))
+    if v is None:
+        assert e_max <= 16.0 * PREDICTED * sigma_s, what
+    else:
+        v = oracle.as_f64(v)
+        assert float(np.abs(err).max()) <= 8.0 * PREDICTED * sigma_s * float(np.sqrt(np.mean(v * v))), what
+    if rms_bound:
+        assert 0.4 * PREDICTED * sigma_s <= e_rms <= 1.35 * PREDICTED * sigma_s, what
+    return e_rms, e_max
+
+
+def run_self(cfg, q, k, v, **kw):
+    import torch
+
+    res = B.dit_attn_forward(to_dev(q), to_dev(k), to_dev(v), cfg["grid"], cfg["split"], **kw)
+    torch.cuda.synchronize()
+    return res
+
+
+@pytest.mark.parametrize("shape", sorted(SHAPES))
+@pytest.mark.parametrize("pv", [0, B.DIT_FLAG_PV_BF16])
+def test_mid_config_all_rows(shape, pv):
+    """6,240 tokens x 4 heads x d128 (97.5 key tiles: ragged tail), every row, plus the log-sum-exp."""
+    import torch
+
+    cfg = wl.CONFIGS["mid"]
+    q, k, v = wl.self_attn_inputs(cfg)
+    ref, ref_lse = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], want_lse=True)
+    out, lse = run_self(cfg, q, k, v, flags=FP8 | SHAPES[shape] | pv, out_dtype=torch.float32, want_lse=True)
+    check(to_f64(out), ref, what="mid %s pv=%d" % (shape, pv))
+    # the score errors average out over the keys that carry the mass
+    assert np.max(np.abs(to_f64(lse) - ref_lse)) < 2e-2
+    out = run_self(cfg, q, k, v, flags=FP8 | SHAPES[shape] | pv)
+    check(to_f64(out), ref, what="mid %s pv=%d, bf16 out" % (shape, pv))
+
+
+def test_tiny_config_d64_fp32_inputs():
+    import torch
+
+    cfg = wl.CONFIGS["tiny"]
+    q, k, v = wl.self_attn_inputs(cfg)
+    ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"])
+    for shape in sorted(SHAPES):
+        out = run_self(cfg, q, k, v, flags=FP8 | SHAPES[shape], out_dtype=torch.float32)
+        check(to_f64(out), ref, what="tiny %s" % shape)
+
+
+@pytest.mark.parametrize("grid", [(1, 1, 1), (1, 1, 2), (1, 3, 21), (1, 1, 64), (1, 5, 13), (2, 8, 8), (1, 3, 43),
+                                  (3, 7, 19)])
+@pytest.mark.parametrize("D", [64, 128])
+def test_ragged_sizes(grid, D):
+    """Token counts 1 .. 399 around the tile boundaries.  Too few elements for the RMS window, so
+    only the largest error is bounded; a single token must come back exactly (P = 1)."""
+    import torch
+
+    split = (22, 20, 22) if D == 64 else (44, 42, 42)
+    cfg = dict(B=2, grid=grid, H=3, D=D, split=split, dtype="bf16", seed=99 + D + grid[2])
+    q, k, v = wl.self_attn_inputs(cfg)
+    ref = oracle.self_attn(q, k, v, grid, split)
+    for shape in sorted(SHAPES):
+        out = to_f64(run_self(cfg, q, k, v, flags=FP8 | SHAPES[shape], out_dtype=torch.float32))
+        if int(np.prod(grid)) == 1:
+            assert np.array_equal(out, ref)
+        else:
+            check(out, ref, what="ragged %s D=%d %s" % (grid, D, shape), rms_bound=False, v=v)
+
+
+def test_wider_scores_scale_the_error():
+    """q, k scaled x2 with scale 0.11: scores ~ N(0, 5^2), non-zero origin, other base.  The error
+    follows the score spread, as the derivation says."""
+    import torch
+
+    cfg = dict(B=1, grid=(3, 9, 17), H=2, D=128, split=(44, 42, 42), dtype="bf16", seed=4242)
+    q, k, v = wl.self_attn_inputs(cfg, gain=2.0)
+    kw = dict(origin=(5, -3, 11), scale=0.11)
+    ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], base=500.0, **kw)
+    out = run_self(cfg, q, k, v, flags=FP8, out_dtype=torch.float32, rope_base=500.0, **kw)
+    sigma_s = 0.11 * 4.0 * np.sqrt(128.0)
+    check(to_f64(out), ref, sigma_s=sigma_s, what="peaky", rms_bound=False, v=v)
+    e = to_f64(out) - ref
+    assert np.sqrt(np.mean(e * e)) / np.sqrt(np.mean(ref * ref)) < 1.35 * PREDICTED * sigma_s
+
+
+def test_normalised_q_k_and_packed_requests():
+    """Token-mode q/k normalisation ahead of the 8-bit rounding; packed requests of mixed sizes."""
+    import torch
+
+    cfg = wl.CONFIGS["mid"]
+    q, k, v = wl.self_attn_inputs(cfg, gain=3.0)
+    gq, gk = wl.norm_weights(cfg)
+    ref = oracle.self_attn_normed(q, k, v, cfg["grid"], cfg["split"], gq, gk, 1e-6, "token")
+    out = run_self(cfg, q, k, v, flags=FP8, out_dtype=torch.float32, norm=("token", 1e-6, to_dev(gq), to_dev(gk)))
+    # spread of the scores, measured on a corner of the score matrix (the rotation does not change it)
+    sig = float(np.std(np.einsum("blhd,bmhd->bhlm", oracle.qk_rmsnorm(q, gq, 1e-6, "token")[:, :256],
+                                 oracle.qk_rmsnorm(k, gk, 1e-6, "token")[:, :256]))) / np.sqrt(128.0)
+    check(to_f64(out), ref, sigma_s=sig, what="mid normed")
+
+    cfg = wl.CONFIGS["varlen_small"]
+    q, k, v = wl.varlen_attn_inputs(cfg)
+    ref = oracle.self_attn_packed(q, k, v, cfg["grids"], cfg["split"])
+    for shape in sorted(SHAPES):
+        out = B.dit_attn_varlen_forward(to_dev(q), to_dev(k), to_dev(v), cfg["grids"], cfg["split"],
+                                        flags=FP8 | SHAPES[shape], out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check(to_f64(out), ref, what="packed requests %s" % shape, v=v)  # (requests of 1 to 1,024 tokens)
+
+
+def test_full_size_sampled_rows_and_resident_tiles():
+    """32,760 tokens x 40 heads x d128, the shape the benchmark times (8-wavefront workgroups): sampled
+    rows of every head; then a second call on the resident 8-bit tiles returns the same bits."""
+    import torch
+
+    cfg = wl.CONFIGS["dit_14b"]
+    q, k, v = wl.self_attn_inputs(cfg)
+    rows = wl.sample_rows(q.shape[1], cfg["seed"], edge=64, n_random=128)
+    ref = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], rows=rows)
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    p = B.self_attn_params(qd, kd, vd, qd, cfg["grid"], cfg["split"], flags=FP8)
+    ws = torch.empty(B.dit_attn_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    out = B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], flags=FP8, workspace=ws)
+    torch.cuda.synchronize()
+    check(to_f64(out[:, torch.from_numpy(rows).cuda()]), ref, what="dit_14b sampled rows, bf16 out")
+    out2 = B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], flags=FP8 | B.DIT_FLAG_KV_RESIDENT,
+                              workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
