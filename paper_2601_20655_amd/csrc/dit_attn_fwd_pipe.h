@@ -181,16 +181,28 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
         uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
         if (i < 2 * NI) {
-            const int c = (wave + NW * (i >> 1)) * 1024;
-            if ((i & 1) == 0)
-                __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
-            else
+            const int r = i >> 1;
+            const int c = (wave + NW * r) * 1024;
+            if ((i & 1) == 0) {
+                // FP8: the 8-bit K' rows and their scale codes fill pieces 0..9 of the K part; whole
+                // rounds move pieces 0..7, the odd load below pieces 8 and 9, the rest stays behind
+                if (!FP8 || (r + 1) * NW <= 8)
+                    __builtin_amdgcn_global_load_lds((gptr_t)(ksrc + c + lane_off), (lptr_t)(kdst + c), 16, 0, 0);
+            } else {
                 __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + c + lane_off), (lptr_t)(vdst + c), 16, 0, 0);
+            }
         } else if (NW == 4 || wave < 4) {
             const int c = (NW * NI + (wave & 1)) * 1024;
-            const uint8_t* osrc = wave < 2 ? ksrc : vsrc;
-            uint8_t* odst = wave < 2 ? kdst : vdst;
-            __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
+            if constexpr (FP8) {
+                const int ck = (8 + (wave & 1)) * 1024;
+                const uint8_t* osrc = wave < 2 ? ksrc + ck : vsrc + c;
+                uint8_t* odst = wave < 2 ? kdst + ck : vdst + c;
+                __builtin_amdgcn_global_load_lds((gptr_t)(osrc + lane_off), (lptr_t)odst, 16, 0, 0);
+            } else {
+                const uint8_t* osrc = wave < 2 ? ksrc : vsrc;
+                uint8_t* odst = wave < 2 ? kdst : vdst;
+                __builtin_amdgcn_global_load_lds((gptr_t)(osrc + c + lane_off), (lptr_t)(odst + c), 16, 0, 0);
+            }
         }
     };
     auto dma_tiles = [&](int tk, int kb_, int tv, int vb_) {
@@ -328,6 +340,9 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     constexpr int LAK = FP8 ? 2 * NKS : LA;  // FP8: a tile's few (32-byte) K' operands are all read up front
     static_assert(LAK <= 2 * NKS && LA <= 4 * NDB && LAK * QB <= NA, "lookahead too deep");
     constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4 && !FP8;
+    // (FP8: all softmax slices stay in part A, whose four long MFMA steps leave the vector ALU to them,
+    // while the other wavefront of the SIMD is in its MFMA-heavy part B; moving half of the slices into
+    // part B measured 8 % slower.)
     constexpr bool COPY = QB == 2;
 
     // Wavefronts of the late half (staggered form) pass the workgroup barrier between the two parts
