@@ -12,6 +12,9 @@ from .dit_oracle import (  # noqa: F401
     qk_rmsnorm,
     self_attn_normed,
     as_f64,
+    e4m3_round,
+    e4m3_quantise_rows,
+    self_attn_fp8_scores,
     rope3d,
     self_attn,
     token_positions,

@@ -227,3 +227,52 @@ def cross_attn_decoupled(q, k, v, split, kv_valid=None, scale=0.0, rows=None):
         part = cross_attn(q, k[:, lo:hi], v[:, lo:hi], val, scale=scale, rows=rows)
         total = part if total is None else total + part
     return total
+
+
+# ---- the optional 8-bit score operands (library flag DIT_FLAG_QK_FP8), written out as a definition ----
+
+E4M3_MAX = 448.0
+
+
+def e4m3_round(x):
+    """Nearest value of the OCP 8-bit floating-point format E4M3 (1 sign, 4 exponent bits with bias
+    7, 3 mantissa bits; normal numbers 2^-6 .. 448, subnormals in steps of 2^-9), ties to the even
+    mantissa, magnitudes beyond 448 saturate to 448.  Input and result float64."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    _, ex = np.frexp(np.maximum(a, 2.0 ** -6))  # a in [2^(ex-1), 2^ex); below 2^-6 the subnormal step applies
+    step = np.ldexp(1.0, ex - 1 - 3)
+    r = np.minimum(np.round(a / step) * step, E4M3_MAX)  # numpy rounds halves to even
+    return np.copysign(r, x)
+
+
+def e4m3_quantise_rows(x):
+    """Each row (last axis) is multiplied by the power of two that brings its largest magnitude
+    into [128, 256), rounded to E4M3, and divided back; an all-zero row stays zero.  Returns the
+    float64 values the 8-bit operands stand for."""
+    x = np.asarray(x, dtype=np.float64)
+    amax = np.max(np.abs(x), axis=-1, keepdims=True)
+    _, ex = np.frexp(amax)  # amax in [2^(ex-1), 2^ex)
+    e = np.where(amax > 0, 8 - ex, 0)
+    return np.ldexp(e4m3_round(np.ldexp(x, e)), -e)
+
+
+def self_attn_fp8_scores(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, scale=0.0):
+    """Self-attention whose SCORE operands are rounded to E4M3: q' = rope(q) * scale * log2(e) and
+    k' = rope(k), each row quantised by e4m3_quantise_rows; scores = q' k'^T (in base-2 units),
+    softmax and the value product in float64.  q, k, v: [B, L, H, D]; returns [B, L, H, D] float64.
+    Sizes the plain numpy products below can hold (L up to a few thousand)."""
+    q, k, v = as_f64(q), as_f64(k), as_f64(v)
+    B, L, H, D = q.shape
+    pos = token_positions(grid, origin)
+    if scale <= 0:
+        scale = 1.0 / np.sqrt(D)
+    out = np.empty_like(q)
+    for b in range(B):
+        for h in range(H):
+            qr = e4m3_quantise_rows(rope3d(q[b, :, h], pos, split, base) * (scale * np.log2(np.e)))
+            kr = e4m3_quantise_rows(rope3d(k[b, :, h], pos, split, base))
+            s = qr @ kr.T
+            p = np.exp2(s - s.max(axis=1, keepdims=True))
+            out[b, :, h] = (p @ v[b, :, h]) / p.sum(axis=1, keepdims=True)
+    return out

@@ -514,3 +514,91 @@ def test_oracle_matches_its_stored_regression_values():
         fa = np.array([float(x) for x in ta if "e" in x and x[0] in "-0123456789"])
         fb = np.array([float(x) for x in tb if "e" in x and x[0] in "-0123456789"])
         np.testing.assert_allclose(fa, fb, rtol=1e-12, atol=1e-15)
+
+
+# ---- the 8-bit score operands (E4M3) ----
+
+def e4m3_code_values():
+    """All finite E4M3 values, decoded from the format's definition: sign, 4 exponent bits (bias 7),
+    3 mantissa bits; exponent field 0 = subnormal m/8 * 2^-6; field 15 with mantissa 7 = NaN."""
+    vals = []
+    for code in range(256):
+        s, e, m = code >> 7, (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            continue
+        mag = (m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        vals.append((-mag if s else mag, m))
+    return vals
+
+
+def test_e4m3_round_pins(rng):
+    vals = e4m3_code_values()
+    mags = sorted({abs(x) for x, _ in vals})
+    assert len(mags) == 127 and mags[0] == 0.0 and mags[1] == 2.0 ** -9 and mags[-1] == 448.0
+    # every code value is a fixed point; a point between two neighbours goes to the nearer one
+    allv = np.array([x for x, _ in vals])
+    assert np.array_equal(oracle.e4m3_round(allv), allv)
+    lo, hi = np.array(mags[:-1]), np.array(mags[1:])
+    assert np.array_equal(oracle.e4m3_round(lo + 0.25 * (hi - lo)), lo)
+    assert np.array_equal(oracle.e4m3_round(-(lo + 0.75 * (hi - lo))), -hi)
+    # ties go to the neighbour with the even mantissa
+    mant = {abs(x): m for x, m in vals}
+    tie = oracle.e4m3_round(0.5 * (lo + hi))
+    for t, a, b in zip(tie, lo, hi):
+        assert t == (a if mant[a] % 2 == 0 else b)
+    # hand values: step 2^-5 below 0.5, step 2 between 16 and 32, saturation, the smallest tie
+    assert np.array_equal(oracle.e4m3_round([0.3, 17.0, 19.0, 500.0, -1e9, 2.0 ** -10, 3 * 2.0 ** -10]),
+                          [0.3125, 16.0, 20.0, 448.0, -448.0, 0.0, 2.0 ** -8])
+    # an independent library routine: torch's cast to float8_e4m3fn
+    import torch
+
+    x = np.concatenate([rng.normal(size=20000) * s for s in (1e-3, 0.05, 1.0, 30.0, 150.0)]).astype(np.float32)
+    x = x[np.abs(x) <= 448.0]
+    ref = torch.from_numpy(x).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(oracle.e4m3_round(x.astype(np.float64)), ref)
+
+
+def test_e4m3_quantise_rows_pins(rng):
+    # values with at most 4 significant bits, within 2^14 of the row's largest: unchanged
+    x = np.array([[3.0, -0.75, 1.5, 0.09375, 0.0, 13.0 * 2.0 ** -12], [-15.0 * 2.0 ** 40, 2.0 ** 30, 9.0 * 2.0 ** 35, 0, 0, 0]])
+    assert np.array_equal(oracle.e4m3_quantise_rows(x), x)
+    assert np.array_equal(oracle.e4m3_quantise_rows(np.zeros((2, 5))), np.zeros((2, 5)))
+    # a power of two in front of a row changes nothing else; rows do not influence each other
+    y = rng.normal(size=(7, 64))
+    qy = oracle.e4m3_quantise_rows(y)
+    assert np.array_equal(oracle.e4m3_quantise_rows(y * 2.0 ** -17), qy * 2.0 ** -17)
+    assert np.array_equal(oracle.e4m3_quantise_rows(y[3:4]), qy[3:4])
+    # the scaled row tops out in [128, 256): elements round with 4 significant bits (relative error
+    # at most 2^-4) down to 2^-6 / 256 of the largest; the largest element itself keeps that bound
+    big = np.abs(y) >= np.max(np.abs(y), axis=1, keepdims=True) * 2.0 ** -13
+    assert np.all(np.abs(qy - y)[big] <= 2.0 ** -4 * np.abs(y)[big])
+    # hand-worked row: largest 5.3 -> factor 2^5 (169.6 in [128, 256)), steps 16/32 = 0.5 in [4, 8),
+    # 2/32 = 0.0625 in [0.5, 1), subnormal step 2^-9 / 32 below 2^-6 / 32
+    assert np.array_equal(oracle.e4m3_quantise_rows(np.array([[5.3, 0.7, 2.0 ** -13]])),
+                          [[5.5, 0.6875, 2.0 ** -13]])
+    # (1.4 * 2^-15 * 32 = 0.7 * 2^-9 -> one subnormal step; 0.4 * 2^-14 * 32 = 0.4 * 2^-9 -> zero)
+    assert np.array_equal(oracle.e4m3_quantise_rows(np.array([[5.3, 2.0 ** -15 * 1.4, 2.0 ** -14 * 0.4]])),
+                          [[5.5, 2.0 ** -14, 0.0]])
+
+
+def test_self_attn_fp8_scores_pins(rng, monkeypatch):
+    grid, split, D = (2, 3, 20), (22, 20, 22), 64
+    L = int(np.prod(grid))
+    q, k, v = (rng.normal(size=(1, L, 2, D)) for _ in range(3))
+    kw = dict(origin=(3, -1, 2), base=300.0, scale=0.2)
+    exact = oracle.self_attn(q, k, v, grid, split, **kw)
+    # with the rounding taken out, the routine is the plain definition (rotation, scale, base-2 softmax)
+    import oracle.dit_oracle as impl
+
+    with monkeypatch.context() as mp:
+        mp.setattr(impl, "e4m3_quantise_rows", lambda x: np.asarray(x, dtype=np.float64))
+        assert np.max(np.abs(oracle.self_attn_fp8_scores(q, k, v, grid, split, **kw) - exact)) < 1e-12
+    # with it, the result moves by what the rounding model predicts: relative operand error of RMS
+    # 2^-4 / sqrt(3) * 0.7355 on both sides, score spread sigma_s = scale * sqrt(D) for unit inputs
+    got = oracle.self_attn_fp8_scores(q, k, v, grid, split, **kw)
+    err = np.sqrt(np.mean((got - exact) ** 2)) / np.sqrt(np.mean(exact ** 2))
+    predicted = 2.0 ** -4 / math.sqrt(3.0) * 0.7355 * math.sqrt(2.0) * (0.2 * math.sqrt(D))
+    assert 0.6 * predicted < err < 1.4 * predicted, (err, predicted)
+    # a single key: the output is that value row whatever the scores round to
+    one = oracle.self_attn_fp8_scores(q[:, :1], k[:, :1], v[:, :1], (1, 1, 1), split)
+    assert np.array_equal(one, v[:, :1])
