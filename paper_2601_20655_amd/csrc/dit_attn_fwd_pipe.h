@@ -14,6 +14,9 @@
 // accumulator filled with -m instead of zero, so exp2 applies to the MFMA result directly and the
 // per-score subtraction disappears from the vector ALU.  When a row's maximum has to move (rare,
 // thresholded), the accumulator, the row sum and the pending score tile are shifted together.
+//
+// QK_OP = OP_FP8 swaps the score product for the 8-bit MFMA (64 channels per instruction, row factors
+// applied by the instruction); everything after the scores is the same code.
 #pragma once
 #include <type_traits>
 

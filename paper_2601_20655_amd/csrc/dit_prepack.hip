@@ -1,9 +1,10 @@
 // Memory-bound helper kernels that run before the attention kernel on the same stream:
 //  * rope_table_kernel: (cos, sin) of every (axis, position, pair) angle, evaluated in fp64
 //    and stored as fp32, so that the rotation itself never calls a transcendental.
-//  * kv_prepack_kernel: rotates K, rounds K' and V once to the 16-bit MFMA operand types and
-//    writes each 64-key tile as the exact byte image the attention kernel keeps in LDS
-//    (K' rows, then V^T rows with keys permuted into the order the PV product consumes).
+//  * kv_prepack_kernel: rotates K, rounds K' and V once to the MFMA operand types (16-bit, or for
+//    K' 8-bit E4M3 with one power-of-two factor per row) and writes each 64-key tile as the exact
+//    byte image the attention kernel keeps in LDS (K' rows, then V^T rows with keys permuted into
+//    the order the PV product consumes).
 #include "dit_attn_device.h"
 
 namespace dit {
