@@ -68,3 +68,48 @@ def test_graph_replay_matches_eager():
         torch.cuda.synchronize()
         assert torch.equal(out, ref), "self-attention replay %d differs from eager" % rep
         assert torch.equal(cout, cref), "cross-attention replay %d differs from eager" % rep
+
+
+def test_graph_replay_of_the_other_entry_points_and_flags():
+    """Packed requests with token-mode q/k normalisation, the 8-bit score path, and a cross-attention
+    call on resident tiles, all captured into one graph and replayed with eager work in between."""
+    import torch
+
+    vcfg = wl.CONFIGS["varlen_small"]
+    vq, vk, vv = (to_dev(a) for a in wl.varlen_attn_inputs(vcfg))
+    gq, gk = (to_dev(a) for a in wl.norm_weights(vcfg))
+    norm = ("token", 1e-6, gq, gk)
+    cfg, q, k, v, cq, ck, cv, valid = _inputs()
+    vd = torch.from_numpy(valid).cuda()
+    grids = list(vcfg["grids"])
+
+    vout, out8, cout = torch.empty_like(vq), torch.empty_like(q), torch.empty_like(cq)
+    big = 64 << 20
+    vws, ws8, cws = (torch.empty(big, dtype=torch.uint8, device="cuda") for _ in range(3))
+    vref = B.dit_attn_varlen_forward(vq, vk, vv, grids, vcfg["split"], norm=norm, workspace=vws).clone()
+    ref8 = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], flags=B.DIT_FLAG_QK_FP8, workspace=ws8).clone()
+    cref = B.dit_cross_attn_forward(cq, ck, cv, vd, workspace=cws).clone()  # leaves its tiles in cws
+    torch.cuda.synchronize()
+
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            B.dit_attn_varlen_forward(vq, vk, vv, grids, vcfg["split"], norm=norm, out=vout, workspace=vws, stream=side)
+            B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], flags=B.DIT_FLAG_QK_FP8, out=out8, workspace=ws8,
+                               stream=side)
+            B.dit_cross_attn_forward(cq, ck, cv, None, flags=B.DIT_FLAG_KV_RESIDENT, out=cout, workspace=cws,
+                                     stream=side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (vout, out8, cout):
+            t.fill_(-3.0)
+        vws.fill_(rep)  # rebuilt by every replay; cws keeps the resident tiles and is left alone
+        ws8.fill_(rep)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(vout, vref), "packed requests, replay %d" % rep
+        assert torch.equal(out8, ref8), "8-bit scores, replay %d" % rep
+        assert torch.equal(cout, cref), "resident cross-attention, replay %d" % rep
