@@ -29,7 +29,8 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     }
 }
 
-// acc + lo + hi of one packed operand pair, summed in fp32 (one v_dot2c against (1, 1)).
+// acc + lo + hi of one packed operand pair, summed in fp32 (one v_dot2c against (1, 1)).  Used for bf16
+// probabilities only: the instruction does not overlap with a running MFMA.
 template <int OP>
 __device__ __forceinline__ float sum2(uint32_t packed, float acc) {
     if constexpr (OP == OP_F16) {

@@ -319,20 +319,28 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) S[kb][qb][r] = __builtin_amdgcn_exp2f(S[kb][qb][r] - mr);
-                // The row sum is taken over the ROUNDED probabilities, the same numbers the PV
-                // product consumes, so numerator and denominator stay consistent.
-                float lsum = 0.f;
+                // fp16 P: the row sum is taken in fp32 over the unrounded probabilities, four chains of
+                // plain additions: the dot-product instruction that would sum the packed pairs does
+                // not overlap with a running MFMA (measured: about 8 clocks each, unhidden), additions
+                // do.  Numerator and denominator then differ by at most 2^-11 relative.
+                float lsum4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kg = 0; kg < 4; ++kg) {
                     const int o = 8 * (kg & 1);
                     const f32x16& s = S[kg >> 1][qb];
                     P[kg][qb] = mk4(pack2<PV_OP>(s[o + 0], s[o + 1]), pack2<PV_OP>(s[o + 2], s[o + 3]),
                                     pack2<PV_OP>(s[o + 4], s[o + 5]), pack2<PV_OP>(s[o + 6], s[o + 7]));
-                    lsum = sum2<PV_OP>(P[kg][qb].x, lsum);
-                    lsum = sum2<PV_OP>(P[kg][qb].y, lsum);
-                    lsum = sum2<PV_OP>(P[kg][qb].z, lsum);
-                    lsum = sum2<PV_OP>(P[kg][qb].w, lsum);
+                    if constexpr (PV_OP == OP_F16) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) lsum4[e & 3] += s[o + e];
+                    } else {  // bf16 P: sum the rounded values, which cancels their (8-bit) rounding error
+                        lsum4[0] = sum2<PV_OP>(P[kg][qb].x, lsum4[0]);
+                        lsum4[1] = sum2<PV_OP>(P[kg][qb].y, lsum4[1]);
+                        lsum4[2] = sum2<PV_OP>(P[kg][qb].z, lsum4[2]);
+                        lsum4[3] = sum2<PV_OP>(P[kg][qb].w, lsum4[3]);
+                    }
                 }
+                const float lsum = (lsum4[0] + lsum4[1]) + (lsum4[2] + lsum4[3]);
                 l_run[qb] += lsum;
             }
 

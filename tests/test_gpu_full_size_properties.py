@@ -27,7 +27,8 @@ def test_constant_values_come_back_for_every_row():
     vd = cd.to(torch.bfloat16)[None, None].expand(1, qd.shape[1], H, D).contiguous()
     out = B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out_dtype=torch.float32)
     torch.cuda.synchronize()
-    # probabilities are rounded to 11 significant bits and summed in the same rounded form
+    # probabilities are rounded to 11 significant bits for the PV product and summed unrounded in fp32:
+    # over 32,760 keys the two agree to far better than the 2^-11 of a single rounding
     err = (out[0] - cd[None]).abs().max().item()
     print("constant V, all rows: max|out - c| = %.3e (max|c| = %.2f)" % (err, float(np.abs(c).max())))
     assert err <= 1e-4 * float(np.abs(c).max())
@@ -116,4 +117,6 @@ def test_cross_attention_ignores_padded_keys_for_every_row():
         want = c[None, None] * (2.0 if split else 1.0)  # two softmaxes, each returns c
         err = (out - want).abs().max().item()
         print("cross constant V (split=%d), all rows: max|out - c| = %.3e" % (split, err))
-        assert err <= 1e-4 * c.abs().max().item()
+        # P is rounded to 11 significant bits for the PV product and summed unrounded: a row whose mass
+        # sits on one key is off by up to 2^-11 relative (rows over thousands of keys average it out)
+        assert err <= 1.1 * 2.0 ** -11 * (2.0 if split else 1.0) * c.abs().max().item()
