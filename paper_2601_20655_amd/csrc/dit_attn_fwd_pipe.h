@@ -27,7 +27,7 @@
 #define DIT_PIPE_LA 6   // LDS fragment reads are issued this many fragments ahead of their MFMA
 #endif
 #ifndef DIT_PIPE_PRE
-#define DIT_PIPE_PRE 4  // exp slices issued before the first MFMA of an iteration (covers LDS latency)
+#define DIT_PIPE_PRE 2  // exp2 of a softmax slice runs this many slices ahead of its pack (and before the first MFMA)
 #endif
 
 #ifndef DIT_PIPE_STAGGER
@@ -36,22 +36,7 @@
 #ifndef DIT_PIPE_PRIO
 #define DIT_PIPE_PRIO 1  // staggered form: wavefront priority raised during part A (1), part B (2), never (0)
 #endif
-#ifndef DIT_PIPE_BALANCED
-#define DIT_PIPE_BALANCED 1  // move 6 of the 16 softmax slices from part A into part B (32-row wavefronts, d128)
-#endif
-
 namespace dit {
-
-// Balanced schedule (16 MFMA steps per part, 16 softmax slices): which slice gets its exp2 / its
-// pack+sum after MFMA step t of part A resp. step u of part B (-1: none).  Slices 0..3 take their
-// exp2 before step 0.  A slice is packed at least two steps after its exp2, and part B's PV steps
-// 4*kg.. read the packed slices 4*kg..4*kg+3, so slice c must be packed before step 4*(c/4).
-constexpr int bal_a_exp(int t) { return (t % 2 == 0 && t <= 10) ? 4 + t / 2 : -1; }
-constexpr int bal_a_pack(int t) { return (t % 2 == 1 && t <= 11) ? t / 2 : (t >= 12 ? t - 6 : -1); }
-constexpr int bal_b_exp(int u) { return u <= 2 ? 10 + u : ((u % 2 == 0 && u <= 8) ? 11 + u / 2 : -1); }
-constexpr int bal_b_pack(int u) {
-    return (u % 2 == 1 && u >= 3 && u <= 9) ? 10 + (u - 3) / 2 : (u == 10 ? 14 : (u == 11 ? 15 : -1));
-}
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -342,7 +327,10 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
     static_assert(CPA * NA == NCH && CPB * NB == NCH, "slices must divide evenly over MFMA steps");
     constexpr int LAK = FP8 ? 2 * NKS : LA;  // FP8: a tile's few (32-byte) K' operands are all read up front
     static_assert(LAK <= 2 * NKS && LA <= 4 * NDB && LAK * QB <= NA, "lookahead too deep");
-    constexpr bool BAL = DIT_PIPE_BALANCED && QB == 1 && D == 128 && PRE == 4 && !FP8;
+    // All softmax slices of tile j run in part A, under the score MFMAs of tile j + 1, while the SIMD's
+    // other wavefront is in its part B (PV MFMAs and the cheap maxima).  Spreading the slices over both
+    // parts paid while each slice carried a v_dot2c; since the row sums are plain additions it measures
+    // 2.7 % slower than this.
     // (FP8: all softmax slices stay in part A, whose four long MFMA steps leave the vector ALU to them,
     // while the other wavefront of the SIMD is in its MFMA-heavy part B; moving half of the slices into
     // part B measured 8 % slower.)
@@ -424,16 +412,11 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
                 if (t >= NA - LA) vf[t - (NA - LA)] = vfrag(t - (NA - LA));
             }
             Sn[kb][qb] = score_mfma(kf[f], Qf[qb][ks], ks == 0 ? negm[qb] : Sn[kb][qb], kc[kb], q_code[qb]);
-            if constexpr (BAL) {
-                if (bal_a_exp(t) >= 0) exp_slice(bal_a_exp(t));
-                if (bal_a_pack(t) >= 0) pack_slice(bal_a_pack(t));
-            } else {
 #pragma unroll
-                for (int cc = 0; cc < CPA; ++cc) {
-                    const int c = t * CPA + cc;
-                    if (c + PRE < NCH) exp_slice(c + PRE);
-                    pack_slice(c);
-                }
+            for (int cc = 0; cc < CPA; ++cc) {
+                const int c = t * CPA + cc;
+                if (c + PRE < NCH) exp_slice(c + PRE);
+                pack_slice(c);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -476,10 +459,6 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             if (u >= 2) {
 #pragma unroll
                 for (int cc = 0; cc < CPB; ++cc) max_slice((u - 2) * CPB + cc);
-            }
-            if constexpr (BAL) {
-                if (bal_b_exp(u) >= 0) exp_slice(bal_b_exp(u));
-                if (bal_b_pack(u) >= 0) pack_slice(bal_b_pack(u));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
