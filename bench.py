@@ -27,7 +27,7 @@ PEAK_TFLOPS_8BIT_DENSE = 5000.0   # published dense fp8 MFMA peak
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
 # keyed by library version: a library whose kernel has changed since reports null.
 # (111 added a host-side flag only and 112 separate instantiations; their default kernel is that of 110.)
-TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9}
+TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9}
 
 
 class HipEvents:
