@@ -26,8 +26,9 @@ PEAK_TFLOPS_8BIT_DENSE = 5000.0   # published dense fp8 MFMA peak
 # HBM bytes per launch of the self-attention kernel at the dit_14b shape, default flags, from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
 # keyed by library version: a library whose kernel has changed since reports null.
-# (111 added a host-side flag only and 112 separate instantiations; their default kernel is that of 110.)
-TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9}
+# (111 added a host-side flag only and 112 separate instantiations; their default kernel is that of 110.
+# 115 changed the cross-attention workgroup order only; its self-attention kernel is that of 114, checked byte for byte.)
+TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9, 115: 3.92e9}
 
 
 class HipEvents:

@@ -49,9 +49,23 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
         const int chunk = nblk >> 3, rem = nblk & 7;
         logical = xcd * chunk + (xcd < rem ? xcd : rem) + idx;
     }
-    const int qt = logical % a.nQT;
-    const int bh = logical / a.nQT;
-    const int b = bh / a.H, h = bh - b * a.H;
+    // Self-attention: consecutive workgroups are the query tiles of one (batch, head).  With per-request
+    // key lists (cross-attention) requests differ in length, so they are interleaved instead: every
+    // XCD gets the same share of every request (contiguous ranges would leave the XCDs unequal work),
+    // and the workgroups that share a CU are of different lengths and drift out of lock step.
+    int qt, b, h;
+    if (a.tile_mask) {
+        b = logical % a.B;
+        const int rest = logical / a.B;
+        qt = rest % a.nQT;
+        h = rest / a.nQT;
+    } else {
+        qt = logical % a.nQT;
+        const int bh_ = logical / a.nQT;
+        b = bh_ / a.H;
+        h = bh_ - b * a.H;
+    }
+    const int bh = b * a.H + h;
 
     // ---- staging of K/V tiles ----
     const int kchunk_off = (tid / CPR) * G::KROW + (tid % CPR) * 16;

@@ -649,11 +649,19 @@ __device__ __forceinline__ int xcd_contiguous_block() {
 template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
 __global__ void __launch_bounds__(64 * NW, QB == 1 ? 2 : 1) attn_fwd_pipe_kernel(const AttnArgs a) {
     const int logical = xcd_contiguous_block();
-    const int bh = logical / a.nQT;
     PipeView pv;
-    pv.qt = logical % a.nQT;
-    pv.b = bh / a.H;
-    pv.h = bh - pv.b * a.H;
+    if constexpr (LISTED) {  // requests of different lengths: interleaved (see attn_fwd_kernel)
+        pv.b = logical % a.B;
+        const int rest = logical / a.B;
+        pv.qt = rest % a.nQT;
+        pv.h = rest / a.nQT;
+    } else {
+        const int bh_ = logical / a.nQT;
+        pv.qt = logical % a.nQT;
+        pv.b = bh_ / a.H;
+        pv.h = bh_ - pv.b * a.H;
+    }
+    const int bh = pv.b * a.H + pv.h;
     pv.Lq = a.Lq;
     pv.Lk = a.Lk;
     pv.nKT = a.nKT;
