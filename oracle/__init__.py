@@ -15,6 +15,7 @@ from .dit_oracle import (  # noqa: F401
     e4m3_round,
     e4m3_quantise_rows,
     self_attn_fp8_scores,
+    linear,
     rope3d,
     self_attn,
     token_positions,

@@ -276,3 +276,17 @@ def self_attn_fp8_scores(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, s
             p = np.exp2(s - s.max(axis=1, keepdims=True))
             out[b, :, h] = (p @ v[b, :, h]) / p.sum(axis=1, keepdims=True)
     return out
+
+
+def linear(x, w, bias=None):
+    """Dense projection of token rows, y = x w^T + bias: the query/key/value and output projections
+    either side of attention in a block of the Diffusion stage (Section 2.4, the AIGC workflow;
+    the model is the cited video transformer, whose layers store a weight as [out, in]).
+
+    x: [M, K], w: [N, K], bias: [N] or None; uint16 bf16 bit patterns, float32 or float64.
+    Returns float64 [M, N]: every input converted exactly, one fp64 matrix product.
+    """
+    y = as_f64(x) @ as_f64(w).T
+    if bias is not None:
+        y = y + as_f64(bias)[None, :]
+    return y

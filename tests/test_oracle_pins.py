@@ -602,3 +602,28 @@ def test_self_attn_fp8_scores_pins(rng, monkeypatch):
     # a single key: the output is that value row whatever the scores round to
     one = oracle.self_attn_fp8_scores(q[:, :1], k[:, :1], v[:, :1], (1, 1, 1), split)
     assert np.array_equal(one, v[:, :1])
+
+
+def test_linear_pins(rng):
+    """y = x w^T + bias with w stored [out, in]: brute force by loops in Python floats, the
+    identity and one-hot weights (which catch a transposed operand), a rectangular shape (which
+    catches swapped M/N), additivity in the bias, and exact widening of 16-bit inputs."""
+    M, N, K = 5, 3, 7
+    x, w, b = rng.normal(size=(M, K)), rng.normal(size=(N, K)), rng.normal(size=N)
+    y = oracle.linear(x, w, b)
+    assert y.shape == (M, N) and y.dtype == np.float64
+    for m in range(M):
+        for n in range(N):
+            acc = math.fsum(float(x[m, k]) * float(w[n, k]) for k in range(K)) + float(b[n])
+            assert abs(y[m, n] - acc) < 1e-13
+    # one-hot rows of w pick columns of x; w[n, k] = 1 means output n reads input k
+    sel = np.zeros((N, K))
+    sel[0, 4] = sel[1, 0] = sel[2, 6] = 1.0
+    assert np.array_equal(oracle.linear(x, sel), x[:, [4, 0, 6]])
+    assert np.array_equal(oracle.linear(x, np.eye(K)), x)
+    assert np.max(np.abs(oracle.linear(x, w) + b[None, :] - y)) < 1e-14
+    # bf16 bit patterns widen exactly: 0x3FC0 = 1.5, 0xC000 = -2, 0x3E80 = 0.25
+    xb = np.array([[0x3FC0, 0xC000]], dtype=np.uint16)
+    wb = np.array([[0x3E80, 0x3FC0], [0xC000, 0x3E80]], dtype=np.uint16)
+    assert np.array_equal(oracle.linear(xb, wb, np.array([0x3FC0, 0x0000], dtype=np.uint16)),
+                          np.array([[1.5 * 0.25 - 2 * 1.5 + 1.5, -3.0 - 0.5]]))
