@@ -240,6 +240,31 @@ dit_status dit_attn_varlen_forward(const void *q, const void *k, const void *v, 
                                    size_t workspace_bytes, void *stream);
 
 /*
+ * Dense projection of token rows: y[m, n] = sum_k x[m, k] * w[n, k] + bias[n] -- the query, key,
+ * value and output projections either side of attention in a transformer block of the Diffusion
+ * stage (Sec. 2.4); weights are stored [out features, in features] as the model's linear layers
+ * keep them, so the fused q/k/v projection is one call on the three weights stacked along n.
+ * x: [M, K] bf16, w: [N, K] bf16, bias: [N] bf16 or NULL, y: [M, N] bf16 or fp32 (out_dtype); all
+ * DEVICE pointers, row strides ldx, ldw, ldy in ELEMENTS (>= the row length), element stride 1.
+ * Products are exact in fp32, sums are accumulated in fp32 on the matrix cores (contraction
+ * order unspecified), the bias is added in fp32, the result is rounded once (nearest-even) if bf16.
+ * x and w may not overlap y.  No workspace.
+ * Errors: NULL x/w/y/p, M, N or K < 1, a stride shorter than its row, bad out_dtype or nonzero
+ * flags -> DIT_ERR_INVALID_ARG; K not a multiple of 64 or N not a multiple of 8 ->
+ * DIT_ERR_UNSUPPORTED; a base pointer or row stride that breaks 16-byte row alignment (8 bytes for
+ * bias) -> DIT_ERR_ALIGNMENT.
+ */
+typedef struct {
+    int32_t M, N, K;
+    int64_t ldx, ldw, ldy;
+    int32_t out_dtype; /* DIT_BF16 or DIT_F32 */
+    uint32_t flags;    /* reserved, must be 0 */
+} dit_linear_params;
+
+dit_status dit_linear_forward(const void *x, const void *w, const void *bias, void *y,
+                              const dit_linear_params *p, void *stream);
+
+/*
  * Timing hook for benchmarks and profilers (not part of the attention definition): while
  * both handles are non-NULL, every forward call made by the calling thread records the
  * hipEvent_t `before` on the stream just before the attention kernel and `after` just after

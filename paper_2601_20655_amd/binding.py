@@ -42,6 +42,7 @@ EXPORTS = (
     "dit_cross_attn_forward",
     "dit_attn_varlen_workspace_bytes",
     "dit_attn_varlen_forward",
+    "dit_linear_forward",
     "dit_attn_set_timing_events",
     "dit_strerror",
     "dit_last_hip_error",
@@ -110,6 +111,14 @@ class dit_varlen_attn_params(ctypes.Structure):
     ]
 
 
+class dit_linear_params(ctypes.Structure):
+    _fields_ = [
+        ("M", ctypes.c_int32), ("N", ctypes.c_int32), ("K", ctypes.c_int32),
+        ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldy", ctypes.c_int64),
+        ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+    ]
+
+
 class DitError(RuntimeError):
     def __init__(self, status, what):
         self.status = int(status)
@@ -146,6 +155,8 @@ def lib():
         L.dit_attn_varlen_forward.restype = ctypes.c_int
         L.dit_attn_varlen_forward.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(dit_varlen_attn_params), vp,
                                               ctypes.c_size_t, vp]
+        L.dit_linear_forward.restype = ctypes.c_int
+        L.dit_linear_forward.argtypes = [vp, vp, vp, vp, ctypes.POINTER(dit_linear_params), vp]
         L.dit_attn_set_timing_events.restype = None
         L.dit_attn_set_timing_events.argtypes = [vp, vp]
         L.dit_strerror.restype = ctypes.c_char_p
@@ -353,3 +364,32 @@ def dit_attn_varlen_forward(q, k, v, grids, split, out=None, lse=None, origin=(0
     if st != DIT_OK:
         raise DitError(st, "dit_attn_varlen_forward")
     return (out, lse) if lse is not None else out
+
+
+def linear_params(x, w, y, flags=0):
+    if x.dim() != 2 or w.dim() != 2 or y.dim() != 2 or x.stride(1) != 1 or w.stride(1) != 1 or y.stride(1) != 1:
+        raise ValueError("expected 2-D tensors with contiguous rows")
+    if x.shape[1] != w.shape[1] or tuple(y.shape) != (x.shape[0], w.shape[0]):
+        raise ValueError("shapes do not fit y[M, N] = x[M, K] w[N, K]^T")
+    return dit_linear_params(x.shape[0], w.shape[0], x.shape[1], x.stride(0), w.stride(0), y.stride(0),
+                             _dtype_code(y), flags)
+
+
+def dit_linear_forward(x, w, bias=None, out=None, out_dtype=None, stream=None):
+    """y = x w^T + bias: x [M, K] bf16, w [N, K] bf16, bias [N] bf16 or None; y [M, N] bf16 or fp32."""
+    import torch
+
+    if not x.is_cuda:
+        raise ValueError("dit_linear_forward needs device tensors")
+    if x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or (bias is not None and bias.dtype != torch.bfloat16):
+        raise TypeError("x, w and bias must be bfloat16")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != w.shape[0] or bias.stride(0) != 1):
+        raise ValueError("bias must be a dense [N] tensor")
+    if out is None:
+        out = torch.empty((x.shape[0], w.shape[0]), dtype=out_dtype or x.dtype, device=x.device)
+    p = linear_params(x, w, out)
+    st = lib().dit_linear_forward(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                  out.data_ptr(), ctypes.byref(p), _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_linear_forward")
+    return out

@@ -618,6 +618,42 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     return DIT_OK;
 }
 
+dit_status dit_linear_forward(const void* x, const void* w, const void* bias, void* y, const dit_linear_params* p,
+                              void* stream) {
+    if (!x || !w || !y || !p) return DIT_ERR_INVALID_ARG;
+    if (p->M < 1 || p->N < 1 || p->K < 1 || p->flags != 0) return DIT_ERR_INVALID_ARG;
+    if (p->ldx < p->K || p->ldw < p->K || p->ldy < p->N) return DIT_ERR_INVALID_ARG;
+    if (p->out_dtype != DIT_BF16 && p->out_dtype != DIT_F32) return DIT_ERR_INVALID_ARG;
+    if (p->K % dit::kLinBK != 0 || p->N % 8 != 0) return DIT_ERR_UNSUPPORTED;
+    const size_t ye = p->out_dtype == DIT_F32 ? 4 : 2;
+    if ((uintptr_t)x % 16 || (uintptr_t)w % 16 || (uintptr_t)y % 16 || (p->ldx * 2) % 16 || (p->ldw * 2) % 16 ||
+        (p->ldy * ye) % 16 || (uintptr_t)bias % 8)
+        return DIT_ERR_ALIGNMENT;
+    dit::LinearArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.w = static_cast<const uint16_t*>(w);
+    a.bias = static_cast<const uint16_t*>(bias);
+    a.y = y;
+    a.M = p->M;
+    a.N = p->N;
+    a.K = p->K;
+    a.ldx = p->ldx;
+    a.ldw = p->ldw;
+    a.ldy = p->ldy;
+    a.nTM = (p->M + dit::kLinBM - 1) / dit::kLinBM;
+    a.nTN = (p->N + dit::kLinBN - 1) / dit::kLinBN;
+    a.out_f32 = p->out_dtype == DIT_F32;
+    if ((int64_t)a.nTM * a.nTN > 0x7fffffff) return DIT_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool timed = g_ev_before && g_ev_after;
+    hipError_t e;
+    if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    e = dit::launch_linear(a, s);
+    if (e != hipSuccess) return hip_fail(e, "linear_kernel");
+    if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    return DIT_OK;
+}
+
 void dit_attn_set_timing_events(void* before, void* after) {
     g_ev_before = static_cast<hipEvent_t>(before);
     g_ev_after = static_cast<hipEvent_t>(after);

@@ -145,4 +145,20 @@ hipError_t launch_attn(const AttnArgs& a, int D, int qb, int qk_op, int pv_op, b
 // plain kernel, two softmaxes (AttnArgs::tile_count_a set), 32 rows per wavefront
 hipError_t launch_attn_split(const AttnArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
 
+// ---- dense projection y = x w^T + bias ----
+constexpr int kLinBM = 256;  // tokens per workgroup tile
+constexpr int kLinBN = 256;  // output features per workgroup tile
+constexpr int kLinBK = 64;   // contraction indices per step
+struct LinearArgs {
+    const uint16_t* x;     // [M, K] bf16, row stride ldx
+    const uint16_t* w;     // [N, K] bf16, row stride ldw
+    const uint16_t* bias;  // [N] bf16, nullable
+    void* y;               // [M, N] bf16 or fp32, row stride ldy
+    int M, N, K;           // K a multiple of kLinBK, N a multiple of 8
+    int64_t ldx, ldw, ldy;
+    int nTM, nTN;          // tiles along M and N
+    int out_f32;
+};
+hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
+
 }  // namespace dit

@@ -35,6 +35,12 @@ CONFIGS = {
     "varlen_14b": dict(kind="varlen", grids=((13, 30, 52), (21, 45, 80), (1, 45, 80), (21, 30, 52), (9, 45, 80),
                                              (13, 30, 52), (21, 30, 52)),
                        H=40, D=128, split=(44, 42, 42), dtype="bf16", seed=20655 + 9),
+    # the dense projections either side of attention at 14B width (5,120 = 40 heads x 128): the fused
+    # q/k/v projection (three weights stacked along the output axis) and the output projection
+    "qkv_proj_14b": dict(kind="linear", M=32760, N=3 * 5120, K=5120, seed=20655 + 10),
+    "out_proj_14b": dict(kind="linear", M=32760, N=5120, K=5120, seed=20655 + 11),
+    # all-elements comparison: two full tiles and a ragged one along both M and N, three K steps
+    "proj_small": dict(kind="linear", M=600, N=520, K=192, seed=20655 + 12),
 }
 
 
@@ -109,6 +115,16 @@ def cross_attn_inputs(cfg, seed=None, dtype=None):
         valid[b, : text_len[b]] = 1
         valid[b, cfg["n_text"]:] = 1
     return q, k, v, valid, text_len
+
+
+def linear_inputs(cfg, seed=None):
+    """x [M, K] ~ N(0, 1), w [N, K] ~ N(0, 1/K) (so outputs have unit variance, as after a
+    normalisation layer and a variance-preserving initialisation), bias [N] ~ N(0, 0.1^2); bf16 bits."""
+    seed = cfg["seed"] if seed is None else seed
+    x = normal((cfg["M"], cfg["K"]), seed, 0)
+    w = normal((cfg["N"], cfg["K"]), seed, 1, gain=cfg["K"] ** -0.5)
+    b = normal((cfg["N"],), seed, 2, gain=0.1)
+    return x, w, b
 
 
 def sample_rows(L, seed, edge=64, n_random=128):

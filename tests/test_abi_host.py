@@ -217,6 +217,25 @@ def test_varlen_workspace_and_rejections():
     assert call_varlen(p) == B.DIT_ERR_ALIGNMENT
 
 
+def linear_call(M=64, N=64, K=64, ldx=None, ldw=None, ldy=None, out_dtype=None, flags=0, x=FAKE, w=FAKE, y=FAKE,
+                bias=None):
+    p = B.dit_linear_params(M, N, K, K if ldx is None else ldx, K if ldw is None else ldw, N if ldy is None else ldy,
+                            B.DIT_BF16 if out_dtype is None else out_dtype, flags)
+    return B.lib().dit_linear_forward(x, w, bias, y, ctypes.byref(p), None)
+
+
+def test_linear_rejects_bad_arguments():
+    for kw in (dict(x=0), dict(w=0), dict(y=0), dict(M=0), dict(N=0), dict(K=0), dict(flags=1), dict(out_dtype=2),
+               dict(ldx=56), dict(ldw=56), dict(ldy=56)):
+        assert linear_call(**kw) == B.DIT_ERR_INVALID_ARG, kw
+    assert B.lib().dit_linear_forward(FAKE, FAKE, None, FAKE, None, None) == B.DIT_ERR_INVALID_ARG
+    for kw in (dict(K=96), dict(N=60), dict(K=8)):
+        assert linear_call(**kw) == B.DIT_ERR_UNSUPPORTED, kw
+    for kw in (dict(x=FAKE + 8), dict(w=FAKE + 2), dict(y=FAKE + 4), dict(ldx=68), dict(ldw=70), dict(ldy=68),
+               dict(bias=FAKE + 4), dict(out_dtype=B.DIT_F32, ldy=66)):
+        assert linear_call(**kw) == B.DIT_ERR_ALIGNMENT, kw
+
+
 def test_python_wrappers_refuse_host_tensors():
     import torch
 

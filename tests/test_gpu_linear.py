@@ -1,0 +1,93 @@
+"""GPU parity of the dense projection y = x w^T + bias (dit_linear_forward) against the CPU fp64
+oracle.  Tolerance: the 16-bit inputs are exact on both sides and every product is exact in fp32, so
+the only error is the fp32 accumulation of K terms (at most K * 2^-24 relative to sum |x_k w_k|, in
+practice a random walk) and, for bf16 output, the final rounding (half a unit in the last place).
+With unit-variance outputs sum |x w| is about 0.64 * sqrt(K) * RMS(y); the bound used is
+2^-22 * sqrt(K) * RMS(y) (4.3e-5 * RMS at K = 5,120), far below the 2e-2 of the attention contract."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2601_20655_amd import binding as B
+from paper_2601_20655_amd import workloads as wl
+from gpu_util import compare, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def tol(K):
+    return 2.0 ** -22 * K ** 0.5
+
+
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_small_projection_all_elements(out, with_bias):
+    import torch
+
+    cfg = wl.CONFIGS["proj_small"]
+    x, w, b = wl.linear_inputs(cfg)
+    y = B.dit_linear_forward(to_dev(x), to_dev(w), to_dev(b) if with_bias else None,
+                             out_dtype=torch.float32 if out == "f32" else torch.bfloat16)
+    torch.cuda.synchronize()
+    ref = oracle.linear(x, w, b if with_bias else None)
+    compare(to_f64(y), ref, bf16_out=out == "bf16", tol=tol(cfg["K"]), what="proj_small %s" % out)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 8, 64), (31, 264, 64), (257, 8, 128), (256, 256, 64), (513, 1000, 320)])
+def test_edge_shapes(M, N, K):
+    """One row, one feature quad pair, exact tile multiples, one row past a tile."""
+    import torch
+
+    cfg = dict(M=M, N=N, K=K, seed=31 + M)
+    x, w, b = wl.linear_inputs(cfg)
+    y = B.dit_linear_forward(to_dev(x), to_dev(w), to_dev(b), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    compare(to_f64(y), oracle.linear(x, w, b), tol=tol(K), what="M=%d N=%d K=%d" % (M, N, K))
+
+
+def test_row_strides_and_untouched_padding():
+    """x, w and y are column slices of wider buffers; the columns of y's buffer outside the slice keep
+    their contents."""
+    import torch
+
+    cfg = dict(M=300, N=72, K=128, seed=5)
+    x, w, b = wl.linear_inputs(cfg)
+    xb = torch.zeros((300, 128 + 64), dtype=torch.bfloat16, device="cuda")
+    wb = torch.zeros((72, 128 + 8), dtype=torch.bfloat16, device="cuda")
+    yb = torch.full((300, 72 + 24), 7.0, dtype=torch.float32, device="cuda")
+    xb[:, 64:] = to_dev(x)
+    wb[:, :128] = to_dev(w)
+    B.dit_linear_forward(xb[:, 64:], wb[:, :128], to_dev(b), out=yb[:, 8:80])
+    torch.cuda.synchronize()
+    compare(to_f64(yb[:, 8:80]), oracle.linear(x, w, b), tol=tol(128), what="strided")
+    assert torch.all(yb[:, :8] == 7.0) and torch.all(yb[:, 80:] == 7.0)
+
+
+def test_exact_small_integers():
+    """Integer-valued inputs whose sums fit 24 bits: every output is exact, whatever the order."""
+    import torch
+
+    rng = np.random.default_rng(11)
+    x = rng.integers(-8, 9, size=(260, 192)).astype(np.float32)
+    w = rng.integers(-8, 9, size=(264, 192)).astype(np.float32)
+    bias = rng.integers(-64, 65, size=264).astype(np.float32)
+    xb, wb, bb = (wl.f32_to_bf16_bits(a) for a in (x, w, bias))
+    y = B.dit_linear_forward(to_dev(xb), to_dev(wb), to_dev(bb), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(y), oracle.linear(xb, wb, bb))
+
+
+@pytest.mark.parametrize("name", ["out_proj_14b", "qkv_proj_14b"])
+def test_full_size_sampled_rows(name):
+    """The benchmark's shapes and launch: 192 sampled token rows (first, last, seeded in between),
+    every feature, against the oracle; bf16 output as the benchmark writes it."""
+    import torch
+
+    cfg = wl.CONFIGS[name]
+    x, w, b = wl.linear_inputs(cfg)
+    y = B.dit_linear_forward(to_dev(x), to_dev(w), to_dev(b))
+    torch.cuda.synchronize()
+    rows = wl.sample_rows(cfg["M"], cfg["seed"], edge=40, n_random=112)
+    got = to_f64(y[torch.from_numpy(rows).cuda()])
+    ref = oracle.linear(x[rows], w, b)
+    compare(got, ref, bf16_out=True, tol=tol(cfg["K"]), what=name)
