@@ -24,12 +24,31 @@ namespace {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-constexpr int kLinStage = (kLinBM + kLinBN) * kLinBK * 2;  // bytes of one stage: x tile, then w tile
-constexpr int kLinXBytes = kLinBM * kLinBK * 2;
+#ifndef DIT_LIN_BK
+#define DIT_LIN_BK 64
+#endif
+#ifndef DIT_LIN_STAGES
+#define DIT_LIN_STAGES 2
+#endif
+#ifndef DIT_LIN_WAVES
+#define DIT_LIN_WAVES 8
+#endif
 constexpr int kLinGroup = 8;  // token tiles per group of the workgroup order
 
-template <bool OUT_F32>
-__global__ void __launch_bounds__(512, 1) linear_kernel(const LinearArgs a) {
+// BK contraction indices per step (32 or 64), S stages of LDS, NW wavefronts (8: 128 tokens x 64
+// features each, two per SIMD; 4: 128 x 128 each, one per SIMD with the accumulators in the AGPRs).
+template <int BK, int S, int NW, bool OUT_F32>
+__global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) {
+    static_assert(kLinBM == 256 && kLinBN == 256 && (BK == 32 || BK == 64) && S >= 2, "tile shape");
+    static_assert(NW == 4 || NW == 8, "wavefronts per workgroup");
+    constexpr int FB = 16 / NW;  // 32-feature blocks per wavefront
+    constexpr int kLinStage = (kLinBM + kLinBN) * BK * 2;  // bytes of one stage: x tile, then w tile
+    constexpr int kLinXBytes = kLinBM * BK * 2;
+    constexpr int PPR = BK / 8;         // 16-byte pieces per row
+    constexpr int RPC = 64 / PPR;       // rows per 1 KiB chunk
+    constexpr int RP = 256 / (BK * 2);  // rows per 256 bytes (one sweep of the banks)
+    constexpr int NCH = BK / 2 / NW;    // chunks per wavefront and tile
+    constexpr int ROWB = BK * 2;        // bytes per row
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -54,78 +73,119 @@ __global__ void __launch_bounds__(512, 1) linear_kernel(const LinearArgs a) {
         tn = within / gsz;
     }
 
-    // ---- DMA sources: wavefront w moves 1 KiB chunks w, w+8, w+16, w+24 of both tiles; a chunk is 8
-    // rows.  Rows past the end of x or w are clamped to the last one (their products are never stored).
-    const uint16_t* xsrc[4];
-    const uint16_t* wsrc[4];
+    // ---- DMA sources: wavefront w moves 1 KiB chunks w, w+NW, ... of both tiles; a chunk is RPC rows.
+    // Rows past the end of x or w are clamped to the last one (their products are never stored).
+    const uint16_t* xsrc[NCH];
+    const uint16_t* wsrc[NCH];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = 8 * (wave + 8 * i) + (lane >> 3);
-        const int p = (lane & 7) ^ ((r >> 1) & 7);
+    for (int i = 0; i < NCH; ++i) {
+        const int r = RPC * (wave + NW * i) + lane / PPR;
+        const int p = (lane % PPR) ^ ((r / RP) % PPR);
         int xr = tm * kLinBM + r, wr = tn * kLinBN + r;
         xr = xr < a.M ? xr : a.M - 1;
         wr = wr < a.N ? wr : a.N - 1;
         xsrc[i] = a.x + (int64_t)xr * a.ldx + 8 * p;
         wsrc[i] = a.w + (int64_t)wr * a.ldw + 8 * p;
     }
+    const int nK = a.K / BK;
+    // (a tile number past the end fetches the last tile again, into a stage nobody reads any more:
+    // every step then has the same number of loads in flight, which the counted wait relies on)
     auto dma = [&](int kt, int st) {
+        kt = kt < nK ? kt : nK - 1;
         uint8_t* const xd = smem + st * kLinStage + wave * 1024;
         uint8_t* const wd = xd + kLinXBytes;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(xsrc[i] + kt * kLinBK), (lptr_t)(xd + i * 8192), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wsrc[i] + kt * kLinBK), (lptr_t)(wd + i * 8192), 16, 0, 0);
+        for (int i = 0; i < NCH; ++i) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(xsrc[i] + kt * BK), (lptr_t)(xd + i * NW * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wsrc[i] + kt * BK), (lptr_t)(wd + i * NW * 1024), 16, 0, 0);
         }
     };
 
     // ---- fragment addresses: row base + swizzled piece of contraction step ks ----
-    const int sw = (l32 >> 1) & 7;
-    int koff[4];
+    const int sw = (l32 / RP) % PPR;
+    int koff[BK / 16];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + half) ^ sw) * 16;
-    const int xread = (wt * 128 + l32) * 128;
-    const int wread = kLinXBytes + (wf * 64 + l32) * 128;
+    for (int ks = 0; ks < BK / 16; ++ks) koff[ks] = ((2 * ks + half) ^ sw) * 16;
+    const int xread = (wt * 128 + l32) * ROWB;
+    const int wread = kLinXBytes + (wf * 32 * FB + l32) * ROWB;
 
-    f32x16 acc[2][4];
+    f32x16 acc[FB][4];
 #pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
+    for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
         for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
 
-    const int nK = a.K / kLinBK;
-    dma(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    for (int kt = 0; kt < nK; ++kt) {
-        const int st = kt & 1;
-        // stage st^1 was last read in step kt-1, which every wavefront left through the barrier
-        if (kt + 1 < nK) dma(kt + 1, st ^ 1);
-        const uint8_t* const xs = smem + st * kLinStage + xread;
-        const uint8_t* const ws = smem + st * kLinStage + wread;
+    // Operand fragments of one 16-index slice: 2 of w, 4 of x.  Two sets alternate, so the reads of
+    // the next slice are in flight while the MFMAs of the current one issue.
+    struct Frag {
+        u32x4 w[FB], x[4];
+    };
+    constexpr int NKS = BK / 16;
+    Frag F[2];
+    auto read_frags = [&](Frag& f, int stage, int ks) {
+        const uint8_t* const xs = smem + stage * kLinStage + xread + koff[ks];
+        const uint8_t* const ws = smem + stage * kLinStage + wread + koff[ks];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 wfrag[2], xfrag[4];
+        for (int fb = 0; fb < FB; ++fb) f.w[fb] = *reinterpret_cast<const u32x4*>(ws + fb * 32 * ROWB);
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) wfrag[fb] = *reinterpret_cast<const u32x4*>(ws + fb * 4096 + koff[ks]);
+        for (int tb = 0; tb < 4; ++tb) f.x[tb] = *reinterpret_cast<const u32x4*>(xs + tb * 32 * ROWB);
+    };
+    auto mfma_row = [&](const Frag& f, int fb) {
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) xfrag[tb] = *reinterpret_cast<const u32x4*>(xs + tb * 4096 + koff[ks]);
-#pragma unroll
-            for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-                for (int tb = 0; tb < 4; ++tb) acc[fb][tb] = mfma32<OP_BF16>(wfrag[fb], xfrag[tb], acc[fb][tb]);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (int tb = 0; tb < 4; ++tb) acc[fb][tb] = mfma32<OP_BF16>(f.w[fb], f.x[tb], acc[fb][tb]);
+    };
+    // Tiles kt+1 .. kt+S-2 may still be in flight when tile kt is needed; the counted wait leaves
+    // exactly their loads outstanding, and the barrier then says that every wavefront's share of the
+    // tile has landed AND that every wavefront has read all it needs of the previous tile, whose stage
+    // the next loads overwrite.
+    auto next_tile = [&](int kt_next, int st_next) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * 2 * NCH) : "memory");
         __syncthreads();
+        dma(kt_next + S - 1, st_next == 0 ? S - 1 : st_next - 1);
+    };
+#pragma unroll
+    for (int j = 0; j < S - 1; ++j) dma(j, j);
+    next_tile(0, 0);
+    read_frags(F[0], 0, 0);
+    int st = 0;
+    for (int kt = 0; kt < nK; ++kt) {
+        const int st_next = st + 1 == S ? 0 : st + 1;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            // Half of the slice's MFMAs, then the reads of the next slice, then the other half: a
+            // fragment is asked for 8 MFMAs of this SIMD (its two wavefronts take turns) before its use.
+            // When the next slice belongs to the next tile the barrier comes first: by then this
+            // wavefront has read every fragment of the present tile, so the present stage may be
+            // refilled behind the barrier.  (A read-ahead of two slices with counted waits, the
+            // wavefronts of a SIMD at different priorities, the loads spread over the step, 4
+            // wavefronts of 128 x 128: all measured the same or slower.)
+#pragma unroll
+            for (int fb = 0; fb < FB / 2; ++fb) mfma_row(F[ks & 1], fb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < NKS) {
+                read_frags(F[(ks + 1) & 1], st, ks + 1);
+            } else {
+                // (after the last tile this fetches and reads a stage nobody uses: uniform control flow)
+                next_tile(kt + 1, st_next);
+                read_frags(F[0], st_next, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int fb = FB / 2; fb < FB; ++fb) mfma_row(F[ks & 1], fb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        st = st_next;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
 
     // ---- epilogue: lane holds token (column l32 of block tb), features 32*fb + 8*g + 4*half + e ----
 #pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
+    for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int n0 = tn * kLinBN + wf * 64 + fb * 32 + 8 * g + 4 * half;
+            const int n0 = tn * kLinBN + wf * 32 * FB + fb * 32 + 8 * g + 4 * half;
             if (n0 >= a.N) continue;  // N is a multiple of 8: a quad is inside or outside as a whole
             float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
             if (a.bias) {
@@ -154,12 +214,12 @@ __global__ void __launch_bounds__(512, 1) linear_kernel(const LinearArgs a) {
 
 template <bool OUT_F32>
 hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
-    auto kern = linear_kernel<OUT_F32>;
-    constexpr int smem = 2 * kLinStage;
+    auto kern = linear_kernel<DIT_LIN_BK, DIT_LIN_STAGES, DIT_LIN_WAVES, OUT_F32>;
+    constexpr int smem = DIT_LIN_STAGES * (kLinBM + kLinBN) * DIT_LIN_BK * 2;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)a.nTM * a.nTN)), dim3(512), smem, s, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)a.nTM * a.nTN)), dim3(64 * DIT_LIN_WAVES), smem, s, a);
     return hipGetLastError();
 }
 
