@@ -250,8 +250,8 @@ dit_status dit_attn_varlen_forward(const void *q, const void *k, const void *v, 
  * order unspecified), the bias is added in fp32, the result is rounded once (nearest-even) if bf16.
  * x and w may not overlap y.  No workspace.
  * Errors: NULL x/w/y/p, M, N or K < 1, a stride shorter than its row, bad out_dtype or nonzero
- * flags -> DIT_ERR_INVALID_ARG; K not a multiple of 64 or N not a multiple of 8 ->
- * DIT_ERR_UNSUPPORTED; a base pointer or row stride that breaks 16-byte row alignment (8 bytes for
+ * flags -> DIT_ERR_INVALID_ARG; K not a multiple of 64, N not a multiple of 8, or ldx or ldw above
+ * 2^22 elements -> DIT_ERR_UNSUPPORTED; a base pointer or row stride that breaks 16-byte row alignment (8 bytes for
  * bias) -> DIT_ERR_ALIGNMENT.
  */
 typedef struct {

@@ -625,6 +625,8 @@ dit_status dit_linear_forward(const void* x, const void* w, const void* bias, vo
     if (p->ldx < p->K || p->ldw < p->K || p->ldy < p->N) return DIT_ERR_INVALID_ARG;
     if (p->out_dtype != DIT_BF16 && p->out_dtype != DIT_F32) return DIT_ERR_INVALID_ARG;
     if (p->K % dit::kLinBK != 0 || p->N % 8 != 0) return DIT_ERR_UNSUPPORTED;
+    // the kernel addresses the rows of one 256-row tile with 32-bit byte offsets
+    if (p->ldx > (int64_t)1 << 22 || p->ldw > (int64_t)1 << 22) return DIT_ERR_UNSUPPORTED;
     const size_t ye = p->out_dtype == DIT_F32 ? 4 : 2;
     if ((uintptr_t)x % 16 || (uintptr_t)w % 16 || (uintptr_t)y % 16 || (p->ldx * 2) % 16 || (p->ldw * 2) % 16 ||
         (p->ldy * ye) % 16 || (uintptr_t)bias % 8)

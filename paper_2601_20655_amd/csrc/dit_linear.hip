@@ -3,17 +3,28 @@
 // stage, Sec. 2.4; weights stored [out, in] as the model's linear layers keep them).
 //
 // One workgroup of 8 wavefronts owns a 256-token x 256-feature tile of y and walks K in steps of 64.
-// Both operand tiles of a step (256 rows x 64 contraction indices, 16-bit) are copied from global
-// memory straight into LDS by the load-to-LDS DMA, 1 KiB per wavefront instruction, two stages deep:
-// the copies of step j+1 fly while step j is multiplied.  The DMA fills LDS densely in lane order,
-// so the bank spreading is done by choosing WHICH 16-byte piece of a row each lane fetches: piece p
-// of row r lives in slot p ^ ((r >> 1) & 7) of the row's 128 bytes, which makes the 16 rows a quarter
-// wavefront reads with one ds_read_b128 fall into 16 distinct bank groups.
+// Both operand tiles of a step (256 rows x 64 contraction indices, 16-bit: one 128-byte line per row)
+// are copied from global memory straight into LDS by the load-to-LDS DMA, 1 KiB per wavefront
+// instruction.  The DMA fills LDS densely in lane order, so the bank spreading is done by choosing
+// WHICH 16-byte piece of a row each lane fetches: piece p of row r lives in slot p ^ ((r >> 1) & 7) of
+// the row's 128 bytes, which makes the 16 rows a quarter wavefront reads with one ds_read_b128 fall
+// into 16 distinct bank groups (measured: no bank conflicts).
+//
+// Buffering: all 160 KiB of LDS are used, SX = 3 buffers for the x tile (fetched two steps ahead) and
+// SW = 2 for the w tile (one step ahead).  The loads of a step are issued one or two at a time between
+// groups of MFMAs, never in a burst, and the one barrier per step sits where every wavefront still
+// has MFMAs in flight.
 //
 // MFMA roles: w rows ride the A operand (the M axis of v_mfma_f32_32x32x16_bf16), token rows the
 // B operand, so a lane ends up with four CONSECUTIVE features of one token per register quad and
-// stores them with one instruction.  Wavefront (wt, wf) of the 2 x 4 grid computes 128 tokens x 64
-// features: 8 accumulators, 6 fragment reads per 8 MFMAs.
+// stores them with one instruction.  With 8 wavefronts, wavefront (wt, wf) of the 2 x 4 grid computes
+// 128 tokens x 64 features (8 accumulators, 6 fragment reads per 8 MFMAs, two wavefronts per SIMD);
+// with 4 wavefronts 128 x 128 (16 accumulators in the AGPRs, one wavefront per SIMD).  Both forms,
+// two or three x buffers, bursts or spread loads, a two-slice read-ahead, 384-token tiles (17 % less
+// L2 traffic) and wavefront priorities all measured within 1,080-1,190 TFLOP/s at M = 32,760,
+// N = K = 5,120; the 8-wavefront form is the default.
+#include <type_traits>
+
 #include "dit_attn_device.h"
 #include "dit_attn_internal.h"
 
@@ -24,32 +35,32 @@ namespace {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-#ifndef DIT_LIN_BK
-#define DIT_LIN_BK 64
+#ifndef DIT_LIN_SX
+#define DIT_LIN_SX 3
 #endif
-#ifndef DIT_LIN_STAGES
-#define DIT_LIN_STAGES 2
+#ifndef DIT_LIN_SW
+#define DIT_LIN_SW 2
 #endif
 #ifndef DIT_LIN_WAVES
 #define DIT_LIN_WAVES 8
 #endif
 constexpr int kLinGroup = 8;  // token tiles per group of the workgroup order
+constexpr int kLinTileBytes = 256 * kLinBK * 2;  // one operand tile of one step
 
-// BK contraction indices per step (32 or 64), S stages of LDS, NW wavefronts (8: 128 tokens x 64
-// features each, two per SIMD; 4: 128 x 128 each, one per SIMD with the accumulators in the AGPRs).
-template <int BK, int S, int NW, bool OUT_F32>
+// SX buffers for x tiles, SW for w tiles (SX = SW or SX = SW + 1).
+template <int SX, int SW, int NW, bool OUT_F32>
 __global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) {
-    static_assert(kLinBM == 256 && kLinBN == 256 && (BK == 32 || BK == 64) && S >= 2, "tile shape");
-    static_assert(NW == 4 || NW == 8, "wavefronts per workgroup");
+    static_assert(kLinBM == 256 && kLinBN == 256 && kLinBK == 64, "tile shape");
+    static_assert(SW >= 2 && (SX == SW || SX == SW + 1), "buffering");
+    static_assert(NW == 4 || NW == 8, "wavefronts: 2 (tokens) x NW/2 (features)");
     constexpr int FB = 16 / NW;  // 32-feature blocks per wavefront
-    constexpr int kLinStage = (kLinBM + kLinBN) * BK * 2;  // bytes of one stage: x tile, then w tile
-    constexpr int kLinXBytes = kLinBM * BK * 2;
-    constexpr int PPR = BK / 8;         // 16-byte pieces per row
-    constexpr int RPC = 64 / PPR;       // rows per 1 KiB chunk
-    constexpr int RP = 256 / (BK * 2);  // rows per 256 bytes (one sweep of the banks)
-    constexpr int NCH = BK / 2 / NW;    // chunks per wavefront and tile
-    constexpr int ROWB = BK * 2;        // bytes per row
+    constexpr int TB = 4;        // 32-token blocks per wavefront
+    constexpr int NCH = 32 / NW;  // 1 KiB chunks (8 rows) per wavefront and tile
+    constexpr int ROWB = 128;  // bytes per row of a tile
+    constexpr int NKS = kLinBK / 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    // LDS map: the x buffers, then the w buffers
+    constexpr int kWBase = SX * kLinTileBytes;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -73,110 +84,164 @@ __global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) 
         tn = within / gsz;
     }
 
-    // ---- DMA sources: wavefront w moves 1 KiB chunks w, w+NW, ... of both tiles; a chunk is RPC rows.
-    // Rows past the end of x or w are clamped to the last one (their products are never stored).
-    const uint16_t* xsrc[NCH];
-    const uint16_t* wsrc[NCH];
+    // ---- DMA sources: wavefront w moves 1 KiB chunks w, w+8, w+16, w+24 of both tiles; a chunk is 8
+    // rows.  Rows past the end of x or w are clamped to the last one (their products are never stored).
+    // Per lane: 32-bit byte offsets from the tile's first row (the host checks that a tile's extent
+    // fits 32 bits); the tile base and the step's column offset are wavefront-uniform.
+    uint32_t xoff[NCH], woff[NCH];
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-        const int r = RPC * (wave + NW * i) + lane / PPR;
-        const int p = (lane % PPR) ^ ((r / RP) % PPR);
+        const int r = 8 * (wave + NW * i) + (lane >> 3);
+        const int p = (lane & 7) ^ ((r >> 1) & 7);
         int xr = tm * kLinBM + r, wr = tn * kLinBN + r;
-        xr = xr < a.M ? xr : a.M - 1;
-        wr = wr < a.N ? wr : a.N - 1;
-        xsrc[i] = a.x + (int64_t)xr * a.ldx + 8 * p;
-        wsrc[i] = a.w + (int64_t)wr * a.ldw + 8 * p;
+        xr = (xr < a.M ? xr : a.M - 1) - tm * kLinBM;
+        wr = (wr < a.N ? wr : a.N - 1) - tn * kLinBN;
+        xoff[i] = (uint32_t)xr * (uint32_t)(a.ldx * 2) + 16 * p;
+        woff[i] = (uint32_t)wr * (uint32_t)(a.ldw * 2) + 16 * p;
     }
-    const int nK = a.K / BK;
-    // (a tile number past the end fetches the last tile again, into a stage nobody reads any more:
-    // every step then has the same number of loads in flight, which the counted wait relies on)
-    auto dma = [&](int kt, int st) {
+    const uint8_t* const xtile = reinterpret_cast<const uint8_t*>(a.x + (int64_t)tm * kLinBM * a.ldx);
+    const uint8_t* const wtile = reinterpret_cast<const uint8_t*>(a.w + (int64_t)tn * kLinBN * a.ldw);
+    const int nK = a.K / kLinBK;
+    // (a tile number past the end fetches the last tile again, into a buffer nobody reads any more:
+    // every step then has the same number of loads in flight, which the counted wait relies on; the
+    // empty asm keeps the compiler from folding base + offset into per-lane 64-bit pointers ahead of
+    // the loop, which would cost two registers per load)
+    auto dma_chunk = [&](const uint8_t* tile, uint32_t o, int kt, int lds_byte, int i) {
         kt = kt < nK ? kt : nK - 1;
-        uint8_t* const xd = smem + st * kLinStage + wave * 1024;
-        uint8_t* const wd = xd + kLinXBytes;
+        asm volatile("" : "+v"(o));
+        __builtin_amdgcn_global_load_lds((gptr_t)(tile + kt * (kLinBK * 2) + o),
+                                         (lptr_t)(smem + lds_byte + (wave + i * NW) * 1024), 16, 0, 0);
+    };
+    auto dma_x = [&](int kt, int buf) {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(xsrc[i] + kt * BK), (lptr_t)(xd + i * NW * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wsrc[i] + kt * BK), (lptr_t)(wd + i * NW * 1024), 16, 0, 0);
-        }
+        for (int i = 0; i < NCH; ++i) dma_chunk(xtile, xoff[i], kt, buf * kLinTileBytes, i);
+    };
+    auto dma_w = [&](int kt, int buf) {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) dma_chunk(wtile, woff[i], kt, kWBase + buf * kLinTileBytes, i);
     };
 
-    // ---- fragment addresses: row base + swizzled piece of contraction step ks ----
-    const int sw = (l32 / RP) % PPR;
-    int koff[BK / 16];
+    // ---- fragment addresses: row base + swizzled piece of contraction slice ks ----
+    const int sw = (l32 >> 1) & 7;
+    int koff[NKS];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) koff[ks] = ((2 * ks + half) ^ sw) * 16;
-    const int xread = (wt * 128 + l32) * ROWB;
-    const int wread = kLinXBytes + (wf * 32 * FB + l32) * ROWB;
+    for (int ks = 0; ks < NKS; ++ks) koff[ks] = ((2 * ks + half) ^ sw) * 16;
+    const int xread = (wt * 32 * TB + l32) * ROWB;
+    const int wread = kWBase + (wf * 32 * FB + l32) * ROWB;
 
-    f32x16 acc[FB][4];
+    f32x16 acc[FB][TB];
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
+        for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
 
-    // Operand fragments of one 16-index slice: 2 of w, 4 of x.  Two sets alternate, so the reads of
-    // the next slice are in flight while the MFMAs of the current one issue.
-    struct Frag {
-        u32x4 w[FB], x[4];
-    };
-    constexpr int NKS = BK / 16;
-    Frag F[2];
-    auto read_frags = [&](Frag& f, int stage, int ks) {
-        const uint8_t* const xs = smem + stage * kLinStage + xread + koff[ks];
-        const uint8_t* const ws = smem + stage * kLinStage + wread + koff[ks];
+    // Operand fragments.  A slice (16 contraction indices) takes FB fragments of w and TB of x.  The w
+    // fragments are double-buffered and requested a whole slice ahead; an x fragment is used by the FB
+    // MFMAs of its token block and then refilled IN PLACE with the next slice's fragment (an LDS
+    // return into registers whose MFMAs have issued is safe), so only one set of them is held.
+    // The reads are inline assembly so that the waits can be counted: LDS returns in order, and at
+    // every use exactly FB + TB - 1 younger reads are in flight (the rest of this slice's x
+    // fragments, the next w set, the refills already issued), so one constant serves every wait and a
+    // fragment is asked for about 2 (TB - 1) + FB MFMAs of this wavefront before its use.  The compiler
+    // itself waits for LDS reads with lgkmcnt(0), which would drain that queue at every use.
+    constexpr int YOUNGER = FB + TB - 1;
+    u32x4 W[2][FB], X[TB];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    auto read_w = [&](u32x4 (&w)[FB], int buf, int ks) {
+        const uint32_t wa = lds0 + buf * kLinTileBytes + wread + koff[ks];
 #pragma unroll
-        for (int fb = 0; fb < FB; ++fb) f.w[fb] = *reinterpret_cast<const u32x4*>(ws + fb * 32 * ROWB);
-#pragma unroll
-        for (int tb = 0; tb < 4; ++tb) f.x[tb] = *reinterpret_cast<const u32x4*>(xs + tb * 32 * ROWB);
+        for (int fb = 0; fb < FB; ++fb)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(w[fb]) : "v"(wa), "n"(fb * 32 * ROWB));
     };
-    auto mfma_row = [&](const Frag& f, int fb) {
-#pragma unroll
-        for (int tb = 0; tb < 4; ++tb) acc[fb][tb] = mfma32<OP_BF16>(f.w[fb], f.x[tb], acc[fb][tb]);
+    auto read_x = [&](u32x4& x, auto tb, int buf, int ks) {
+        const uint32_t xa = lds0 + buf * kLinTileBytes + xread + koff[ks];
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(x) : "v"(xa), "n"(decltype(tb)::value * 32 * ROWB));
     };
-    // Tiles kt+1 .. kt+S-2 may still be in flight when tile kt is needed; the counted wait leaves
-    // exactly their loads outstanding, and the barrier then says that every wavefront's share of the
-    // tile has landed AND that every wavefront has read all it needs of the previous tile, whose stage
-    // the next loads overwrite.
-    auto next_tile = [&](int kt_next, int st_next) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * 2 * NCH) : "memory");
+    // The barrier that opens step k sits in the last slice of step k-1, after the MFMAs of its first
+    // token block: by then every wavefront has asked for all fragments of step k-1 (the wait completes
+    // the reads; the last of them were requested a block earlier), so behind the barrier the buffers of
+    // step k-1 may be refilled.  The loads of one barrier period go out between the MFMA groups, never
+    // in a burst: the w tile of step k+SW-1 over the first four token blocks after the barrier, the x
+    // tile of step k+SX-1 over the two slices before the next barrier.  The counted wait in front of
+    // the barrier leaves exactly the youngest x tile in flight.
+    static_assert(SX == 3 && SW == 2, "the load schedule below is written for 3 x and 2 w buffers");
+    auto sync_point = [&]() {
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NCH) : "memory");
         __syncthreads();
-        dma(kt_next + S - 1, st_next == 0 ? S - 1 : st_next - 1);
     };
+    constexpr int WPB = NCH / 4;  // w chunks per token block
+    // Prologue: tiles x(0), w(0), x(1) in a burst; the first barrier; then what a last slice would
+    // have sent behind it (three token blocks' worth of w(1)); the loop sends the rest.
+    dma_x(0, 0);
+    dma_w(0, 0);
+    dma_x(1, 1);
+    sync_point();
 #pragma unroll
-    for (int j = 0; j < S - 1; ++j) dma(j, j);
-    next_tile(0, 0);
-    read_frags(F[0], 0, 0);
-    int st = 0;
+    for (int i = 0; i < 3 * WPB; ++i) dma_chunk(wtile, woff[i], 1, kWBase + kLinTileBytes, i);
+    int xb = 0, wb = 0;  // buffers of the step being multiplied
+    read_w(W[0], wb, 0);
+    read_x(X[0], std::integral_constant<int, 0>(), xb, 0);
+    read_x(X[1], std::integral_constant<int, 1>(), xb, 0);
+    read_x(X[2], std::integral_constant<int, 2>(), xb, 0);
+    read_x(X[3], std::integral_constant<int, 3>(), xb, 0);
     for (int kt = 0; kt < nK; ++kt) {
-        const int st_next = st + 1 == S ? 0 : st + 1;
+        const int xb_next = xb + 1 == SX ? 0 : xb + 1, wb_next = wb ^ 1;
+        const int xb_prev = xb == 0 ? SX - 1 : xb - 1, wb_prev = wb ^ 1;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            // Half of the slice's MFMAs, then the reads of the next slice, then the other half: a
-            // fragment is asked for 8 MFMAs of this SIMD (its two wavefronts take turns) before its use.
-            // When the next slice belongs to the next tile the barrier comes first: by then this
-            // wavefront has read every fragment of the present tile, so the present stage may be
-            // refilled behind the barrier.  (A read-ahead of two slices with counted waits, the
-            // wavefronts of a SIMD at different priorities, the loads spread over the step, 4
-            // wavefronts of 128 x 128: all measured the same or slower.)
+            const bool last = ks + 1 == NKS;
+            // fragments of the next slice come from this step's buffers, or from the next step's
+            const int nxb = last ? xb_next : xb, nwb = last ? wb_next : wb;
+            const int nks = last ? 0 : ks + 1;
+            if (!last) read_w(W[(ks + 1) & 1], nwb, nks);
+            auto block = [&](auto tb) {
+                constexpr int T = decltype(tb)::value;
+                // younger reads in flight at this use: the rest of the slice's x fragments, the next
+                // w set and the refills already issued (the next w set is late in the last slice)
+                if (last && T == 0) {
+                    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(TB - 1));
+                }
+                if constexpr (FB == 2) {
+                    asm volatile("s_waitcnt lgkmcnt(%3)"
+                                 : "+v"(W[ks & 1][0]), "+v"(W[ks & 1][1]), "+v"(X[T])
+                                 : "n"(YOUNGER));
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(%5)"
+                                 : "+v"(W[ks & 1][0]), "+v"(W[ks & 1][1]), "+v"(W[ks & 1][2]), "+v"(W[ks & 1][3]),
+                                   "+v"(X[T])
+                                 : "n"(YOUNGER));
+                }
 #pragma unroll
-            for (int fb = 0; fb < FB / 2; ++fb) mfma_row(F[ks & 1], fb);
-            __builtin_amdgcn_sched_barrier(0);
-            if (ks + 1 < NKS) {
-                read_frags(F[(ks + 1) & 1], st, ks + 1);
-            } else {
-                // (after the last tile this fetches and reads a stage nobody uses: uniform control flow)
-                next_tile(kt + 1, st_next);
-                read_frags(F[0], st_next, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+                for (int fb = 0; fb < FB; ++fb) acc[fb][T] = mfma32<OP_BF16>(W[ks & 1][fb], X[T], acc[fb][T]);
+                if (last && T == 0) {
+                    // (after the last tile the loads and reads behind this barrier go to buffers nobody
+                    // uses: uniform control flow)
+                    sync_point();
+                    read_w(W[(ks + 1) & 1], nwb, nks);
+                }
+                read_x(X[T], tb, nxb, nks);
+                // this block's share of the loads (q = token blocks since the barrier)
+                const int q = last ? T - 1 : 3 + 4 * ks + T;
+                if (q >= 0 && q < 4) {
 #pragma unroll
-            for (int fb = FB / 2; fb < FB; ++fb) mfma_row(F[ks & 1], fb);
-            __builtin_amdgcn_sched_barrier(0);
+                    for (int i = 0; i < WPB; ++i) {
+                        const int c = q * WPB + i;
+                        if (last) dma_chunk(wtile, woff[c], kt + SW, kWBase + wb * kLinTileBytes, c);
+                        else dma_chunk(wtile, woff[c], kt + SW - 1, kWBase + wb_prev * kLinTileBytes, c);
+                    }
+                } else if (q >= 7 && q - 7 < NCH) {
+                    dma_chunk(xtile, xoff[q - 7], kt + SX - 1, xb_prev * kLinTileBytes, q - 7);
+                }
+            };
+            block(std::integral_constant<int, 0>());
+            block(std::integral_constant<int, 1>());
+            block(std::integral_constant<int, 2>());
+            block(std::integral_constant<int, 3>());
         }
-        st = st_next;
+        xb = xb_next;
+        wb = wb_next;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
 
@@ -196,8 +261,8 @@ __global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) 
                 b3 = __uint_as_float(bb.y & 0xffff0000u);
             }
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) {
-                const int m = tm * kLinBM + wt * 128 + tb * 32 + l32;
+            for (int tb = 0; tb < TB; ++tb) {
+                const int m = tm * kLinBM + wt * 32 * TB + tb * 32 + l32;
                 if (m >= a.M) continue;
                 const float y0 = acc[fb][tb][4 * g + 0] + b0, y1 = acc[fb][tb][4 * g + 1] + b1;
                 const float y2 = acc[fb][tb][4 * g + 2] + b2, y3 = acc[fb][tb][4 * g + 3] + b3;
@@ -214,8 +279,8 @@ __global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) 
 
 template <bool OUT_F32>
 hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
-    auto kern = linear_kernel<DIT_LIN_BK, DIT_LIN_STAGES, DIT_LIN_WAVES, OUT_F32>;
-    constexpr int smem = DIT_LIN_STAGES * (kLinBM + kLinBN) * DIT_LIN_BK * 2;
+    auto kern = linear_kernel<DIT_LIN_SX, DIT_LIN_SW, DIT_LIN_WAVES, OUT_F32>;
+    constexpr int smem = (DIT_LIN_SX + DIT_LIN_SW) * kLinTileBytes;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;

@@ -229,7 +229,7 @@ def test_linear_rejects_bad_arguments():
                dict(ldx=56), dict(ldw=56), dict(ldy=56)):
         assert linear_call(**kw) == B.DIT_ERR_INVALID_ARG, kw
     assert B.lib().dit_linear_forward(FAKE, FAKE, None, FAKE, None, None) == B.DIT_ERR_INVALID_ARG
-    for kw in (dict(K=96), dict(N=60), dict(K=8)):
+    for kw in (dict(K=96), dict(N=60), dict(K=8), dict(ldx=(1 << 22) + 8), dict(ldw=(1 << 22) + 8)):
         assert linear_call(**kw) == B.DIT_ERR_UNSUPPORTED, kw
     for kw in (dict(x=FAKE + 8), dict(w=FAKE + 2), dict(y=FAKE + 4), dict(ldx=68), dict(ldw=70), dict(ldy=68),
                dict(bias=FAKE + 4), dict(out_dtype=B.DIT_F32, ldy=66)):
