@@ -27,8 +27,9 @@ PEAK_TFLOPS_8BIT_DENSE = 5000.0   # published dense fp8 MFMA peak
 # FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
 # keyed by library version: a library whose kernel has changed since reports null.
 # (111 added a host-side flag only and 112 separate instantiations; their default kernel is that of 110.
-# 115 changed the cross-attention workgroup order only; its self-attention kernel is that of 114, checked byte for byte.)
-TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9, 115: 3.92e9}
+# 115 changed the cross-attention workgroup order only and 116 added the projection entry point; their self-attention
+# kernel is that of 114, checked byte for byte.)
+TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9, 115: 3.92e9, 116: 3.92e9}
 
 
 class HipEvents:
@@ -98,8 +99,17 @@ def other_workload(args):
     def dev(a):
         return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
 
-    H, D = cfg["H"], cfg["D"]
-    if cfg["kind"] == "self":
+    H, D = cfg.get("H"), cfg.get("D")
+    if cfg["kind"] == "linear":
+        x, w, b = (dev(a) for a in wl.linear_inputs(cfg))
+        out = torch.empty((cfg["M"], cfg["N"]), dtype=torch.bfloat16, device="cuda")
+        flops = 2.0 * cfg["M"] * cfg["N"] * cfg["K"]
+        what = "projection y = x w^T + bias, %d tokens, %d -> %d features" % (cfg["M"], cfg["K"], cfg["N"])
+        kernel = "linear_kernel"
+
+        def call():
+            B.dit_linear_forward(x, w, b, out=out, stream=stream)
+    elif cfg["kind"] == "self":
         q, k, v = (dev(a) for a in wl.self_attn_inputs(cfg))
         out = torch.empty_like(q)
         ws = torch.empty(B.dit_attn_workspace_bytes(B.self_attn_params(q, k, v, out, cfg["grid"], cfg["split"],
@@ -156,12 +166,14 @@ def other_workload(args):
     # 8-bit scores: half of the flops run at the 8-bit peak, half at the 16-bit peak
     peak = 2.0 / (1.0 / PEAK_TFLOPS_8BIT_DENSE + 1.0 / PEAK_TFLOPS_16BIT_DENSE) if fp8 else PEAK_TFLOPS_16BIT_DENSE
     print(json.dumps({
-        "metric": "attention TFLOP/s, %s" % args.workload + (" (decoupled)" if args.decoupled else "")
+        "metric": ("projection" if cfg["kind"] == "linear" else "attention") + " TFLOP/s, %s" % args.workload
+                  + (" (decoupled)" if args.decoupled else "")
                   + (" (8-bit score operands: outside the 16-bit parity contract)" if fp8 else ""),
         "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "fp8 scores, f16 PV" if fp8 else "f16" if not (args.flags & B.DIT_FLAG_QK_BF16) else "bf16",
+        "dtype": "bf16" if cfg["kind"] == "linear" else "fp8 scores, f16 PV" if fp8
+                 else "f16" if not (args.flags & B.DIT_FLAG_QK_BF16) else "bf16",
         "data": "synthetic",
         "config": {"workload": what, "flags": args.flags, "attn_kernel_ms": round(kern_ms, 4), "flops_per_step": flops},
         "roofline": {"kernel": kernel, "bound": "mfma", "achieved": round(achieved, 2),
@@ -181,7 +193,7 @@ def main():
                          "counter run (FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
     ap.add_argument("--workload", default="step",
                     help="'step' (default: the headline metric) or one of the other shapes for a secondary "
-                         "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b")
+                         "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b, qkv_proj_14b, out_proj_14b")
     ap.add_argument("--decoupled", action="store_true", help="cross_14b: one softmax per conditioning sequence")
     args = ap.parse_args()
     if args.gpus != 1:
