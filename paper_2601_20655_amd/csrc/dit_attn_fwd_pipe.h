@@ -381,21 +381,17 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
             Sc[i / 8][qv][(2 * i) % 16] = __builtin_amdgcn_exp2f(Sc[i / 8][qv][(2 * i) % 16]);
             Sc[i / 8][qv][(2 * i + 1) % 16] = __builtin_amdgcn_exp2f(Sc[i / 8][qv][(2 * i + 1) % 16]);
         };
-        // fp16 P: the row sum runs in fp32 over the unrounded probabilities, two chains of plain
-        // additions: the dot-product instruction that would sum a packed pair does not overlap with a
-        // running MFMA (about 8 clocks each, unhidden; additions, maxima and exp2 hide completely).
-        // Numerator (rounded P) and denominator then differ by at most 2^-11 relative, typically by
-        // 2^-12 / sqrt(keys that carry the mass).
+        // The row sum runs in fp32 over the unrounded probabilities, two chains of plain additions: the
+        // dot-product instruction that would sum a packed pair does not overlap with a running MFMA
+        // (about 8 clocks each, unhidden; additions, maxima and exp2 hide completely).  Numerator
+        // (rounded P) and denominator then differ by at most half a unit of P's last place relative
+        // (2^-11 for fp16 P, 2^-8 for bf16 P), typically by that / sqrt(keys that carry the mass).
         auto pack_slice = [&](int c) {
             const int qv = c / 16, i = c % 16;
             const float e0 = Sc[i / 8][qv][(2 * i) % 16], e1 = Sc[i / 8][qv][(2 * i + 1) % 16];
             Pd[qv][i] = pack2<PV_OP>(e0, e1);
-            if constexpr (PV_OP == OP_F16) {
-                ls[qv][0] += e0;
-                ls[qv][1] += e1;
-            } else {  // bf16 P (8 significant bits): keep the sum over the rounded values, which cancels their error
-                ls[qv][i & 1] = sum2<PV_OP>(Pd[qv][i], ls[qv][i & 1]);
-            }
+            ls[qv][0] += e0;
+            ls[qv][1] += e1;
         };
 #pragma unroll
         for (int c = 0; c < PRE; ++c) exp_slice(c);
