@@ -172,6 +172,49 @@ int main(void)
         hipFree(dq); hipFree(dk); hipFree(dv); hipFree(dvalid); hipFree(dout); hipFree(ws);
         free(q); free(k); free(v); free(valid); free(out); free(rows); free(ref);
     }
+    /* ---- projection: y = x w^T + bias, 300 tokens, 192 -> 264 features (ragged tiles on both axes),
+     * checked against a triple loop in double written out here ---- */
+    {
+        const int32_t M = 300, N = 264, K = 192;
+        uint16_t *x = make_bf16((size_t)M * K), *w = make_bf16((size_t)N * K), *b = make_bf16((size_t)N);
+        void *dx = to_device(x, (size_t)M * K * 2), *dw = to_device(w, (size_t)N * K * 2);
+        void *db = to_device(b, (size_t)N * 2), *dy = to_device(NULL, (size_t)M * N * 4);
+        if (!dx || !dw || !db || !dy) return 2;
+        dit_linear_params p;
+        memset(&p, 0, sizeof(p));
+        p.M = M; p.N = N; p.K = K; p.ldx = K; p.ldw = K; p.ldy = N; p.out_dtype = DIT_F32;
+        dit_status st = dit_linear_forward(dx, dw, db, dy, &p, NULL);
+        if (st != DIT_OK) {
+            fprintf(stderr, "dit_linear_forward: %s %s\n", dit_strerror(st), dit_last_hip_error());
+            return 1;
+        }
+        CHECK_HIP(hipDeviceSynchronize());
+        float *y = (float *)malloc((size_t)M * N * 4);
+        CHECK_HIP(hipMemcpy(y, dy, (size_t)M * N * 4, hipMemcpyDeviceToHost));
+        double *ref = (double *)malloc((size_t)M * N * 8);
+        for (int m = 0; m < M; ++m)
+            for (int n = 0; n < N; ++n) {
+                double acc = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    uint32_t ux = (uint32_t)x[(size_t)m * K + k] << 16, uw = (uint32_t)w[(size_t)n * K + k] << 16;
+                    float fx, fw;
+                    memcpy(&fx, &ux, 4);
+                    memcpy(&fw, &uw, 4);
+                    acc += (double)fx * (double)fw;
+                }
+                uint32_t ub = (uint32_t)b[n] << 16;
+                float fb;
+                memcpy(&fb, &ub, 4);
+                ref[(size_t)m * N + n] = acc + (double)fb;
+            }
+        double e = rel_err(y, ref, (size_t)M * N);
+        printf("projection      max|err|/RMS = %.3e\n", e);
+        if (!(e < 1e-5)) return 1;
+        p.K = 100; /* not a multiple of 64: refused before anything is launched */
+        if (dit_linear_forward(dx, dw, db, dy, &p, NULL) != DIT_ERR_UNSUPPORTED) return 1;
+        hipFree(dx); hipFree(dw); hipFree(db); hipFree(dy);
+        free(x); free(w); free(b); free(y); free(ref);
+    }
     printf("c caller ok\n");
     return 0;
 }
