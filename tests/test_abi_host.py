@@ -259,8 +259,9 @@ def test_public_header_is_plain_c(compiler, std, tmp_path):
     src.write_text(
         '#include "dit_attn.h"\n#include <stdio.h>\n'
         "int main(void) {\n"
-        '  printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(dit_strides), sizeof(dit_qk_norm), sizeof(dit_self_attn_params),\n'
-        "         sizeof(dit_cross_attn_params), sizeof(dit_varlen_attn_params), sizeof(dit_grid));\n"
+        '  printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(dit_strides), sizeof(dit_qk_norm), sizeof(dit_self_attn_params),\n'
+        "         sizeof(dit_cross_attn_params), sizeof(dit_varlen_attn_params), sizeof(dit_grid),\n"
+        "         sizeof(dit_linear_params));\n"
         "  return 0;\n}\n")
     exe = str(tmp_path / "t")
     subprocess.check_call([compiler, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
@@ -268,7 +269,7 @@ def test_public_header_is_plain_c(compiler, std, tmp_path):
     sizes = [int(x) for x in subprocess.check_output([exe]).split()]
     assert sizes == [ctypes.sizeof(B.dit_strides), ctypes.sizeof(B.dit_qk_norm), ctypes.sizeof(B.dit_self_attn_params),
                      ctypes.sizeof(B.dit_cross_attn_params), ctypes.sizeof(B.dit_varlen_attn_params),
-                     ctypes.sizeof(B.dit_grid)]
+                     ctypes.sizeof(B.dit_grid), ctypes.sizeof(B.dit_linear_params)]
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -71,8 +71,9 @@ def test_graph_replay_matches_eager():
 
 
 def test_graph_replay_of_the_other_entry_points_and_flags():
-    """Packed requests with token-mode q/k normalisation, the 8-bit score path, and a cross-attention
-    call on resident tiles, all captured into one graph and replayed with eager work in between."""
+    """Packed requests with token-mode q/k normalisation, the 8-bit score path, a cross-attention call
+    on resident tiles and a projection, all captured into one graph and replayed with eager work in
+    between."""
     import torch
 
     vcfg = wl.CONFIGS["varlen_small"]
@@ -89,6 +90,9 @@ def test_graph_replay_of_the_other_entry_points_and_flags():
     vref = B.dit_attn_varlen_forward(vq, vk, vv, grids, vcfg["split"], norm=norm, workspace=vws).clone()
     ref8 = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], flags=B.DIT_FLAG_QK_FP8, workspace=ws8).clone()
     cref = B.dit_cross_attn_forward(cq, ck, cv, vd, workspace=cws).clone()  # leaves its tiles in cws
+    lx, lw, lb = (to_dev(a) for a in wl.linear_inputs(wl.CONFIGS["proj_small"]))
+    lref = B.dit_linear_forward(lx, lw, lb).clone()
+    lout = torch.empty_like(lref)
     torch.cuda.synchronize()
 
     g = torch.cuda.CUDAGraph()
@@ -101,9 +105,10 @@ def test_graph_replay_of_the_other_entry_points_and_flags():
                                stream=side)
             B.dit_cross_attn_forward(cq, ck, cv, None, flags=B.DIT_FLAG_KV_RESIDENT, out=cout, workspace=cws,
                                      stream=side)
+            B.dit_linear_forward(lx, lw, lb, out=lout, stream=side)
     torch.cuda.synchronize()
     for rep in range(3):
-        for t in (vout, out8, cout):
+        for t in (vout, out8, cout, lout):
             t.fill_(-3.0)
         vws.fill_(rep)  # rebuilt by every replay; cws keeps the resident tiles and is left alone
         ws8.fill_(rep)
@@ -113,3 +118,4 @@ def test_graph_replay_of_the_other_entry_points_and_flags():
         assert torch.equal(vout, vref), "packed requests, replay %d" % rep
         assert torch.equal(out8, ref8), "8-bit scores, replay %d" % rep
         assert torch.equal(cout, cref), "resident cross-attention, replay %d" % rep
+        assert torch.equal(lout, lref), "projection, replay %d" % rep
