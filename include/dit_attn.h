@@ -178,7 +178,9 @@ dit_status dit_attn_forward(const void *q, const void *k, const void *v, void *o
  * not available in this form (DIT_ERR_UNSUPPORTED).  kv_valid (nullable): uint8 [B, Lk] dense, 1 = key attends, 0 = padding.
  * A request with no valid key yields out = 0 and lse = -inf.
  * Flags: QK_*, PV_*, WIDE_QTILE, PIPELINED_SCHEDULE and (with it) the workgroup-size flags apply; K/V are
- * always pre-packed; tiles without a valid key are neither loaded nor computed.
+ * always pre-packed.  With kv_valid, the valid keys of a request (of each sequence in the decoupled form)
+ * are packed densely, in ascending order, into 64-key tiles: a request costs ceil(valid keys / 64)
+ * tiles per sequence wherever its padding sits, and only the last of them is partly filled.
  */
 typedef struct {
     int32_t B, H, D;

@@ -319,7 +319,7 @@ struct CrossPlan {
     Flags fl;
     int nKT, nQT;
     int split, nTA;  // decoupled form: first key of the second sequence, tiles of the first (0, 0: joint)
-    size_t mask_off, list_off, count_off, count_a_off, tiles_off, rstd_off, total;
+    size_t mask_off, list_off, count_off, count_a_off, keysrc_off, tiles_off, rstd_off, total;
 };
 
 dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
@@ -357,12 +357,14 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     pl->nQT = (p->Lq + bq - 1) / bq;
     if ((int64_t)pl->nQT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
     if ((int64_t)pl->nKT * p->B * p->H > 0x7fffffffLL) return DIT_ERR_UNSUPPORTED;
-    // workspace: per-tile key masks, compacted list of non-empty tiles, their count, tile images
+    // workspace: per-tile key masks, compacted list of non-empty tiles, their count, the source key of
+    // every tile slot, tile images
     pl->mask_off = 0;
     pl->list_off = round_up((size_t)p->B * pl->nKT * sizeof(uint64_t), kAlign);
     pl->count_off = pl->list_off + round_up((size_t)p->B * pl->nKT * sizeof(int), kAlign);
     pl->count_a_off = pl->count_off + round_up((size_t)p->B * sizeof(int), kAlign);
-    pl->tiles_off = pl->count_a_off + round_up((size_t)p->B * sizeof(int), kAlign);
+    pl->keysrc_off = pl->count_a_off + round_up((size_t)p->B * sizeof(int), kAlign);
+    pl->tiles_off = pl->keysrc_off + round_up((size_t)p->B * pl->nKT * dit::kBK * sizeof(int), kAlign);
     pl->rstd_off = pl->tiles_off + round_up((size_t)p->B * p->H * pl->nKT * dit::tile_bytes(p->D), kAlign);
     pl->total = pl->rstd_off + rstd_bytes(p->norm, (int64_t)p->B * p->Lq, (int64_t)p->B * p->Lk);
     return DIT_OK;
@@ -495,6 +497,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.tile_list = reinterpret_cast<int*>(ws + pl.list_off);
     pa.tile_count = reinterpret_cast<int*>(ws + pl.count_off);
     pa.tile_count_a = pl.split > 0 ? reinterpret_cast<int*>(ws + pl.count_a_off) : nullptr;
+    pa.key_src = kv_valid ? reinterpret_cast<int*>(ws + pl.keysrc_off) : nullptr;
     pa.split = pl.split;
     pa.nTA = pl.nTA;
     pa.tab = nullptr;
@@ -503,7 +506,9 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.sk_b = p->sk.batch; pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
     pa.sv_b = p->sv.batch; pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
     if (!pl.fl.resident) {
-        hipError_t e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
+        hipError_t e = hipSuccess;
+        if (pa.key_src && (e = dit::launch_key_compact(pa, s)) != hipSuccess) return hip_fail(e, "key_compact_kernel");
+        e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
         if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
         e = dit::launch_tile_compact(pa, s);
         if (e != hipSuccess) return hip_fail(e, "tile_compact_kernel");
@@ -675,6 +680,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 117; }
+int dit_attn_version(void) { return 118; }
 
 }  // extern "C"

@@ -74,6 +74,7 @@ struct PackArgs {
     const void* k;
     const void* v;
     const uint8_t* valid;  // nullable [B, Lk]
+    int* key_src;          // with valid: [B, nKT, 64] source key of every tile slot, -1 = empty (launch_key_compact)
     uint8_t* tiles;        // [B*H, nKT, TILE_BYTES]
     uint64_t* tile_mask;   // nullable [B, nKT]
     int* tile_list;        // nullable [B, nKT], filled by launch_tile_compact
@@ -137,6 +138,9 @@ hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D
 hipError_t launch_attn_pipe_varlen(const AttnArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, int nw,
                                    hipStream_t s);
 hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
+// before launch_prepack when a.valid is set: the valid keys of every batch entry (of each key group) in
+// ascending order, densely over the tile slots
+hipError_t launch_key_compact(const PackArgs& a, hipStream_t s);
 // after launch_prepack: compact the non-empty tiles of every batch entry into tile_list / tile_count
 hipError_t launch_tile_compact(const PackArgs& a, hipStream_t s);
 // qb = 32-row query blocks per wavefront (1 or 2)

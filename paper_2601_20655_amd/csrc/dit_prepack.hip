@@ -65,6 +65,7 @@ struct PackTile {
     uint8_t* dst;        // tile image
     int64_t k_off, v_off;  // element offset of key 0 of this sequence for this head
     int key0, key_end;   // keys [key0, key0 + 64) clipped to key_end
+    const int* key_src;  // if set: slot r holds key key_src[r] (-1: empty) instead of key0 + r
     RopeGeom rg;         // with this sequence's grid
     int h;               // head (channel weights of the normalisation)
     int64_t stat_off;    // index of key 0 in the per-token normalisation table
@@ -83,18 +84,19 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int r = tid / CPR + i * ROWS_PER_PASS;
-        const int key = t.key0 + r;
+        const int key = t.key_src ? t.key_src[r] : t.key0 + r;
+        const bool ok = t.key_src ? key >= 0 : key < t.key_end;
         float xk[8], xv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) xk[e] = xv[e] = 0.f;
-        if (key < t.key_end) {
+        if (ok) {
             load8(a.k, t.k_off + (int64_t)key * a.sk_t + 8 * c, a.in_f32, xk);
             load8(a.v, t.v_off + (int64_t)key * a.sv_t + 8 * c, a.in_f32, xv);
         }
         if (a.kn.mode) {  // the CPR neighbouring lanes that share a row add up its squares
             float rs;
             if (a.kn.mode == 2) {
-                rs = key < t.key_end ? a.kn.rstd[t.stat_off + key] : 0.f;
+                rs = ok ? a.kn.rstd[t.stat_off + key] : 0.f;
             } else {
                 float ss = 0.f;
 #pragma unroll
@@ -103,9 +105,9 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
                 for (int m = 1; m < CPR; m <<= 1) ss += __shfl_xor(ss, m);
                 rs = 1.0f / sqrtf(ss * (1.0f / D) + a.kn.eps);
             }
-            if (key < t.key_end) norm8(xk, a.kn, rs, t.h, D, c);
+            if (ok) norm8(xk, a.kn, rs, t.h, D, c);
         }
-        if (key < t.key_end) {
+        if (ok) {
             if (a.tab) {
                 int pt, ph, pw;
                 token_pos(key, t.rg, pt, ph, pw);
@@ -171,15 +173,14 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     const bool second = a.split > 0 && j >= a.nTA;
     t.key0 = second ? a.split + (j - a.nTA) * kBK : j * kBK;
     t.key_end = (a.split > 0 && !second) ? a.split : a.Lk;
+    t.key_src = a.key_src ? a.key_src + ((size_t)b * a.nKT + j) * kBK : nullptr;
     t.rg = a.rg;
     t.h = h;
     t.stat_off = (int64_t)b * a.Lk;
     pack_tile<D, QK_OP, PV_OP>(a, t, vs);
 
     if (a.tile_mask && h == 0 && tid < 64) {
-        const int key = t.key0 + tid;
-        bool ok = key < t.key_end;
-        if (ok && a.valid) ok = a.valid[(size_t)b * a.Lk + key] != 0;
+        const bool ok = t.key_src ? t.key_src[tid] >= 0 : t.key0 + tid < t.key_end;
         const uint64_t m = __ballot(ok);
         if (tid == 0) a.tile_mask[(size_t)b * a.nKT + j] = m;
     }
@@ -201,12 +202,40 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_varlen_kernel(const PackA
     t.v_off = (int64_t)q.tok0 * a.sv_t + (int64_t)h * a.sv_h;
     t.key0 = j * kBK;
     t.key_end = q.L;
+    t.key_src = nullptr;
     t.rg = a.rg;
     t.rg.Hg = q.Hg;
     t.rg.Wg = q.Wg;
     t.h = h;
     t.stat_off = q.tok0;
     pack_tile<D, QK_OP, PV_OP>(a, t, vs);
+}
+
+// Key padding masks: one wavefront per (batch entry, key group) writes the group's valid keys, in
+// ascending order, densely into the slots of the group's tiles; the slots left over get -1.  Attention
+// does not depend on the order of the keys, so the padded keys cost no tile: a request keeps
+// ceil(valid keys / 64) tiles per group whatever the positions of its padding.
+__global__ void __launch_bounds__(64) key_compact_kernel(const uint8_t* valid, int* key_src, int Lk, int nKT,
+                                                         int split, int nTA) {
+    const int b = blockIdx.x, g = blockIdx.y, lane = threadIdx.x;
+    const int k0 = g == 0 ? 0 : split, k1 = (g == 0 && split > 0) ? split : Lk;
+    const int t0 = g == 0 ? 0 : nTA, t1 = (g == 0 && split > 0) ? nTA : nKT;
+    int* out = key_src + ((size_t)b * nKT + t0) * kBK;
+    int count = 0;
+    for (int base = k0; base < k1; base += 64) {
+        const int key = base + lane;
+        const bool ok = key < k1 && valid[(size_t)b * Lk + key] != 0;
+        const uint64_t m = __ballot(ok);
+        if (ok) out[count + __popcll(m & ((1ull << lane) - 1ull))] = key;
+        count += __popcll(m);
+    }
+    for (int i = count + lane; i < (t1 - t0) * kBK; i += 64) out[i] = -1;
+}
+
+hipError_t launch_key_compact(const PackArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(key_compact_kernel, dim3(a.B, a.split > 0 ? 2 : 1), dim3(64), 0, s, a.valid, a.key_src, a.Lk,
+                       a.nKT, a.split, a.nTA);
+    return hipGetLastError();
 }
 
 // One wavefront per batch entry: tile_list[b] = ascending indices of tiles whose key mask is not empty.

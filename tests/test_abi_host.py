@@ -68,7 +68,8 @@ def test_workspace_size_formula():
     p = self_params(flags=B.DIT_FLAG_KV_FUSED | B.DIT_FLAG_PV_BF16)
     assert B.dit_attn_workspace_bytes(p) == up((2 * 22 + 3 * 21 + 4 * 21) * 8)
     c = cross_params()
-    assert B.dit_cross_attn_workspace_bytes(c) == up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 2 * 13 * 36 * 1024)
+    assert B.dit_cross_attn_workspace_bytes(c) == (up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 13 * 64 * 4)
+                                                   + up(2 * 2 * 13 * 36 * 1024))
 
 
 FAKE = 0x1000  # a 16-byte aligned non-NULL address that is never dereferenced: validation fails first
@@ -137,11 +138,11 @@ def test_cross_attn_rejects_bad_arguments():
     assert call_cross(cross_params(split=512, flags=B.DIT_FLAG_WIDE_QTILE)) == B.DIT_ERR_UNSUPPORTED
     # a split that is not a tile multiple needs one more tile: 500 -> 8 + 5 tiles of 64 keys
     assert B.dit_cross_attn_workspace_bytes(cross_params(split=500)) == \
-        up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 2 * 13 * 36 * 1024)
+        up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 13 * 64 * 4) + up(2 * 2 * 13 * 36 * 1024)
     assert B.dit_cross_attn_workspace_bytes(cross_params(split=10)) == \
-        up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 2 * 13 * 36 * 1024)
+        up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 13 * 64 * 4) + up(2 * 2 * 13 * 36 * 1024)
     assert B.dit_cross_attn_workspace_bytes(cross_params(split=65)) == \
-        up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 2 * 13 * 36 * 1024)
+        up(2 * 13 * 8) + up(2 * 13 * 4) + 2 * up(2 * 4) + up(2 * 13 * 64 * 4) + up(2 * 2 * 13 * 36 * 1024)
     assert call_cross(cross_params(), q=FAKE + 8) == B.DIT_ERR_ALIGNMENT
     need = B.dit_cross_attn_workspace_bytes(cross_params())
     assert call_cross(cross_params(), ws_bytes=need - 1) == B.DIT_ERR_WORKSPACE

@@ -134,3 +134,46 @@ def test_full_size_decoupled_cross_sampled_rows():
     del out
     out = run_cross(q, k, v, valid, split=cfg["n_text"])
     compare(to_f64(out[:, torch.from_numpy(rows).cuda()]), ref, bf16_out=True, what="cross_14b decoupled bf16 out")
+
+
+@pytest.mark.parametrize("split", [0, 300])
+@pytest.mark.parametrize("shape", [0, B.DIT_FLAG_PIPELINED_SCHEDULE])
+def test_scattered_key_masks_are_compacted(split, shape):
+    """Validity scattered over the keys instead of a padded tail: every third key, a request with
+    two isolated keys in different tiles, a request with one whole tile valid in the middle, and a
+    request with every key valid.  The library packs the valid keys densely into tiles (the order of
+    keys does not matter to attention); output and log-sum-exp against the oracle on all rows, and a
+    second call on the resident tiles with the mask pointer gone."""
+    import torch
+
+    if split and shape:
+        pytest.skip("the decoupled form has no pipelined kernel")
+    cfg = dict(B=4, Lq=150, n_text=300, n_image=215, H=2, D=128, dtype="bf16", min_text=16, seed=401)
+    q, k, v, valid, _ = wl.cross_attn_inputs(cfg)
+    Lk = k.shape[1]
+    valid[:] = 0
+    valid[0, ::3] = 1
+    valid[1, 70] = valid[1, 400] = 1
+    valid[2, 320:384] = 1
+    valid[3, :] = 1
+    if split:  # every key group of every request keeps at least one key
+        valid[1, 10] = 1
+        valid[2, 5] = 1
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    want_lse = split == 0
+    res = run_cross(q, k, v, valid, flags=shape, split=split, workspace=ws, out_dtype=torch.float32, want_lse=want_lse)
+    if split:
+        ref = oracle.cross_attn_decoupled(q, k, v, split, valid)
+        compare(to_f64(res), ref, what="scattered masks, decoupled")
+    else:
+        ref, ref_lse = oracle.cross_attn(q, k, v, valid, want_lse=True)
+        out, lse = res
+        compare(to_f64(out), ref, what="scattered masks, joint, flags %d" % shape)
+        assert np.max(np.abs(to_f64(lse) - ref_lse)) < 5e-3
+    q2 = wl.cross_attn_inputs(cfg, seed=402)[0]
+    nan = torch.full((cfg["B"], Lk, cfg["H"], cfg["D"]), float("nan"), dtype=torch.bfloat16, device="cuda")
+    out2 = B.dit_cross_attn_forward(to_dev(q2), nan, nan, None, flags=shape | B.DIT_FLAG_KV_RESIDENT, split=split,
+                                    workspace=ws, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ref2 = oracle.cross_attn_decoupled(q2, k, v, split, valid) if split else oracle.cross_attn(q2, k, v, valid)
+    compare(to_f64(out2), ref2, what="scattered masks, resident call")
