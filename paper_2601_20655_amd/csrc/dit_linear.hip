@@ -167,9 +167,13 @@ __global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) 
     // tile of step k+SX-1 over the two slices before the next barrier.  The counted wait in front of
     // the barrier leaves exactly the youngest x tile in flight.
     static_assert(SX == 3 && SW == 2, "the load schedule below is written for 3 x and 2 w buffers");
+    // (the bare barrier instruction: __syncthreads() is a fence too, for which the compiler drains every
+    // load in flight -- vmcnt(0) -- in front of the barrier, and the x tile that is meant to stay in
+    // flight across it would be waited for after all)
     auto sync_point = [&]() {
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NCH) : "memory");
-        __syncthreads();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
     };
     constexpr int WPB = NCH / 4;  // w chunks per token block
     // Prologue: tiles x(0), w(0), x(1) in a burst; the first barrier; then what a last slice would
