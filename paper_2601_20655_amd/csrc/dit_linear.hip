@@ -249,21 +249,31 @@ __global__ void __launch_bounds__(64 * NW, 1) linear_kernel(const LinearArgs a) 
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
 
-    // ---- epilogue: lane holds token (column l32 of block tb), features 32*fb + 8*g + 4*half + e ----
+    // ---- epilogue: lane holds token (column l32 of block tb), features 32*fb + 8*g + 4*half + e.
+    // All bias values are fetched before the first store: a load waited for behind stores would wait
+    // for the stores too (one counter tracks both), eight round trips in a row.
+    uint2 bb[FB][4];
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n0 = tn * kLinBN + wf * 32 * FB + fb * 32 + 8 * g + 4 * half;
+            bb[fb][g] = make_uint2(0u, 0u);
+            if (a.bias && n0 < a.N) bb[fb][g] = *reinterpret_cast<const uint2*>(a.bias + n0);
+        }
+    // (the wait for them happens here, once: the empty statement reads every value)
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) asm volatile("" : "+v"(bb[fb][g].x), "+v"(bb[fb][g].y));
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int n0 = tn * kLinBN + wf * 32 * FB + fb * 32 + 8 * g + 4 * half;
             if (n0 >= a.N) continue;  // N is a multiple of 8: a quad is inside or outside as a whole
-            float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
-            if (a.bias) {
-                const uint2 bb = *reinterpret_cast<const uint2*>(a.bias + n0);
-                b0 = __uint_as_float(bb.x << 16);
-                b1 = __uint_as_float(bb.x & 0xffff0000u);
-                b2 = __uint_as_float(bb.y << 16);
-                b3 = __uint_as_float(bb.y & 0xffff0000u);
-            }
+            const float b0 = __uint_as_float(bb[fb][g].x << 16), b1 = __uint_as_float(bb[fb][g].x & 0xffff0000u);
+            const float b2 = __uint_as_float(bb[fb][g].y << 16), b3 = __uint_as_float(bb[fb][g].y & 0xffff0000u);
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
                 const int m = tm * kLinBM + wt * 32 * TB + tb * 32 + l32;
