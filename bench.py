@@ -198,7 +198,7 @@ def main():
     ap.add_argument("--decoupled", action="store_true", help="cross_14b: one softmax per conditioning sequence")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (all heads of one request on one MI355X, no "
+        sys.exit("bench.py: this library runs on ONE GPU (all heads of one request on one MI355X, no "
                  "collectives); --gpus %d is not supported" % args.gpus)
     if args.workload != "step":
         return other_workload(args)
