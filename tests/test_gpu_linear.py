@@ -91,3 +91,25 @@ def test_full_size_sampled_rows(name):
     got = to_f64(y[torch.from_numpy(rows).cuda()])
     ref = oracle.linear(x[rows], w, b)
     compare(got, ref, bf16_out=True, tol=tol(cfg["K"]), what=name)
+
+
+@pytest.mark.parametrize("M", [255, 256, 257, 511, 513])
+@pytest.mark.parametrize("N", [248, 256, 264])
+def test_tile_boundaries_exact(M, N):
+    """Token and feature counts one short of, on and one past a tile boundary, with integer-valued
+    inputs whose sums fit 24 bits: every output, bias included, must be exact (no tolerance), so a row
+    or feature quad that lands in the wrong place, is dropped or is written twice cannot hide."""
+    import torch
+
+    K = 128
+    rng = np.random.default_rng(1000 * M + N)
+    x = rng.integers(-8, 9, size=(M, K)).astype(np.float32)
+    w = rng.integers(-8, 9, size=(N, K)).astype(np.float32)
+    bias = rng.integers(-64, 65, size=N).astype(np.float32)
+    xb, wb, bb = (wl.f32_to_bf16_bits(a) for a in (x, w, bias))
+    y = torch.full((M + 2, N + 8), -77.0, dtype=torch.float32, device="cuda")
+    B.dit_linear_forward(to_dev(xb), to_dev(wb), to_dev(bb), out=y[1:M + 1, :N])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(y[1:M + 1, :N]), oracle.linear(xb, wb, bb))
+    # the guard rows and columns around the output keep their contents
+    assert torch.all(y[0] == -77.0) and torch.all(y[M + 1] == -77.0) and torch.all(y[:, N:] == -77.0)
