@@ -28,9 +28,9 @@ PEAK_TFLOPS_8BIT_DENSE = 5000.0   # published dense fp8 MFMA peak
 # keyed by library version: a library whose kernel has changed since reports null.
 # (111 added a host-side flag only and 112 separate instantiations; their default kernel is that of 110.
 # 115 changed the cross-attention workgroup order only, 116 added the projection entry point, 117 changed the row sums
-# of the bf16-P variants, 118 the packing of masked cross-attention keys and 119, 120 the projection kernel; the
+# of the bf16-P variants, 118 the packing of masked cross-attention keys 119, 120 the projection kernel and 121 the plain (cross-attention) kernel; the
 # default self-attention kernel is that of 114, checked instruction for instruction.)
-TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9, 115: 3.92e9, 116: 3.92e9, 117: 3.92e9, 118: 3.92e9, 119: 3.92e9, 120: 3.92e9}
+TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9, 115: 3.92e9, 116: 3.92e9, 117: 3.92e9, 118: 3.92e9, 119: 3.92e9, 120: 3.92e9, 121: 3.92e9}
 
 
 class HipEvents:

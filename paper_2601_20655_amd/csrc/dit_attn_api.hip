@@ -680,6 +680,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 120; }
+int dit_attn_version(void) { return 121; }
 
 }  // extern "C"

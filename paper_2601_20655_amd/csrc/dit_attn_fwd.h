@@ -158,11 +158,17 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
 
     // ---- running state ----
     f32x16 O[NDB][QB];
+    // negm: every element = -(running maximum), or 0 while the row has seen no valid key.  A score
+    // MFMA chain starts from it, so the scores come out relative to the running maximum and the common
+    // case (no row tops it by more than the threshold) needs no subtraction in front of exp2.
+    f32x16 negm[QB];
     float m_run[QB], l_run[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         m_run[qb] = -INFINITY;
         l_run[qb] = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) negm[qb][r] = 0.f;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -261,6 +267,8 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
                         }
                     m_run[qb] = -INFINITY;
                     l_run[qb] = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) negm[qb][r] = 0.f;
                 }
             }
         }
@@ -281,18 +289,13 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
             // S^T[key][query] for two 32-key blocks
             f32x16 S[2][QB];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) S[kb][qb][r] = 0.f;
-#pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
                     const u32x4 ka = *reinterpret_cast<const u32x4*>(kt + kb * 32 * G::KROW + ks * 32);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) S[kb][qb] = mfma32<QK_OP>(ka, Qf[qb][ks], S[kb][qb]);
+                    for (int qb = 0; qb < QB; ++qb)
+                        S[kb][qb] = mfma32<QK_OP>(ka, Qf[qb][ks], ks == 0 ? negm[qb] : S[kb][qb]);
                 }
             }
 
@@ -318,21 +321,31 @@ __global__ void __launch_bounds__(kThreads, QB == 1 ? 2 : 1) attn_fwd_kernel(con
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[1][qb][r]);
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const bool need = mx > m_run[qb] + kRescaleThr;
+                // mx is relative to the base the chain started from: the running maximum, or 0 for a row
+                // that has seen no valid key yet (which takes the update as soon as it sees one)
+                const bool fresh = m_run[qb] == -INFINITY;
+                const bool need = fresh ? mx > -INFINITY : mx > kRescaleThr;
                 if (__any(need)) {
-                    const float alpha = need ? __builtin_amdgcn_exp2f(m_run[qb] - mx) : 1.0f;
-                    m_run[qb] = need ? mx : m_run[qb];
+                    const float m_new = (fresh ? 0.f : m_run[qb]) + mx;
+                    const float alpha = need ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.0f;
+                    const float shift = need ? mx : 0.f;
+                    m_run[qb] = need ? m_new : m_run[qb];
                     l_run[qb] *= alpha;
 #pragma unroll
                     for (int db = 0; db < NDB; ++db)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) O[db][qb][r] *= alpha;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        negm[qb][r] = m_run[qb] == -INFINITY ? 0.f : -m_run[qb];
+                        S[0][qb][r] -= shift;
+                        S[1][qb][r] -= shift;
+                    }
                 }
-                const float mr = m_run[qb];
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) S[kb][qb][r] = __builtin_amdgcn_exp2f(S[kb][qb][r] - mr);
+                    for (int r = 0; r < 16; ++r) S[kb][qb][r] = __builtin_amdgcn_exp2f(S[kb][qb][r]);
                 // fp16 P: the row sum is taken in fp32 over the unrounded probabilities, four chains of
                 // plain additions: the dot-product instruction that would sum the packed pairs does
                 // not overlap with a running MFMA (measured: about 8 clocks each, unhidden), additions
