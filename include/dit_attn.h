@@ -202,6 +202,29 @@ dit_status dit_cross_attn_forward(const void *q, const void *k, const void *v,
                                   size_t workspace_bytes, void *stream);
 
 /*
+ * dit_cross_attn_forward for callers that cannot allocate device memory or take a workspace from
+ * an allocator: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results, flags and errors as dit_cross_attn_forward, minus the workspace: the
+ * scratch is a device array of DIT_STATIC_WORKSPACE_BYTES bytes that is part of the library image
+ * (every GPU the library runs on holds its own copy until the process ends).  The call makes no
+ * hipMalloc / hipFree and calls no allocating routine; it works on the device that is current.
+ *  - DIT_ERR_WORKSPACE if dit_cross_attn_workspace_bytes(p) exceeds DIT_STATIC_WORKSPACE_BYTES
+ *    (the batched 14B-class case -- 4 requests x 40 heads x 769 keys, d128 -- needs 73.2 MiB).
+ *  - The first call on a device looks the array's address up (hipGetSymbolAddress; this may load
+ *    the library's code object on that device): make one call before capturing a graph.
+ *  - All calls on one GPU share the one array: calls that overlap on a GPU (two streams, two
+ *    threads) race, and the caller must order them.  The array keeps what the last call left, and
+ *    nothing in it has to start at zero: every call writes each mask, list, count and tile before
+ *    it reads it.  With DIT_FLAG_KV_RESIDENT the tiles of the last call ON THIS ENTRY POINT AND GPU
+ *    are reused, under that flag's rules.
+ */
+#define DIT_STATIC_WORKSPACE_BYTES (96u << 20)
+
+dit_status dit_cross_attn_forward_static(const void *q, const void *k, const void *v,
+                                         const uint8_t *kv_valid, void *out, float *lse,
+                                         const dit_cross_attn_params *p, void *stream);
+
+/*
  * Self-attention of several requests in one call (batched serving: the Diffusion stage works on
  * a batch of Tasks whose videos differ in resolution and length, Sec. 4.4 "TaskWorker").
  * Request i has its own latent grid grids[i] = (T, Hg, Wg) and L_i = T*Hg*Wg tokens; the requests

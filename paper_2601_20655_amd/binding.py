@@ -40,6 +40,7 @@ EXPORTS = (
     "dit_attn_forward",
     "dit_cross_attn_workspace_bytes",
     "dit_cross_attn_forward",
+    "dit_cross_attn_forward_static",
     "dit_attn_varlen_workspace_bytes",
     "dit_attn_varlen_forward",
     "dit_linear_forward",
@@ -150,6 +151,8 @@ def lib():
         L.dit_cross_attn_forward.restype = ctypes.c_int
         L.dit_cross_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(dit_cross_attn_params),
                                              vp, ctypes.c_size_t, vp]
+        L.dit_cross_attn_forward_static.restype = ctypes.c_int
+        L.dit_cross_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(dit_cross_attn_params), vp]
         L.dit_attn_varlen_workspace_bytes.restype = ctypes.c_size_t
         L.dit_attn_varlen_workspace_bytes.argtypes = [ctypes.POINTER(dit_varlen_attn_params)]
         L.dit_attn_varlen_forward.restype = ctypes.c_int
@@ -334,6 +337,31 @@ def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0
                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if st != DIT_OK:
         raise DitError(st, "dit_cross_attn_forward")
+    return (out, lse) if lse is not None else out
+
+
+DIT_STATIC_WORKSPACE_BYTES = 96 << 20
+
+
+def dit_cross_attn_forward_static(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0, flags=0, split=0,
+                                  stream=None, norm=None):
+    """dit_cross_attn_forward on the library's own static device workspace.  `out` (and `lse`) must be
+    given: this wrapper allocates nothing either."""
+    import torch
+
+    if not q.is_cuda or out is None:
+        raise ValueError("dit_cross_attn_forward_static needs device tensors and a caller-provided out")
+    B = q.shape[0]
+    if kv_valid is not None:
+        if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, k.shape[1]):
+            raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
+    p = cross_attn_params(q, k, v, out, scale, flags, split, norm)
+    st = lib().dit_cross_attn_forward_static(q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                             kv_valid.data_ptr() if kv_valid is not None else None,
+                                             out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                             ctypes.byref(p), _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_cross_attn_forward_static")
     return (out, lse) if lse is not None else out
 
 

@@ -51,6 +51,12 @@ dit_status hip_fail(hipError_t e, const char* where) {
     return DIT_ERR_HIP;
 }
 
+}  // namespace
+
+int dit::report_hip_error(hipError_t e, const char* where) { return hip_fail(e, where); }
+
+namespace {
+
 constexpr size_t kAlign = 256;
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -132,6 +132,9 @@ struct VarlenTable {
     ReqDesc r[kMaxRequests];
 };
 
+// Records "<where>: <HIP error text>" for dit_last_hip_error() of the calling thread; returns DIT_ERR_HIP.
+int report_hip_error(hipError_t e, const char* where);
+
 hipError_t launch_rope_table(const TableArgs& a, hipStream_t s);
 hipError_t launch_token_rstd(const RstdArgs& a, hipStream_t s);
 hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, hipStream_t s);

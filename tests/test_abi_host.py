@@ -282,3 +282,19 @@ def test_bench_refuses_more_than_one_gpu():
                        stderr=subprocess.PIPE, text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_static_workspace_rejects_what_does_not_fit():
+    # 8 x 64 heads x 13 tiles x 36 KiB = 234 MiB of tiles: beyond the array; refused before any launch
+    Bz, Lq, Lk, H, D = 8, 64, 769, 64, 128
+    sq = B.dit_strides(Lq * H * D, H * D, D)
+    sk = B.dit_strides(Lk * H * D, H * D, D)
+    p = B.dit_cross_attn_params(Bz, H, D, Lq, Lk, 0.0, B.DIT_BF16, B.DIT_BF16, 0, 0, sq, sk, sk, sq)
+    assert B.dit_cross_attn_workspace_bytes(p) > B.DIT_STATIC_WORKSPACE_BYTES
+    fake = 0x1000
+    st = B.lib().dit_cross_attn_forward_static(fake, fake, fake, None, fake, None, ctypes.byref(p), None)
+    assert st == B.DIT_ERR_WORKSPACE
+    # invalid parameters come back with the ordinary entry point's status
+    p.D = 96
+    st = B.lib().dit_cross_attn_forward_static(fake, fake, fake, None, fake, None, ctypes.byref(p), None)
+    assert st == B.DIT_ERR_UNSUPPORTED
