@@ -6,8 +6,9 @@ over the 32,760 tokens of a 21x30x52 latent grid (40 heads, head_dim 128, 3-axis
 followed by cross-attention of the same 32,760 queries over 769 conditioning keys (512 text with a
 padding mask + 257 image).  Inputs are seeded synthetic bf16 N(0,1) tensors resident in HBM before
 the timed region.  Prints ONE JSON line: whole-step attention TFLOP/s (4*H*Lq*Lk*D flop per
-product pair, RoPE/softmax/mask not counted), a roofline object for the dominant kernel (the
-self-attention kernel, timed with HIP events on its stream) and the CPU fp64 oracle timed on a
+product pair over the keys that attend, RoPE/softmax/mask not counted), a roofline object for the
+dominant kernel (the self-attention kernel, timed with HIP events on its stream; beside the published
+peak, what an MFMA-only micro-benchmark sustains on the same board) and the CPU fp64 oracle timed on a
 bounded row sample as a baseline.
 """
 import argparse
@@ -23,14 +24,75 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
 PEAK_TFLOPS_8BIT_DENSE = 5000.0   # published dense fp8 MFMA peak
 
-# HBM bytes per launch of the self-attention kernel at the dit_14b shape, default flags, from the
-# FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by a plain copy kernel),
-# keyed by library version: a library whose kernel has changed since reports null.
-# (111 added a host-side flag only and 112 separate instantiations; their default kernel is that of 110.
-# 115 changed the cross-attention workgroup order only, 116 added the projection entry point, 117 changed the row sums
-# of the bf16-P variants, 118 the packing of masked cross-attention keys 119, 120 the projection kernel and 121 the plain (cross-attention) kernel; the
-# default self-attention kernel is that of 114, checked instruction for instruction.)
-TRAFFIC_BYTES_BY_VERSION = {110: 4.01e9, 111: 4.01e9, 112: 4.01e9, 113: 3.99e9, 114: 3.92e9, 115: 3.92e9, 116: 3.92e9, 117: 3.92e9, 118: 3.92e9, 119: 3.92e9, 120: 3.92e9, 121: 3.92e9}
+COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "attn_fwd_pipe_kernel_dit14b_counters.txt")
+
+
+def traffic_bytes_for(version):
+    """HBM bytes per launch of the self-attention kernel at the dit_14b shape with default flags, from the
+    FETCH_SIZE / WRITE_SIZE counter runs summarised in COUNTER_SUMMARY (each scaled by a plain copy kernel).
+    The summary names the library version it was taken with ("library_version: N") and the figure
+    ("traffic_bytes_per_launch: X"); a library of any other version reports null."""
+    try:
+        text = open(COUNTER_SUMMARY).read()
+    except OSError:
+        return None
+    found = {}
+    for line in text.splitlines():
+        key, _, val = line.partition(":")
+        if key.strip() in ("library_version", "traffic_bytes_per_launch"):
+            try:
+                found[key.strip()] = float(val.split()[0])
+            except (ValueError, IndexError):
+                return None
+    if int(found.get("library_version", -1)) != int(version):
+        return None
+    return found.get("traffic_bytes_per_launch")
+
+
+def measure_mfma_peak(B, torch, launches=3, mfma_per_wavefront=1_200_000):
+    """Sustained rate of the matrix cores alone on this board (dit_mfma_probe: two wavefronts per SIMD issuing
+    32x32x16 MFMAs back to back from registers), TFLOP/s, for fp16 and bf16 operands, constant and random.
+    Each figure is the mean of `launches` launches of about 50 ms after one warm-up launch."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(2 * cus * 256, dtype=torch.float32, device="cuda")
+    out = {}
+    for dt, dname in ((B.DIT_PROBE_F16, "f16"), (B.DIT_PROBE_BF16, "bf16")):
+        for rnd, rname in ((0, "constant"), (1, "random")):
+            B.dit_mfma_probe(dt, rnd, mfma_per_wavefront, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = 0.0
+            for _ in range(launches):
+                flops += B.dit_mfma_probe(dt, rnd, mfma_per_wavefront, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            out["%s_%s" % (dname, rname)] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return out
+
+
+def mfma_peak_workload(args):
+    """Secondary line: the MFMA-only micro-benchmark by itself."""
+    import torch
+
+    from paper_2601_20655_amd import binding as B
+
+    B.lib()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    t0 = time.perf_counter()
+    rates = measure_mfma_peak(B, torch, launches=max(args.steps, 1))
+    dt = time.perf_counter() - t0
+    v = rates["f16_random"]
+    print(json.dumps({
+        "metric": "MFMA-only sustained TFLOP/s (32x32x16, two wavefronts per SIMD, random fp16 operands)",
+        "value": v, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": 1,
+        "ms_per_step": round(dt * 1e3 / (4 * max(args.steps, 1)), 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "mfma_peak: every SIMD issues MFMAs from registers, nothing else", "rates_tflops": rates},
+        "roofline": {"kernel": "mfma_probe_kernel", "bound": "mfma", "achieved": v, "peak": PEAK_TFLOPS_16BIT_DENSE,
+                     "unit": "TFLOP/s", "frac": round(v / PEAK_TFLOPS_16BIT_DENSE, 4), "traffic": None},
+    }))
 
 
 class HipEvents:
@@ -149,6 +211,9 @@ def other_workload(args):
                          dtype=torch.uint8, device="cuda")
         Lq = q.shape[1]
         flops = 4.0 * H * Lq * D * float(valid.sum())  # keys that attend; padded keys are skipped, not computed
+        flops_dense = 4.0 * cfg["B"] * H * Lq * D * float(valid.shape[1])
+        # algorithmic bytes: q read and out written once, the attending k and v rows read once
+        io_bytes = 2.0 * q.numel() * q.element_size() + 2.0 * float(valid.sum()) * H * D * k.element_size()
         what = "%s cross-attention, B=%d, %d queries x (512 text masked to %s + 257 image) keys, %d heads, d%d" % (
             "decoupled" if split else "joint", cfg["B"], Lq, list(map(int, text_len)), H, D)
         kernel = "attn_fwd_kernel"
@@ -163,6 +228,16 @@ def other_workload(args):
         args.flags = resident
     ms, kern_ms = time_calls(B, torch, call, args.steps, args.warmup)
     achieved = flops / (kern_ms * 1e-3) / 1e12
+    extra = {}
+    if cfg["kind"] == "cross":
+        # this shape is close enough to the HBM roofline that the streaming rate is reported beside the flops
+        extra = {"tflops_dense_count": round(flops_dense / (ms * 1e-3) / 1e12, 2),
+                 "tflops_over_attending_keys": round(flops / (ms * 1e-3) / 1e12, 2),
+                 "algorithmic_bytes": io_bytes,
+                 "achieved_GBps_whole_call": round(io_bytes / (ms * 1e-3) / 1e9, 1),
+                 "achieved_GBps_attn_kernel": round(io_bytes / (kern_ms * 1e-3) / 1e9, 1),
+                 "hbm_peak_GBps": 8000.0,
+                 "hbm_floor_ms": round(io_bytes / 8e12 * 1e3, 4)}
     fp8 = bool(args.flags & B.DIT_FLAG_QK_FP8)
     # 8-bit scores: half of the flops run at the 8-bit peak, half at the 16-bit peak
     peak = 2.0 / (1.0 / PEAK_TFLOPS_8BIT_DENSE + 1.0 / PEAK_TFLOPS_16BIT_DENSE) if fp8 else PEAK_TFLOPS_16BIT_DENSE
@@ -176,7 +251,8 @@ def other_workload(args):
         "dtype": "bf16" if cfg["kind"] == "linear" else "fp8 scores, f16 PV" if fp8
                  else "f16" if not (args.flags & B.DIT_FLAG_QK_BF16) else "bf16",
         "data": "synthetic",
-        "config": {"workload": what, "flags": args.flags, "attn_kernel_ms": round(kern_ms, 4), "flops_per_step": flops},
+        "config": dict({"workload": what, "flags": args.flags, "attn_kernel_ms": round(kern_ms, 4),
+                        "flops_per_step": flops}, **extra),
         "roofline": {"kernel": kernel, "bound": "mfma", "achieved": round(achieved, 2),
                      "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None},
     }))
@@ -189,17 +265,21 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--flags", type=int, default=0, help="DIT_FLAG_* bits for both calls (0 = library defaults)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-mfma-peak", action="store_true", help="skip the MFMA-only micro-benchmark leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the timed region, so that a "
                          "counter run (FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
     ap.add_argument("--workload", default="step",
                     help="'step' (default: the headline metric) or one of the other shapes for a secondary "
-                         "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b, qkv_proj_14b, out_proj_14b")
+                         "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b, qkv_proj_14b, out_proj_14b, "
+                         "mfma_peak (the MFMA-only micro-benchmark)")
     ap.add_argument("--decoupled", action="store_true", help="cross_14b: one softmax per conditioning sequence")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU (all heads of one request on one MI355X, no "
                  "collectives); --gpus %d is not supported" % args.gpus)
+    if args.workload == "mfma_peak":
+        return mfma_peak_workload(args)
     if args.workload != "step":
         return other_workload(args)
     if args.flags & (1 << 12):
@@ -255,26 +335,35 @@ def main():
     torch.cuda.synchronize()
 
     ev = HipEvents(args.steps)
+    # the whole self-attention call (rotation table, pre-pack pass, attention kernel) is bracketed too
+    call_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         a, b = ev.pairs[i]
+        call_ev[i][0].record(stream)
         B.dit_attn_set_timing_events(a, b)
         B.dit_attn_forward(qd, kd, vd, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
                            stream=stream)
         B.dit_attn_set_timing_events(None, None)
+        call_ev[i][1].record(stream)
         B.dit_cross_attn_forward(out, ckd, cvd, cvalid_d, out=cout, flags=pc.flags, workspace=ws, stream=stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kern_ms = ev.elapsed_ms()
     ev.close()
+    self_call_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in call_ev]))
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     flops_self = 4.0 * Bsz * H * L * L * D
-    flops_cross = 4.0 * Bsz * H * L * Lk * D  # dense count over all 769 keys
+    # cross-attention: padded keys are skipped, not computed, so only the keys that attend count
+    n_attend = float(cvalid.sum())
+    flops_cross = 4.0 * H * L * D * n_attend
     tflops = (flops_self + flops_cross) / (ms_per_step * 1e-3) / 1e12
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = flops_self / (kern_avg_ms * 1e-3) / 1e12
+    qk_name = "bf16" if args.flags & B.DIT_FLAG_QK_BF16 else "fp16"
+    pv_name = "bf16" if args.flags & B.DIT_FLAG_PV_BF16 else "fp16"
 
     result = {
         "metric": "attention TFLOP/s + % bf16 MFMA peak at 32,760 tokens x 40 heads x d128",
@@ -287,16 +376,26 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16" if not (args.flags & B.DIT_FLAG_QK_BF16) else "bf16",
+        "dtype": "f16" if qk_name == "fp16" else "bf16",
         "data": "synthetic",
         "config": {
             "workload": "dit_14b self-attention (B=1, grid 21x30x52 = 32,760 tokens, 40 heads, d128, RoPE 44/42/42) "
-                        "+ cross-attention of the same queries over 769 keys (512 text masked to %d, 257 image)"
-                        % int(text_len[0]),
-            "io": "bf16 in, bf16 out; 16-bit MFMA operands, fp32 accumulate",
+                        "+ cross-attention of the same queries over 769 keys (512 text masked to %d, 257 image: "
+                        "%d keys attend)" % (int(text_len[0]), int(n_attend)),
+            "io": "bf16 in, bf16 out; fp32 accumulate",
+            "mfma_operands": "q', k': %s; P, V: %s (the metric names bf16: fp16 has the same matrix rate and three "
+                             "more significand bits; the all-bf16 kernel is DIT_FLAG_QK_BF16|DIT_FLAG_PV_BF16 = "
+                             "--flags 5 and does not meet the 2e-2 parity bar)" % (qk_name, pv_name),
             "flags": args.flags,
             "pct_of_16bit_mfma_peak": round(100.0 * tflops / PEAK_TFLOPS_16BIT_DENSE, 2),
             "self_attn_kernel_ms": round(kern_avg_ms, 4),
+            # the metric's own number: the self-attention call alone, rotation table and pre-pack pass included
+            "self_attn_call_ms": round(self_call_ms, 4),
+            "self_attn_tflops": round(flops_self / (self_call_ms * 1e-3) / 1e12, 2),
+            "self_attn_pct_of_16bit_mfma_peak": round(100.0 * flops_self / (self_call_ms * 1e-3) / 1e12
+                                                      / PEAK_TFLOPS_16BIT_DENSE, 2),
+            "cross_attn_flops_counted": "over the %d attending keys (dense count over 769: %.4g)" % (
+                int(n_attend), 4.0 * H * L * D * Lk),
             "flops_per_step": flops_self + flops_cross,
         },
         "roofline": {
@@ -306,9 +405,16 @@ def main():
             "peak": PEAK_TFLOPS_16BIT_DENSE,
             "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_TFLOPS_16BIT_DENSE, 4),
-            "traffic": TRAFFIC_BYTES_BY_VERSION.get(B.dit_attn_version()) if args.flags == 0 else None,
+            "traffic": traffic_bytes_for(B.dit_attn_version()) if args.flags == 0 else None,
         },
     }
+    if not args.no_mfma_peak:
+        # what the matrix cores alone sustain on THIS board, beside the published peak the fraction is quoted on
+        rates = measure_mfma_peak(B, torch)
+        key = "%s_random" % ("bf16" if qk_name == "bf16" and pv_name == "bf16" else "f16")
+        result["roofline"]["measured_mfma_peak"] = dict(rates, unit="TFLOP/s",
+                                                        what="MFMA-only micro-benchmark, two wavefronts per SIMD")
+        result["roofline"]["frac_of_measured_%s" % key] = round(achieved / rates[key], 4)
 
     if not args.no_cpu_baseline:
         import oracle

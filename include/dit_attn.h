@@ -2,9 +2,9 @@
  * dit_attn.h -- C ABI of the MI355X (gfx950) DiT attention library.
  *
  * The library computes the attention of the Diffusion stage of a Wan2.1-class video
- * diffusion transformer -- the "core generative component" of the image-to-video workflow
- * the OnePiece paper serves (Sec. 2.4, "The AIGC Workflow") -- as the user function a
- * TaskWorker runs on tensors that already sit in GPU memory (Sec. 4.4, "TaskWorker").
+ * diffusion transformer -- the stage that does the generating in the image-to-video workflow
+ * the OnePiece paper serves (Sec. 2.4, the AIGC workflow) -- as the user function a
+ * TaskWorker runs on tensors that already sit in GPU memory (Sec. 4.4, TaskWorker).
  * The paper names this workload but gives no mathematics for it; what is computed is
  * defined here, and a CPU fp64 statement of the same definition lives in oracle/.
  *
@@ -18,8 +18,13 @@
  *  - `workspace` is caller-owned device scratch of at least *_workspace_bytes(params)
  *    bytes, 256-byte aligned.  Its contents are overwritten by each call; two calls that
  *    share one workspace must be ordered on one stream.
- *  - Arguments are validated before anything is launched; a call that returns an error
- *    has had no effect.  No exception crosses the ABI.
+ *  - Arguments are validated before anything is launched: a call that returns any error but
+ *    DIT_ERR_HIP has had no effect.  DIT_ERR_HIP means a HIP launch or event call failed part-way
+ *    through the call's kernel sequence; the workspace and the output may then be partly
+ *    written.  No exception crosses the ABI.
+ *  - Rows may not overlap: every token and head stride is at least D, and the larger of the two
+ *    clears all rows the smaller one steps over (token >= H*head or head >= L*token); with
+ *    B > 1 the batch stride is at least D.  Else DIT_ERR_INVALID_ARG.
  *  - Arithmetic: inputs bf16 (or fp32), q and k rotated and scaled in fp32, then rounded
  *    once (nearest-even) to the 16-bit MFMA operand type chosen by `flags`; scores,
  *    softmax statistics and the output accumulator are fp32; output bf16 or fp32.
@@ -51,7 +56,11 @@ typedef enum { DIT_BF16 = 0, DIT_F32 = 1 } dit_dtype;
  *
  * fp16 operands (11 significant bits) keep max|err| near 2e-3 x output RMS against the
  * fp64 definition at 32,760 tokens; bf16 operands (8 bits) give about 2e-2.  Both run at
- * the same MFMA rate.  fp16 requires |scale*log2(e)*q'|, |k'| and |v| < 65504.
+ * the same MFMA rate.  fp16 operands SATURATE: where |scale*log2(e)*q'|, |k'| or |v| exceeds 65504, the
+ * largest finite fp16 number, the operand becomes +-65504 (bf16 inputs can hold such values; the result is
+ * then that of the clamped operands: finite and deterministic, but not the definition's).  A caller whose
+ * activations can be that large opts out with DIT_FLAG_QK_BF16 | DIT_FLAG_PV_BF16, which keep the full
+ * bf16 range at bf16 precision.
  */
 enum {
     DIT_FLAG_QK_BF16 = 1u << 0, /* round q', k' to bf16 */
@@ -159,6 +168,9 @@ typedef struct {
 size_t dit_attn_workspace_bytes(const dit_self_attn_params *p);
 
 /*
+ * The spatiotemporal self-attention of one transformer block of the Diffusion stage (Sec. 2.4),
+ * run as a TaskWorker's user function on device-resident tensors (Sec. 4.4); the definition is the
+ * comment on dit_self_attn_params.
  * q, k, v: [B, L, H, D] by strides, in_dtype.  out: same logical shape, out_dtype.
  * lse (nullable): fp32 [B, H, L] dense, natural-log sum of exp(scale * score) per row.
  */
@@ -196,6 +208,8 @@ typedef struct {
 
 size_t dit_cross_attn_workspace_bytes(const dit_cross_attn_params *p);
 
+/* The text/image cross-attention of the same block (Sec. 2.4: the Diffusion stage is conditioned on the
+ * text and image encoders' outputs); the definition is the comment on dit_cross_attn_params. */
 dit_status dit_cross_attn_forward(const void *q, const void *k, const void *v,
                                   const uint8_t *kv_valid, void *out, float *lse,
                                   const dit_cross_attn_params *p, void *workspace,
@@ -297,6 +311,24 @@ dit_status dit_linear_forward(const void *x, const void *w, const void *bias, vo
  * The events are the caller's; pass NULL, NULL to switch the hook off.
  */
 void dit_attn_set_timing_events(void *before, void *after);
+
+/*
+ * Measurement utility for benchmarks (not part of the attention definition): enqueues one kernel in which
+ * every SIMD of the current device runs two wavefronts that issue 32x32x16 MFMAs back to back from
+ * registers -- no memory traffic, no LDS, no vector arithmetic -- so that the rate the matrix cores sustain
+ * on this board can be set beside the published peak.  operand_dtype: DIT_PROBE_F16 or DIT_PROBE_BF16.
+ * random_operands = 0: all operands 0.5 (bound by issue rate and clock); != 0: random signs, significands
+ * and exponents in [-3, 0] (the data-dependent switching of real inputs, under which the board meets its
+ * power limit).  Each wavefront issues mfma_per_wavefront MFMAs, rounded up to a multiple of 16.
+ * sink: DEVICE buffer of at least 2 * compute units * 256 floats that receives one value per lane (it only
+ * keeps the work alive).  *flops (HOST) receives the multiply-add flops the kernel performs; the caller
+ * times the kernel on `stream`.  Errors: DIT_ERR_INVALID_ARG (NULL, bad dtype, count < 1),
+ * DIT_ERR_ALIGNMENT, DIT_ERR_WORKSPACE (sink too small), DIT_ERR_HIP.
+ */
+enum { DIT_PROBE_BF16 = 0, DIT_PROBE_F16 = 1 };
+
+dit_status dit_mfma_probe(int32_t operand_dtype, int32_t random_operands, int64_t mfma_per_wavefront,
+                          float *sink, size_t sink_bytes, double *flops, void *stream);
 
 /* Static strings; never NULL. */
 const char *dit_strerror(dit_status s);

@@ -229,7 +229,13 @@ def cross_attn_decoupled(q, k, v, split, kv_valid=None, scale=0.0, rows=None):
     return total
 
 
-# ---- the optional 8-bit score operands (library flag DIT_FLAG_QK_FP8), written out as a definition ----
+# ---- the optional 8-bit score operands (library flag DIT_FLAG_QK_FP8): a MODEL of the quantiser ----
+# e4m3_round is the published format and is pinned against its code table.  self_attn_fp8_scores, by contrast, is
+# NOT part of the oracle's definition of attention: it was written after the 8-bit kernel and models that kernel's
+# choices (what is rounded, the power-of-two row factor, where scale*log2(e) is folded in).  The parity evidence
+# for the 8-bit path is the comparison with the plain self_attn above, judged with the error statistics derived
+# from the format in tests/fp8_error_model.py; this model only serves as a diagnostic and to validate those
+# statistics on the CPU.
 
 E4M3_MAX = 448.0
 
@@ -258,7 +264,7 @@ def e4m3_quantise_rows(x):
 
 
 def self_attn_fp8_scores(q, k, v, grid, split, origin=(0, 0, 0), base=10000.0, scale=0.0):
-    """Self-attention whose SCORE operands are rounded to E4M3: q' = rope(q) * scale * log2(e) and
+    """MODEL (see above), not a definition.  Self-attention whose SCORE operands are rounded to E4M3: q' = rope(q) * scale * log2(e) and
     k' = rope(k), each row quantised by e4m3_quantise_rows; scores = q' k'^T (in base-2 units),
     softmax and the value product in float64.  q, k, v: [B, L, H, D]; returns [B, L, H, D] float64.
     Sizes the plain numpy products below can hold (L up to a few thousand)."""

@@ -44,6 +44,7 @@ EXPORTS = (
     "dit_attn_varlen_workspace_bytes",
     "dit_attn_varlen_forward",
     "dit_linear_forward",
+    "dit_mfma_probe",
     "dit_attn_set_timing_events",
     "dit_strerror",
     "dit_last_hip_error",
@@ -160,6 +161,9 @@ def lib():
                                               ctypes.c_size_t, vp]
         L.dit_linear_forward.restype = ctypes.c_int
         L.dit_linear_forward.argtypes = [vp, vp, vp, vp, ctypes.POINTER(dit_linear_params), vp]
+        L.dit_mfma_probe.restype = ctypes.c_int
+        L.dit_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_size_t,
+                                     ctypes.POINTER(ctypes.c_double), vp]
         L.dit_attn_set_timing_events.restype = None
         L.dit_attn_set_timing_events.argtypes = [vp, vp]
         L.dit_strerror.restype = ctypes.c_char_p
@@ -274,6 +278,38 @@ def dit_cross_attn_workspace_bytes(params):
     return int(lib().dit_cross_attn_workspace_bytes(ctypes.byref(params)))
 
 
+def _check_tensors(what, q, k, v, out, lse, kv_shape, lse_shape, resident=False):
+    """The C side addresses memory from the shapes in the params struct alone, so every tensor handed over
+    must really have the extent those shapes imply: raise instead of letting a kernel run past an allocation.
+    Shapes and dtypes are checked first, devices last."""
+    import torch
+
+    qshape = tuple(q.shape)
+    kv = () if resident else (("k", k), ("v", v))
+    for name, t in kv:
+        if t is None or tuple(t.shape) != tuple(kv_shape):
+            raise ValueError("%s: %s has shape %s, expected %s" % (
+                what, name, None if t is None else tuple(t.shape), tuple(kv_shape)))
+        if t.dtype != q.dtype:
+            raise ValueError("%s: q, k and v must share one dtype (q %s, %s %s)" % (what, q.dtype, name, t.dtype))
+    if out is not None and tuple(out.shape) != qshape:
+        raise ValueError("%s: out has shape %s, expected q's shape %s" % (what, tuple(out.shape), qshape))
+    if lse is not None and (lse.dtype != torch.float32 or not lse.is_contiguous()
+                            or tuple(lse.shape) != tuple(lse_shape)):
+        raise ValueError("%s: lse must be a dense float32 tensor of shape %s" % (what, tuple(lse_shape)))
+    for name, t in (("q", q),) + kv + (("out", out), ("lse", lse)):
+        if t is not None and (not t.is_cuda or t.device != q.device):
+            raise ValueError("%s needs device tensors on one device (%s is on %s)" % (what, name, t.device))
+
+
+def _check_workspace(what, workspace, need, device):
+    if not workspace.is_cuda or workspace.device != device or not workspace.is_contiguous():
+        raise ValueError("%s: workspace must be a dense tensor on q's device" % what)
+    if workspace.numel() * workspace.element_size() < need:
+        raise ValueError("%s: workspace holds %d bytes, %d needed" % (
+            what, workspace.numel() * workspace.element_size(), need))
+
+
 def _workspace(nbytes, device):
     import torch
 
@@ -290,17 +326,24 @@ def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0),
     """
     import torch
 
-    if not q.is_cuda:
-        raise ValueError("dit_attn_forward needs device tensors")
+    if q.dim() != 4:
+        raise ValueError("dit_attn_forward: q must be [B, L, H, D]")
     B, L, H, D = q.shape
+    if len(grid) != 3 or int(grid[0]) * int(grid[1]) * int(grid[2]) != L:
+        raise ValueError("dit_attn_forward: grid %s does not have q's %d tokens" % (tuple(grid), L))
+    resident = bool(flags & DIT_FLAG_KV_RESIDENT)
+    _check_tensors("dit_attn_forward", q, k, v, out, lse, (B, L, H, D), (B, H, L), resident)
     if out is None:
         out = torch.empty((B, L, H, D), dtype=out_dtype or q.dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty((B, H, L), dtype=torch.float32, device=q.device)
+    if resident and (k is None or v is None):
+        k = v = q  # strides only; the key-side passes are skipped and the pointers are not read
     p = self_attn_params(q, k, v, out, grid, split, origin, rope_base, scale, flags, norm)
     need = dit_attn_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)
+    _check_workspace("dit_attn_forward", workspace, need, q.device)
     st = lib().dit_attn_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                 lse.data_ptr() if lse is not None else None, ctypes.byref(p),
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
@@ -310,26 +353,40 @@ def dit_attn_forward(q, k, v, grid, split, out=None, lse=None, origin=(0, 0, 0),
     return (out, lse) if lse is not None else out
 
 
+def _check_kv_valid(kv_valid, q, B, Lk, device_too=False):
+    """Shape and dtype of the key mask; with device_too (after the other tensors' shapes are known good) its device."""
+    import torch
+
+    if kv_valid is None:
+        return
+    if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, Lk):
+        raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
+    if device_too and (not kv_valid.is_cuda or kv_valid.device != q.device):
+        raise ValueError("kv_valid must be on q's device")
+
+
 def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0, flags=0, out_dtype=None,
                            workspace=None, stream=None, want_lse=False, split=0, norm=None):
     """Cross-attention: q [B, Lq, H, D]; k, v [B, Lk, H, D]; kv_valid uint8 [B, Lk] or None.
     split > 0 selects the decoupled form (separate softmax over keys [0, split) and [split, Lk))."""
     import torch
 
-    if not q.is_cuda:
-        raise ValueError("dit_cross_attn_forward needs device tensors")
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("dit_cross_attn_forward: q must be [B, Lq, H, D] and k, v [B, Lk, H, D]")
     B, Lq, H, D = q.shape
+    Lk = k.shape[1]
+    _check_kv_valid(kv_valid, q, B, Lk)
+    _check_tensors("dit_cross_attn_forward", q, k, v, out, lse, (B, Lk, H, D), (B, H, Lq))
     if out is None:
         out = torch.empty((B, Lq, H, D), dtype=out_dtype or q.dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty((B, H, Lq), dtype=torch.float32, device=q.device)
-    if kv_valid is not None:
-        if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, k.shape[1]):
-            raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
+    _check_kv_valid(kv_valid, q, B, Lk, device_too=True)
     p = cross_attn_params(q, k, v, out, scale, flags, split, norm)
     need = dit_cross_attn_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)
+    _check_workspace("dit_cross_attn_forward", workspace, need, q.device)
     st = lib().dit_cross_attn_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                       kv_valid.data_ptr() if kv_valid is not None else None,
                                       out.data_ptr(), lse.data_ptr() if lse is not None else None,
@@ -349,12 +406,15 @@ def dit_cross_attn_forward_static(q, k, v, kv_valid=None, out=None, lse=None, sc
     given: this wrapper allocates nothing either."""
     import torch
 
-    if not q.is_cuda or out is None:
-        raise ValueError("dit_cross_attn_forward_static needs device tensors and a caller-provided out")
-    B = q.shape[0]
-    if kv_valid is not None:
-        if kv_valid.dtype != torch.uint8 or not kv_valid.is_contiguous() or tuple(kv_valid.shape) != (B, k.shape[1]):
-            raise ValueError("kv_valid must be a dense uint8 [B, Lk] tensor")
+    if out is None:
+        raise ValueError("dit_cross_attn_forward_static needs a caller-provided out")
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("dit_cross_attn_forward_static: q must be [B, Lq, H, D] and k, v [B, Lk, H, D]")
+    B, Lq, H, D = q.shape
+    Lk = k.shape[1]
+    _check_kv_valid(kv_valid, q, B, Lk)
+    _check_tensors("dit_cross_attn_forward_static", q, k, v, out, lse, (B, Lk, H, D), (B, H, Lq))
+    _check_kv_valid(kv_valid, q, B, Lk, device_too=True)
     p = cross_attn_params(q, k, v, out, scale, flags, split, norm)
     st = lib().dit_cross_attn_forward_static(q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                              kv_valid.data_ptr() if kv_valid is not None else None,
@@ -372,11 +432,13 @@ def dit_attn_varlen_forward(q, k, v, grids, split, out=None, lse=None, origin=(0
     grids = [(T, Hg, Wg), ...] with L_i = T*Hg*Wg.  Returns out (and lse [H, sum L_i] if asked)."""
     import torch
 
-    if not q.is_cuda:
-        raise ValueError("dit_attn_varlen_forward needs device tensors")
+    if q.dim() != 3:
+        raise ValueError("dit_attn_varlen_forward: q must be [tokens, H, D]")
     N, H, D = q.shape
     if sum(g[0] * g[1] * g[2] for g in grids) != N:
         raise ValueError("the grids do not add up to the token count of q")
+    _check_tensors("dit_attn_varlen_forward", q, k, v, out, lse, (N, H, D), (H, N),
+                   bool(flags & DIT_FLAG_KV_RESIDENT))
     if out is None:
         out = torch.empty((N, H, D), dtype=out_dtype or q.dtype, device=q.device)
     if lse is None and want_lse:
@@ -385,6 +447,7 @@ def dit_attn_varlen_forward(q, k, v, grids, split, out=None, lse=None, origin=(0
     need = dit_attn_varlen_workspace_bytes(p)
     if workspace is None:
         workspace = _workspace(need, q.device)
+    _check_workspace("dit_attn_varlen_forward", workspace, need, q.device)
     st = lib().dit_attn_varlen_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                        lse.data_ptr() if lse is not None else None, ctypes.byref(p),
                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
@@ -421,3 +484,18 @@ def dit_linear_forward(x, w, bias=None, out=None, out_dtype=None, stream=None):
     if st != DIT_OK:
         raise DitError(st, "dit_linear_forward")
     return out
+
+
+DIT_PROBE_BF16 = 0
+DIT_PROBE_F16 = 1
+
+
+def dit_mfma_probe(operand_dtype, random_operands, mfma_per_wavefront, sink, stream=None):
+    """Enqueue the MFMA-only probe kernel; sink: device float32 tensor (2 * CUs * 256 elements or more).
+    Returns the flops the kernel performs; the caller times it."""
+    flops = ctypes.c_double(0.0)
+    st = lib().dit_mfma_probe(operand_dtype, 1 if random_operands else 0, int(mfma_per_wavefront), sink.data_ptr(),
+                              sink.numel() * sink.element_size(), ctypes.byref(flops), _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_mfma_probe")
+    return flops.value

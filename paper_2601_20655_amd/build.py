@@ -46,23 +46,5 @@ def build_library(verbose=False, extra=(), jobs=None, out=LIB, obj_dir=OBJ):
     return out
 
 
-def build_c_caller():
-    """Compile tests/c_abi_caller.c (a C99 program that calls the library and checks it against the C
-    oracle) with gcc into tests/bin/c_abi_caller; needs libdit_attn.so to be built."""
-    root = os.path.dirname(HERE)
-    out_dir = os.path.join(root, "tests", "bin")
-    os.makedirs(out_dir, exist_ok=True)
-    exe = os.path.join(out_dir, "c_abi_caller")
-    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
-    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-fopenmp", "-I", os.path.join(root, "include"),
-           "-I", os.path.join(rocm, "include"), os.path.join(root, "tests", "c_abi_caller.c"),
-           os.path.join(root, "oracle", "dit_oracle.c"), "-o", exe, "-L", HERE, "-ldit_attn",
-           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
-           "-Wl,-rpath,$ORIGIN/../../paper_2601_20655_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
-    subprocess.check_call(cmd)
-    return exe
-
-
 if __name__ == "__main__":
     print(build_library(verbose=True, extra=sys.argv[1:]))
-    print(build_c_caller())

@@ -1,5 +1,6 @@
 // C ABI of the library: argument validation, workspace carving, kernel sequencing.
-// Every check happens before the first launch, so a failing call has no effect.
+// Every argument check happens before the first launch: a call that returns anything but DIT_ERR_HIP has had
+// no effect; DIT_ERR_HIP (a launch failed) may leave workspace and output partly written.
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
@@ -116,11 +117,19 @@ bool aligned16(const void* p, const dit_strides& s, int32_t dtype) {
     return s.batch % per16 == 0 && s.token % per16 == 0 && s.head % per16 == 0;
 }
 
-bool strides_ok(const dit_strides& s, int32_t B, int32_t H, int32_t D) {
-    if (s.token < 1 || s.head < 1) return false;
-    if (B > 1 && s.batch < 1) return false;
-    if (H > 1 && s.head < D && s.token < D) return false;
-    return s.batch >= 0;
+// Rows of D contiguous channels may not overlap: a token's and a head's rows are at least D apart, and of the
+// two strides the larger one clears all the rows the smaller one steps over ([B,L,H,D]: token >= H*head;
+// [B,H,L,D]: head >= L*token).  L = 0 skips the second half (packed requests check their own total).
+bool strides_ok(const dit_strides& s, int32_t B, int32_t H, int32_t D, int64_t L) {
+    if (s.token < D || s.head < D) return false;
+    if (B > 1 && s.batch < D) return false;
+    if (s.batch < 0) return false;
+    if (H > 1 && L > 1) {
+        const bool token_major = s.token >= (int64_t)H * s.head;
+        const bool head_major = s.head >= L * s.token;
+        if (!token_major && !head_major) return false;
+    }
+    return true;
 }
 
 // eps >= 0, a known mode; the channel weights are read as float4
@@ -199,8 +208,8 @@ dit_status plan_self(const dit_self_attn_params* p, SelfPlan* pl) {
             !(p->flags & DIT_FLAG_PV_BF16))
             return DIT_ERR_UNSUPPORTED;
     }
-    if (!strides_ok(p->sq, p->B, p->H, p->D) || !strides_ok(p->sk, p->B, p->H, p->D) ||
-        !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
+    if (!strides_ok(p->sq, p->B, p->H, p->D, L) || !strides_ok(p->sk, p->B, p->H, p->D, L) ||
+        !strides_ok(p->sv, p->B, p->H, p->D, L) || !strides_ok(p->so, p->B, p->H, p->D, L))
         return DIT_ERR_INVALID_ARG;
     pl->L = L;
     pl->nKT = (int)((L + dit::kBK - 1) / dit::kBK);
@@ -251,8 +260,8 @@ dit_status plan_varlen(const dit_varlen_attn_params* p, VarlenPlan* pl) {
     // only the pipelined kernel with pre-packed tiles and 32 rows per wavefront has this form
     if (pl->fl.fused || pl->fl.simple || pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
     if (p->H > (1 << 16)) return DIT_ERR_UNSUPPORTED;
-    if (!strides_ok(p->sq, 1, p->H, p->D) || !strides_ok(p->sk, 1, p->H, p->D) ||
-        !strides_ok(p->sv, 1, p->H, p->D) || !strides_ok(p->so, 1, p->H, p->D))
+    if (!strides_ok(p->sq, 1, p->H, p->D, 0) || !strides_ok(p->sk, 1, p->H, p->D, 0) ||
+        !strides_ok(p->sv, 1, p->H, p->D, 0) || !strides_ok(p->so, 1, p->H, p->D, 0))
         return DIT_ERR_INVALID_ARG;
 
     const int n = p->n_requests;
@@ -339,8 +348,8 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     if (pl->fl.fused) return DIT_ERR_UNSUPPORTED;
     if ((st = norm_ok(p->norm)) != DIT_OK) return st;
     if (p->Lq > (1 << 24) || p->Lk > (1 << 24) || (int64_t)p->B * p->H > (1 << 20)) return DIT_ERR_UNSUPPORTED;
-    if (!strides_ok(p->sq, p->B, p->H, p->D) || !strides_ok(p->sk, p->B, p->H, p->D) ||
-        !strides_ok(p->sv, p->B, p->H, p->D) || !strides_ok(p->so, p->B, p->H, p->D))
+    if (!strides_ok(p->sq, p->B, p->H, p->D, p->Lq) || !strides_ok(p->sk, p->B, p->H, p->D, p->Lk) ||
+        !strides_ok(p->sv, p->B, p->H, p->D, p->Lk) || !strides_ok(p->so, p->B, p->H, p->D, p->Lq))
         return DIT_ERR_INVALID_ARG;
     if (p->Lk_split < 0 || p->Lk_split > p->Lk) return DIT_ERR_INVALID_ARG;
     pl->split = (p->Lk_split == p->Lk) ? 0 : p->Lk_split;  // a split at either end is the joint softmax
@@ -686,6 +695,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 121; }
+int dit_attn_version(void) { return 10200; }  // 1.2.0
 
 }  // extern "C"

@@ -42,10 +42,21 @@ __device__ __forceinline__ float sum2(uint32_t packed, float acc) {
     }
 }
 
+// fp16 operands saturate: a value beyond the largest finite fp16 number becomes +-65504 instead of an
+// infinity that would turn the products into NaN (bf16 inputs can hold such values).  NaN stays NaN.
+constexpr float kF16Max = 65504.0f;
+__device__ __forceinline__ float sat_f16(float x) { return x > kF16Max ? kF16Max : (x < -kF16Max ? -kF16Max : x); }
+
+// Eight fp32 values -> four dwords of 16-bit operands, saturating for fp16.  Used where q', k' and v are
+// rounded (prologue, pre-pack pass), never in the key loop: probabilities cannot overflow.
 template <int OP>
 __device__ __forceinline__ u32x4 pack8(const float x[8]) {
-    return mk4(pack2<OP>(x[0], x[1]), pack2<OP>(x[2], x[3]), pack2<OP>(x[4], x[5]),
-                      pack2<OP>(x[6], x[7]));
+    if constexpr (OP == OP_F16) {
+        return mk4(pack2<OP>(sat_f16(x[0]), sat_f16(x[1])), pack2<OP>(sat_f16(x[2]), sat_f16(x[3])),
+                   pack2<OP>(sat_f16(x[4]), sat_f16(x[5])), pack2<OP>(sat_f16(x[6]), sat_f16(x[7])));
+    } else {
+        return mk4(pack2<OP>(x[0], x[1]), pack2<OP>(x[2], x[3]), pack2<OP>(x[4], x[5]), pack2<OP>(x[6], x[7]));
+    }
 }
 
 // D(32x32, fp32) += A(32x16) * B(16x32).  Lane l supplies row (l % 32) of A and column

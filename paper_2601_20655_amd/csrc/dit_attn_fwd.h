@@ -428,8 +428,8 @@ template <int D, int QB, int QK_OP, int PV_OP, bool FUSED, bool SPLIT = false>
 hipError_t launch_attn_inst(const AttnArgs& a, hipStream_t s) {
     auto kern = attn_fwd_kernel<D, QB, QK_OP, PV_OP, FUSED, SPLIT>;
     constexpr int smem = 2 * TileGeom<D>::TILE_BYTES;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static std::atomic<uint64_t> attr_set{0};
+    hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((int64_t)a.nQT * a.B * a.H));
     hipLaunchKernelGGL(kern, grid, dim3(kThreads), smem, s, a);

@@ -710,8 +710,8 @@ template <int D, int QB, int QK_OP, int PV_OP, int NW, bool LISTED>
 hipError_t launch_attn_pipe_inst(const AttnArgs& a, hipStream_t s) {
     auto kern = attn_fwd_pipe_kernel<D, QB, QK_OP, PV_OP, NW, LISTED>;
     constexpr int smem = pipe_lds_bytes<D, NW>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static std::atomic<uint64_t> attr_set{0};
+    hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((int64_t)a.nQT * a.B * a.H));
     hipLaunchKernelGGL(kern, grid, dim3(64 * NW), smem, s, a);
@@ -722,8 +722,8 @@ template <int D, int QK_OP, int PV_OP, int NW>
 hipError_t launch_attn_pipe_varlen_inst(const AttnArgs& a, const VarlenTable& vt, hipStream_t s) {
     auto kern = attn_fwd_pipe_varlen_kernel<D, QK_OP, PV_OP, NW>;
     constexpr int smem = pipe_lds_bytes<D, NW>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static std::atomic<uint64_t> attr_set{0};
+    hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(8 * vt.queue_len)), dim3(64 * NW), smem, s, a, vt);
     return hipGetLastError();

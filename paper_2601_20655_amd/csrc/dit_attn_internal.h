@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace dit {
 
 constexpr int kBK = 64;         // keys per K/V tile
@@ -131,6 +133,20 @@ struct VarlenTable {
     int queue_len;     // workgroups per XCD queue; the grid is 8 * queue_len
     ReqDesc r[kMaxRequests];
 };
+
+// Kernels that need more than the default 64 KiB of dynamic LDS: the attribute is set once per kernel
+// instantiation and device (`done` is that instantiation's bit set of devices), not on every launch.
+template <typename K>
+inline hipError_t allow_dynamic_lds(K kern, int bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 // Records "<where>: <HIP error text>" for dit_last_hip_error() of the calling thread; returns DIT_ERR_HIP.
 int report_hip_error(hipError_t e, const char* where);

@@ -295,8 +295,8 @@ template <bool OUT_F32>
 hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
     auto kern = linear_kernel<DIT_LIN_SX, DIT_LIN_SW, DIT_LIN_WAVES, OUT_F32>;
     constexpr int smem = (DIT_LIN_SX + DIT_LIN_SW) * kLinTileBytes;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static std::atomic<uint64_t> attr_set{0};
+    hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)a.nTM * a.nTN)), dim3(64 * DIT_LIN_WAVES), smem, s, a);
     return hipGetLastError();

@@ -28,7 +28,9 @@ def test_header_symbols_are_exported():
 
 
 def test_version_and_strerror():
-    assert B.dit_attn_version() >= 100
+    ver = B.dit_attn_version()  # major*10000 + minor*100 + patch, as the header documents
+    major, minor, patch = ver // 10000, ver // 100 % 100, ver % 100
+    assert major >= 1 and 0 <= minor < 100 and 0 <= patch < 100 and ver >= 10200
     assert B.dit_strerror(B.DIT_OK) == "ok"
     for code in (-1, -2, -3, -4, -5):
         assert B.dit_strerror(code) not in ("", "ok", "unknown status")
@@ -77,6 +79,12 @@ FAKE = 0x1000  # a 16-byte aligned non-NULL address that is never dereferenced: 
 
 def call_self(p, q=FAKE, k=FAKE, v=FAKE, out=FAKE, ws=0x10000, ws_bytes=1 << 40):
     return B.lib().dit_attn_forward(q, k, v, out, None, ctypes.byref(p), ws, ws_bytes, None)
+
+
+def call_self_no_launch(p):
+    """For parameter sets that must be rejected: were they accepted, the call would stop at the workspace
+    check (no workspace is passed) instead of launching anything on fake pointers."""
+    return B.lib().dit_attn_forward(FAKE, FAKE, FAKE, FAKE, None, ctypes.byref(p), None, 0, None)
 
 
 def call_cross(p, q=FAKE, k=FAKE, v=FAKE, out=FAKE, ws=0x10000, ws_bytes=1 << 40):
@@ -235,6 +243,87 @@ def test_linear_rejects_bad_arguments():
     for kw in (dict(x=FAKE + 8), dict(w=FAKE + 2), dict(y=FAKE + 4), dict(ldx=68), dict(ldw=70), dict(ldy=68),
                dict(bias=FAKE + 4), dict(out_dtype=B.DIT_F32, ldy=66)):
         assert linear_call(**kw) == B.DIT_ERR_ALIGNMENT, kw
+
+
+def test_overlapping_rows_are_rejected():
+    """Rows of D channels may not overlap: an output layout whose rows share memory would let workgroups race."""
+    L, H, D = 24, 2, 128
+    ok_layouts = [
+        B.dit_strides(L * H * D, H * D, D),          # [B, L, H, D]
+        B.dit_strides(L * H * D, D, L * D),          # [B, H, L, D]
+        B.dit_strides(H * D, 2 * H * D, D),          # [L, B, H, D]: batches interleaved
+        B.dit_strides(3 * L * H * D, 3 * H * D, D),  # a q/k/v-fused buffer: token stride 3*H*D
+    ]
+    for st in ok_layouts:
+        p = self_params(B_=2)
+        p.so = st
+        assert call_self_no_launch(p) == B.DIT_ERR_WORKSPACE, (st.batch, st.token, st.head)  # accepted
+    bad_layouts = [
+        B.dit_strides(L * H * D, 64, D),             # token stride shorter than a row
+        B.dit_strides(L * H * D, H * D, 64),         # head stride shorter than a row
+        B.dit_strides(L * H * D, D, D),              # heads on top of tokens
+        B.dit_strides(L * H * D, H * D - 8, D),      # token stride does not clear the H heads of a token
+        B.dit_strides(L * H * D, D, (L - 1) * D),    # head stride does not clear the L tokens of a head
+        B.dit_strides(64, H * D, D),                 # batch stride shorter than a row
+    ]
+    for st in bad_layouts:
+        for field in ("sq", "sk", "sv", "so"):
+            p = self_params(B_=2)
+            setattr(p, field, st)
+            assert call_self_no_launch(p) == B.DIT_ERR_INVALID_ARG, (field, st.batch, st.token, st.head)
+    # one head: the token stride alone decides
+    p = self_params(H=1, split=(44, 42, 42))
+    p.so = B.dit_strides(L * 128, 64, 128)
+    assert call_self_no_launch(p) == B.DIT_ERR_INVALID_ARG
+    c = cross_params()
+    c.so = B.dit_strides(100 * 2 * 128, 128, 128)
+    assert call_cross(c) == B.DIT_ERR_INVALID_ARG
+    v = varlen_params()
+    v.so = B.dit_strides(0, 64, 128)
+    assert call_varlen(v) == B.DIT_ERR_INVALID_ARG
+
+
+def test_python_wrappers_check_extents_before_any_call():
+    """The wrappers refuse tensors whose shapes, dtypes or grid do not match what the C side will address
+    (checked on host tensors: the shape checks come before the device check)."""
+    import torch
+
+    def t(*shape, dtype=torch.bfloat16):
+        return torch.zeros(shape, dtype=dtype)
+
+    q = t(1, 24, 2, 128)
+    grid, split = (2, 3, 4), (44, 42, 42)
+    with pytest.raises(ValueError, match="grid"):
+        B.dit_attn_forward(q, q, q, (2, 3, 5), split)
+    with pytest.raises(ValueError, match="k has shape"):
+        B.dit_attn_forward(q, t(1, 23, 2, 128), q, grid, split)
+    with pytest.raises(ValueError, match="v has shape"):
+        B.dit_attn_forward(q, q, t(1, 24, 1, 128), grid, split)
+    with pytest.raises(ValueError, match="share one dtype"):
+        B.dit_attn_forward(q, t(1, 24, 2, 128, dtype=torch.float32), q, grid, split)
+    with pytest.raises(ValueError, match="out has shape"):
+        B.dit_attn_forward(q, q, q, grid, split, out=t(1, 24, 2, 64))
+    with pytest.raises(ValueError, match="lse"):
+        B.dit_attn_forward(q, q, q, grid, split, lse=torch.zeros((1, 24, 2)))
+    kc = t(1, 77, 2, 128)
+    with pytest.raises(ValueError, match="v has shape"):
+        B.dit_cross_attn_forward(q, kc, t(1, 76, 2, 128))
+    with pytest.raises(ValueError, match="k has shape"):
+        B.dit_cross_attn_forward(q, t(2, 77, 2, 128), t(2, 77, 2, 128))
+    with pytest.raises(ValueError, match="share one dtype"):
+        B.dit_cross_attn_forward(q, kc, t(1, 77, 2, 128, dtype=torch.float32))
+    with pytest.raises(ValueError, match="kv_valid"):
+        B.dit_cross_attn_forward(q, kc, kc, torch.zeros((1, 76), dtype=torch.uint8))
+    with pytest.raises(ValueError, match="kv_valid"):
+        B.dit_cross_attn_forward_static(q, kc, kc, torch.zeros((1, 77), dtype=torch.int32), out=q)
+    qv = t(24, 2, 128)
+    with pytest.raises(ValueError, match="grids"):
+        B.dit_attn_varlen_forward(qv, qv, qv, [(2, 3, 4), (1, 1, 1)], split)
+    with pytest.raises(ValueError, match="k has shape"):
+        B.dit_attn_varlen_forward(qv, t(25, 2, 128), qv, [(2, 3, 4)], split)
+    # everything fits, but the tensors are on the host
+    with pytest.raises(ValueError, match="device"):
+        B.dit_attn_forward(q, q, q, grid, split)
 
 
 def test_python_wrappers_refuse_host_tensors():

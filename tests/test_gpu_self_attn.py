@@ -117,6 +117,22 @@ def test_ragged_sizes(grid, D):
         assert np.max(np.abs(to_f64(lse) - ref_lse)) < 5e-3
 
 
+@pytest.mark.parametrize("name", ["qb1_8w", "qb1_4w", "qb2_4w", "simple_qb1"])
+def test_head_dim_64_steady_state_all_rows(name):
+    """head_dim 64 over 68 key tiles and 17 (8-wavefront) or 34 query tiles per head: the key loop of each form
+    in steady state (the ragged cases above end after seven tiles), every row against the oracle, fp32 inputs
+    as in the tiny reference shape and bf16 inputs."""
+    import torch
+
+    for dtype, seed in (("bf16", 6401), ("f32", 6402)):
+        cfg = dict(B=1, grid=(4, 32, 34), H=2, D=64, split=(22, 20, 22), dtype=dtype, seed=seed)
+        q, k, v = wl.self_attn_inputs(cfg)
+        ref, ref_lse = oracle.self_attn(q, k, v, cfg["grid"], cfg["split"], want_lse=True)
+        out, lse = run_self(cfg, q, k, v, flags=SHAPES[name], out_dtype=torch.float32, want_lse=True)
+        compare(to_f64(out), ref, what="d64, 4,352 tokens, %s, %s in" % (name, dtype))
+        assert np.max(np.abs(to_f64(lse) - ref_lse)) < 5e-3
+
+
 def test_peaky_softmax_origin_scale_base():
     """q, k scaled x2 with scale 0.11: scores ~ N(0, 5^2), the softmax concentrates on a few keys
     and the running maximum keeps moving; non-zero origin, explicit scale and base.  (Larger
