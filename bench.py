@@ -49,25 +49,30 @@ def traffic_bytes_for(version):
     return found.get("traffic_bytes_per_launch")
 
 
-def measure_mfma_peak(B, torch, launches=3, mfma_per_wavefront=1_200_000):
+def measure_mfma_peak(B, torch, launches=3, mfma_per_wavefront=1_200_000, sweep=False):
     """Sustained rate of the matrix cores alone on this board (dit_mfma_probe: two wavefronts per SIMD issuing
-    32x32x16 MFMAs back to back from registers), TFLOP/s, for fp16 and bf16 operands, constant and random.
-    Each figure is the mean of `launches` launches of about 50 ms after one warm-up launch."""
+    32x32x16 MFMAs back to back from registers), TFLOP/s, for fp16 and bf16 operands, constant and random
+    (random = every significand bit of the format in use).  With sweep, also fp16 operands that carry fewer
+    significant bits.  Each figure is the mean of `launches` launches of about 50 ms after one warm-up launch."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     sink = torch.empty(2 * cus * 256, dtype=torch.float32, device="cuda")
+    cases = [("f16_constant", B.DIT_PROBE_F16, 0, 0), ("f16_random", B.DIT_PROBE_F16, 11, 11),
+             ("bf16_constant", B.DIT_PROBE_BF16, 0, 0), ("bf16_random", B.DIT_PROBE_BF16, 8, 8)]
+    if sweep:
+        cases += [("f16_%d_%d_bits" % (a, b), B.DIT_PROBE_F16, a, b)
+                  for a, b in ((10, 10), (9, 9), (8, 8), (6, 6), (4, 4), (11, 8), (8, 11), (11, 0), (0, 11))]
     out = {}
-    for dt, dname in ((B.DIT_PROBE_F16, "f16"), (B.DIT_PROBE_BF16, "bf16")):
-        for rnd, rname in ((0, "constant"), (1, "random")):
-            B.dit_mfma_probe(dt, rnd, mfma_per_wavefront, sink)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            flops = 0.0
-            for _ in range(launches):
-                flops += B.dit_mfma_probe(dt, rnd, mfma_per_wavefront, sink)
-            e1.record()
-            torch.cuda.synchronize()
-            out["%s_%s" % (dname, rname)] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    for name, dt, ba, bb in cases:
+        B.dit_mfma_probe(dt, ba, bb, mfma_per_wavefront, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = 0.0
+        for _ in range(launches):
+            flops += B.dit_mfma_probe(dt, ba, bb, mfma_per_wavefront, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
     return out
 
 
@@ -81,13 +86,13 @@ def mfma_peak_workload(args):
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     t0 = time.perf_counter()
-    rates = measure_mfma_peak(B, torch, launches=max(args.steps, 1))
+    rates = measure_mfma_peak(B, torch, launches=max(args.steps, 1), sweep=True)
     dt = time.perf_counter() - t0
     v = rates["f16_random"]
     print(json.dumps({
         "metric": "MFMA-only sustained TFLOP/s (32x32x16, two wavefronts per SIMD, random fp16 operands)",
         "value": v, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": 1,
-        "ms_per_step": round(dt * 1e3 / (4 * max(args.steps, 1)), 3), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(dt * 1e3 / (len(rates) * max(args.steps, 1)), 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": "mfma_peak: every SIMD issues MFMAs from registers, nothing else", "rates_tflops": rates},
         "roofline": {"kernel": "mfma_probe_kernel", "bound": "mfma", "achieved": v, "peak": PEAK_TFLOPS_16BIT_DENSE,
@@ -181,7 +186,7 @@ def other_workload(args):
         L = q.shape[1]
         flops = 4.0 * cfg["B"] * H * L * L * D
         what = "self-attention, grid %dx%dx%d = %d tokens, %d heads, d%d" % (cfg["grid"] + (L, H, D))
-        kernel = "attn_fwd_pipe_kernel"
+        kernel = "attn_fwd_pipe16_kernel"
 
         def call():
             B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
@@ -195,7 +200,7 @@ def other_workload(args):
                          dtype=torch.uint8, device="cuda")
         flops = sum(4.0 * H * D * float(t * h * w) ** 2 for t, h, w in grids)
         what = "self-attention over %d packed requests (%d tokens), %d heads, d%d" % (len(grids), q.shape[0], H, D)
-        kernel = "attn_fwd_pipe_varlen_kernel"
+        kernel = "attn_fwd_pipe16_varlen_kernel"
 
         def call():
             B.dit_attn_varlen_forward(q, k, v, grids, cfg["split"], out=out, flags=args.flags, workspace=ws,
@@ -399,7 +404,7 @@ def main():
             "flops_per_step": flops_self + flops_cross,
         },
         "roofline": {
-            "kernel": "attn_fwd_pipe_kernel (self-attention, 32,760 x 32,760 x 40 heads)",
+            "kernel": "attn_fwd_pipe16_kernel (self-attention, 32,760 x 32,760 x 40 heads)",
             "bound": "mfma",
             "achieved": round(achieved, 2),
             "peak": PEAK_TFLOPS_16BIT_DENSE,

@@ -95,13 +95,15 @@ enum {
     DIT_FLAG_PIPELINED_SCHEDULE = 1u << 10,
     /* The workspace still holds the rotated, pre-packed K'/V^T tile images (and the rotation table,
      * the key tile lists and masks) that an earlier forward call of the SAME entry point wrote for the
-     * same k, v, kv_valid, shapes, grid(s), origin, rope_base, norm (mode, eps, k_gamma), key split and
-     * operand-type flags; that call must precede this one in stream order.  The key-side passes are
-     * skipped: k, v and kv_valid are not read and may be NULL.  q, scale, q_gamma, the output and the
-     * schedule flags may differ from call to call.  This is the K/V cache of a denoising loop: the
-     * conditioning keys and values of cross-attention are the same at every step, and a caller that
-     * evaluates several query sets against one K, V pays for one pre-pack.  Nothing records what the
-     * workspace holds: the caller vouches for it.  Not with DIT_FLAG_KV_FUSED (DIT_ERR_INVALID_ARG). */
+     * same k, v, kv_valid, shapes, grid(s), origin, rope_base, norm (mode, eps, k_gamma), key split,
+     * operand-type flags and, for self-attention, the flags that choose the matrix-instruction shape the
+     * tiles are laid out for (MFMA_32X32, WIDE_QTILE, SIMPLE_SCHEDULE, QK_FP8); that call must precede
+     * this one in stream order.  The key-side passes are skipped: k, v and kv_valid are not read and may
+     * be NULL.  q, scale, q_gamma, the output and the workgroup-size flags may differ from call to call.
+     * This is the K/V cache of a denoising loop: the conditioning keys and values of cross-attention are
+     * the same at every step, and a caller that evaluates several query sets against one K, V pays for
+     * one pre-pack.  Nothing records what the workspace holds: the caller vouches for it.  Not with
+     * DIT_FLAG_KV_FUSED (DIT_ERR_INVALID_ARG). */
     DIT_FLAG_KV_RESIDENT = 1u << 11,
     /* Score product on 8-bit operands: q' and k' are rounded to e4m3 (4 significant bits), each row
      * with its own power-of-two factor that the matrix instruction applies; P and V keep their 16-bit
@@ -112,7 +114,15 @@ enum {
      * pipelined 32-rows-per-wavefront kernel, dit_attn_varlen_forward); excludes QK_BF16 / QK_F16
      * (DIT_ERR_INVALID_ARG) and KV_FUSED, SIMPLE_SCHEDULE, WIDE_QTILE, cross-attention
      * (DIT_ERR_UNSUPPORTED).  Never selected by default. */
-    DIT_FLAG_QK_FP8 = 1u << 12
+    DIT_FLAG_QK_FP8 = 1u << 12,
+    /* Self-attention entry points (dit_attn_forward with the pipelined 32-rows-per-wavefront kernel,
+     * dit_attn_varlen_forward) run on 16x16x32 matrix instructions by default: under the board's power limit
+     * they deliver more flops per joule than 32x32x16 ones (measured: the kernel is 8 % faster on N(0,1) inputs).
+     * This flag selects the 32x32x16 form of the same pipeline instead; same results up to rounding order.  It
+     * decides the key order inside the pre-packed V^T tiles, so it belongs to the flags that may not change
+     * between the calls that share tiles under DIT_FLAG_KV_RESIDENT.  No effect on cross-attention and on the
+     * forms that only exist on 32x32x16 instructions (QK_FP8, WIDE_QTILE, SIMPLE_SCHEDULE, KV_FUSED). */
+    DIT_FLAG_MFMA_32X32 = 1u << 13
 };
 
 typedef struct {
@@ -317,17 +327,20 @@ void dit_attn_set_timing_events(void *before, void *after);
  * every SIMD of the current device runs two wavefronts that issue 32x32x16 MFMAs back to back from
  * registers -- no memory traffic, no LDS, no vector arithmetic -- so that the rate the matrix cores sustain
  * on this board can be set beside the published peak.  operand_dtype: DIT_PROBE_F16 or DIT_PROBE_BF16.
- * random_operands = 0: all operands 0.5 (bound by issue rate and clock); != 0: random signs, significands
- * and exponents in [-3, 0] (the data-dependent switching of real inputs, under which the board meets its
- * power limit).  Each wavefront issues mfma_per_wavefront MFMAs, rounded up to a multiple of 16.
+ * bits_a, bits_b: what the A and B operands hold.  0: the constant 0.5 (the rate is then bound by issue and
+ * clock); n > 0: random signs, exponents in [-3, 0] and random significands of n significant bits, leading one
+ * included (11 = all of fp16, 8 = all of bf16; with fewer the low stored bits are zero; larger values are
+ * clamped to the format) -- the data-dependent switching of real inputs, under which the board meets its
+ * power limit, and which grows with the number of bits the data carries.
+ * Each wavefront issues mfma_per_wavefront MFMAs, rounded up to a multiple of 16.
  * sink: DEVICE buffer of at least 2 * compute units * 256 floats that receives one value per lane (it only
  * keeps the work alive).  *flops (HOST) receives the multiply-add flops the kernel performs; the caller
- * times the kernel on `stream`.  Errors: DIT_ERR_INVALID_ARG (NULL, bad dtype, count < 1),
+ * times the kernel on `stream`.  Errors: DIT_ERR_INVALID_ARG (NULL, bad dtype, a negative count),
  * DIT_ERR_ALIGNMENT, DIT_ERR_WORKSPACE (sink too small), DIT_ERR_HIP.
  */
 enum { DIT_PROBE_BF16 = 0, DIT_PROBE_F16 = 1 };
 
-dit_status dit_mfma_probe(int32_t operand_dtype, int32_t random_operands, int64_t mfma_per_wavefront,
+dit_status dit_mfma_probe(int32_t operand_dtype, int32_t bits_a, int32_t bits_b, int64_t mfma_per_wavefront,
                           float *sink, size_t sink_bytes, double *flops, void *stream);
 
 /* Static strings; never NULL. */

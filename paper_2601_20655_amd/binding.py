@@ -34,6 +34,7 @@ DIT_FLAG_SMALL_WORKGROUP = 1 << 9
 DIT_FLAG_PIPELINED_SCHEDULE = 1 << 10
 DIT_FLAG_KV_RESIDENT = 1 << 11
 DIT_FLAG_QK_FP8 = 1 << 12
+DIT_FLAG_MFMA_32X32 = 1 << 13
 
 EXPORTS = (
     "dit_attn_workspace_bytes",
@@ -162,7 +163,7 @@ def lib():
         L.dit_linear_forward.restype = ctypes.c_int
         L.dit_linear_forward.argtypes = [vp, vp, vp, vp, ctypes.POINTER(dit_linear_params), vp]
         L.dit_mfma_probe.restype = ctypes.c_int
-        L.dit_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_size_t,
+        L.dit_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_size_t,
                                      ctypes.POINTER(ctypes.c_double), vp]
         L.dit_attn_set_timing_events.restype = None
         L.dit_attn_set_timing_events.argtypes = [vp, vp]
@@ -490,11 +491,12 @@ DIT_PROBE_BF16 = 0
 DIT_PROBE_F16 = 1
 
 
-def dit_mfma_probe(operand_dtype, random_operands, mfma_per_wavefront, sink, stream=None):
-    """Enqueue the MFMA-only probe kernel; sink: device float32 tensor (2 * CUs * 256 elements or more).
+def dit_mfma_probe(operand_dtype, bits_a, bits_b, mfma_per_wavefront, sink, stream=None):
+    """Enqueue the MFMA-only probe kernel; bits_a / bits_b: 0 = constant operands, n = random operands of n
+    significant bits; sink: device float32 tensor (2 * CUs * 256 elements or more).
     Returns the flops the kernel performs; the caller times it."""
     flops = ctypes.c_double(0.0)
-    st = lib().dit_mfma_probe(operand_dtype, 1 if random_operands else 0, int(mfma_per_wavefront), sink.data_ptr(),
+    st = lib().dit_mfma_probe(operand_dtype, int(bits_a), int(bits_b), int(mfma_per_wavefront), sink.data_ptr(),
                               sink.numel() * sink.element_size(), ctypes.byref(flops), _stream_ptr(stream))
     if st != DIT_OK:
         raise DitError(st, "dit_mfma_probe")

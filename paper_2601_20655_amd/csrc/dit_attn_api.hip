@@ -63,7 +63,7 @@ size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Flags {
     int qk_op, pv_op, qb, nw;
-    bool fused, simple, pipelined, resident;
+    bool fused, simple, pipelined, resident, mfma32;
 };
 
 // Resolve flag bits into operand types and staging mode.
@@ -71,7 +71,8 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     const uint32_t known = DIT_FLAG_QK_BF16 | DIT_FLAG_QK_F16 | DIT_FLAG_PV_BF16 | DIT_FLAG_PV_F16 |
                            DIT_FLAG_KV_PREPACK | DIT_FLAG_KV_FUSED | DIT_FLAG_WIDE_QTILE |
                            DIT_FLAG_SIMPLE_SCHEDULE | DIT_FLAG_BIG_WORKGROUP | DIT_FLAG_SMALL_WORKGROUP |
-                           DIT_FLAG_PIPELINED_SCHEDULE | DIT_FLAG_KV_RESIDENT | DIT_FLAG_QK_FP8;
+                           DIT_FLAG_PIPELINED_SCHEDULE | DIT_FLAG_KV_RESIDENT | DIT_FLAG_QK_FP8 |
+                           DIT_FLAG_MFMA_32X32;
     if (f & ~known) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_QK_BF16) && (f & DIT_FLAG_QK_F16)) return DIT_ERR_INVALID_ARG;
     if ((f & DIT_FLAG_PV_BF16) && (f & DIT_FLAG_PV_F16)) return DIT_ERR_INVALID_ARG;
@@ -81,6 +82,7 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     out->pv_op = (f & DIT_FLAG_PV_BF16) ? dit::OP_BF16 : dit::OP_F16;
     out->fused = (f & DIT_FLAG_KV_FUSED) != 0;
     out->resident = (f & DIT_FLAG_KV_RESIDENT) != 0;
+    out->mfma32 = (f & DIT_FLAG_MFMA_32X32) != 0;
     if (out->resident && out->fused) return DIT_ERR_INVALID_ARG;  // FUSED keeps nothing to reuse
     out->qb = (f & DIT_FLAG_WIDE_QTILE) ? 2 : 1;
     if ((f & DIT_FLAG_SIMPLE_SCHEDULE) && (f & DIT_FLAG_PIPELINED_SCHEDULE)) return DIT_ERR_INVALID_ARG;
@@ -91,13 +93,22 @@ dit_status parse_flags(uint32_t f, Flags* out) {
     return DIT_OK;
 }
 
+// Self-attention (one sequence per batch entry or packed requests) runs the pipelined kernel on 16x16x32 MFMAs
+// unless a flag asks for a form that only exists on 32x32x16 MFMAs (8-bit scores, 64 rows per wavefront, the
+// plain and fused schedules) or for the 32x32x16 kernel itself.  The V^T tiles are packed in the matching key order.
+bool self_attn_uses_mfma16(const Flags& fl) {
+    return !fl.fused && !fl.simple && fl.qb == 1 && fl.qk_op != dit::OP_FP8 && !fl.mfma32;
+}
+
 // Attention kernel launch, bracketed by the caller's timing events when the hook is set.
-dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused, hipStream_t s) {
+dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused, bool mfma16, hipStream_t s) {
     const bool timed = g_ev_before && g_ev_after;
     hipError_t e;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     if (aa.tile_count_a) {
         e = dit::launch_attn_split(aa, D, fl.qk_op, fl.pv_op, s);
+    } else if (mfma16) {
+        e = dit::launch_attn_pipe16(aa, D, fl.qk_op, fl.pv_op, fl.nw, s);
     } else if (!fused && !fl.simple) {
         e = dit::launch_attn_pipe(aa, D, fl.qb, fl.qk_op, fl.pv_op, fl.nw, s);
     } else {
@@ -452,6 +463,7 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
         pa.tab = ta.tab;
         pa.B = p->B; pa.H = p->H; pa.Lk = (int)pl.L; pa.nKT = pl.nKT;
         pa.in_f32 = p->in_dtype == DIT_F32;
+        pa.v_layout = self_attn_uses_mfma16(pl.fl) ? 1 : 0;
         pa.sk_b = p->sk.batch; pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
         pa.sv_b = p->sv.batch; pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
         pa.rg = rg;
@@ -475,7 +487,7 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
     aa.rg = rg;
     aa.qscale = scale * dit::kLog2e;
     aa.qn = qn;
-    return run_attn(aa, p->D, pl.fl, pl.fl.fused, s);
+    return run_attn(aa, p->D, pl.fl, pl.fl.fused, self_attn_uses_mfma16(pl.fl), s);
 }
 
 dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, const uint8_t* kv_valid,
@@ -544,7 +556,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     aa.so_b = p->so.batch; aa.so_t = p->so.token; aa.so_h = p->so.head;
     aa.qscale = scale * dit::kLog2e;
     aa.qn = qn;
-    return run_attn(aa, p->D, pl.fl, false, s);
+    return run_attn(aa, p->D, pl.fl, false, false, s);
 }
 
 size_t dit_attn_varlen_workspace_bytes(const dit_varlen_attn_params* p) {
@@ -606,6 +618,7 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     pa.tab = ta.tab;
     pa.B = 1; pa.H = p->H; pa.Lk = pl.vt.total_tokens; pa.nKT = pl.vt.total_tiles;
     pa.in_f32 = p->in_dtype == DIT_F32;
+    pa.v_layout = self_attn_uses_mfma16(pl.fl) ? 1 : 0;
     pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
     pa.sv_t = p->sv.token; pa.sv_h = p->sv.head;
     pa.rg = rg;
@@ -632,7 +645,9 @@ dit_status dit_attn_varlen_forward(const void* q, const void* k, const void* v, 
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     e = pl.fl.qk_op == dit::OP_FP8
             ? dit::launch_attn_pipe_varlen_fp8(aa, pl.vt, p->D, pl.fl.pv_op, pl.fl.nw, s)
-            : dit::launch_attn_pipe_varlen(aa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, pl.fl.nw, s);
+            : self_attn_uses_mfma16(pl.fl)
+                  ? dit::launch_attn_pipe16_varlen(aa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, pl.fl.nw, s)
+                  : dit::launch_attn_pipe_varlen(aa, pl.vt, p->D, pl.fl.qk_op, pl.fl.pv_op, pl.fl.nw, s);
     if (e != hipSuccess) return hip_fail(e, "attention kernel");
     if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     return DIT_OK;

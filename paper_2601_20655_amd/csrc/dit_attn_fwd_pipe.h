@@ -373,25 +373,35 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
 
         uint32_t Pd[QB][16];
         float ls[QB][2];
+        // fp16 P: the tile's row sum is taken over the ROUNDED pairs with packed fp16 additions (half the
+        // instructions of two fp32 chains; a tile's 16 values per chain stay below 2^12 and lose at most 2^-11
+        // relative per addition, errors that are independent from tile to tile and average out over the row).
+        constexpr bool PKSUM = PV_OP == OP_F16;
+        f16x2 lsp[QB][2];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) ls[qb][0] = ls[qb][1] = 0.f;
+        for (int qb = 0; qb < QB; ++qb) {
+            ls[qb][0] = ls[qb][1] = 0.f;
+            lsp[qb][0] = lsp[qb][1] = f16x2{(_Float16)0.f, (_Float16)0.f};
+        }
         // slice c = (query block c / 16, dword i = c % 16): scores 2i, 2i+1 of that block
         auto exp_slice = [&](int c) {
             const int qv = c / 16, i = c % 16;
             Sc[i / 8][qv][(2 * i) % 16] = __builtin_amdgcn_exp2f(Sc[i / 8][qv][(2 * i) % 16]);
             Sc[i / 8][qv][(2 * i + 1) % 16] = __builtin_amdgcn_exp2f(Sc[i / 8][qv][(2 * i + 1) % 16]);
         };
-        // The row sum runs in fp32 over the unrounded probabilities, two chains of plain additions: the
-        // dot-product instruction that would sum a packed pair does not overlap with a running MFMA
-        // (about 8 clocks each, unhidden; additions, maxima and exp2 hide completely).  Numerator
-        // (rounded P) and denominator then differ by at most half a unit of P's last place relative
-        // (2^-11 for fp16 P, 2^-8 for bf16 P), typically by that / sqrt(keys that carry the mass).
+        // Row sums: fp16 P -- packed fp16 additions of the rounded pairs (see PKSUM above); bf16 P -- two fp32 chains
+        // over the unrounded values.  The dot-product instruction that would sum a packed pair in fp32 does not
+        // overlap with a running MFMA (about 8 clocks each, unhidden); additions, maxima and exp2 hide completely.
         auto pack_slice = [&](int c) {
             const int qv = c / 16, i = c % 16;
             const float e0 = Sc[i / 8][qv][(2 * i) % 16], e1 = Sc[i / 8][qv][(2 * i + 1) % 16];
             Pd[qv][i] = pack2<PV_OP>(e0, e1);
-            ls[qv][0] += e0;
-            ls[qv][1] += e1;
+            if constexpr (PKSUM) {
+                lsp[qv][i & 1] += __builtin_bit_cast(f16x2, Pd[qv][i]);
+            } else {
+                ls[qv][0] += e0;
+                ls[qv][1] += e1;
+            }
         };
 #pragma unroll
         for (int c = 0; c < PRE; ++c) exp_slice(c);
@@ -462,7 +472,12 @@ __device__ __forceinline__ void attn_pipe_body(const AttnArgs& a, const PipeView
         for (int c = (NB - 2) * CPB; c < NCH; ++c) max_slice(c);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            l_run[qb] += ls[qb][0] + ls[qb][1];
+            if constexpr (PKSUM) {
+                const f16x2 t2 = lsp[qb][0] + lsp[qb][1];
+                l_run[qb] += (float)t2[0] + (float)t2[1];
+            } else {
+                l_run[qb] += ls[qb][0] + ls[qb][1];
+            }
             asm volatile("" : "+v"(l_run[qb]));  // keeps the row-sum chain here (it would sink past the barrier)
         }
 #pragma unroll

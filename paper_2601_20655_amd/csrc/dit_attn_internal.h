@@ -86,6 +86,7 @@ struct PackArgs {
     const float2* tab;     // nullable (no rotation)
     int B, H, Lk, nKT;
     int in_f32;
+    int v_layout;  // key order inside the V^T rows: 0 for kernels on 32x32x16 MFMAs, 1 for 16x16x32 (see pack_tile)
     int64_t sk_b, sk_t, sk_h, sv_b, sv_t, sv_h;
     RopeGeom rg;
     NormArgs kn;  // normalisation of k rows (rstd indexed by b*Lk + key, packed requests: by token)
@@ -157,6 +158,10 @@ hipError_t launch_prepack_varlen(const PackArgs& a, const VarlenTable& vt, int D
 hipError_t launch_attn_pipe_varlen(const AttnArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, int nw,
                                    hipStream_t s);
 hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStream_t s);
+// pipelined self-attention on 16x16x32 MFMAs (16-bit operands, 32 rows per wavefront, tiles packed with v_layout 1)
+hipError_t launch_attn_pipe16(const AttnArgs& a, int D, int qk_op, int pv_op, int nw, hipStream_t s);
+hipError_t launch_attn_pipe16_varlen(const AttnArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, int nw,
+                                     hipStream_t s);
 // before launch_prepack when a.valid is set: the valid keys of every batch entry (of each key group) in
 // ascending order, densely over the tile slots
 hipError_t launch_key_compact(const PackArgs& a, hipStream_t s);

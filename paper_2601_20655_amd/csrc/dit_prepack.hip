@@ -139,18 +139,21 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
     }
     __syncthreads();
 
-    // V^T chunk (d, kc): slot 4g+e holds key 16*(kc/2) + 8g + 4*(kc%2) + e of the tile
+    // V^T chunk (d, kc) = eight key slots, in the order the attention kernel's PV operand wants its keys:
+    //  32x32x16 MFMAs (v_layout 0): slot 4g+e holds key 16*(kc/2) + 8g + 4*(kc%2) + e of the tile;
+    //  16x16x32 MFMAs (v_layout 1): slot 4g+e holds key 32*(kc/4) + 16g + 4*(kc%4) + e.
 #pragma unroll
     for (int i = 0; i < D / 32; ++i) {
         const int d = (tid >> 3) + 32 * i;
         const int kc = tid & 7;
-        const int k0 = 16 * (kc >> 1) + 4 * (kc & 1);
+        const int k0 = a.v_layout ? 32 * (kc >> 2) + 4 * (kc & 3) : 16 * (kc >> 1) + 4 * (kc & 1);
+        const int kstep = a.v_layout ? 16 : 8;
         uint32_t w[4];
 #pragma unroll
         for (int g = 0; g < 2; ++g)
 #pragma unroll
             for (int e2 = 0; e2 < 2; ++e2) {
-                const int ka = k0 + 8 * g + 2 * e2;
+                const int ka = k0 + kstep * g + 2 * e2;
                 w[2 * g + e2] = (uint32_t)vs[ka * VS + d] | ((uint32_t)vs[(ka + 1) * VS + d] << 16);
             }
         *reinterpret_cast<u32x4*>(t.dst + G::K_BYTES + d * G::VROW + kc * 16) = mk4(w[0], w[1], w[2], w[3]);

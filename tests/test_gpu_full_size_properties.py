@@ -72,8 +72,9 @@ def test_moving_the_origin_changes_nothing():
 
 
 def test_two_schedules_agree_on_every_row():
-    """The pipelined 8-wavefront kernel (default) and the plain one-tile-at-a-time kernel share the
-    arithmetic but not the schedule, the tile transport, the rescale bookkeeping or the workgroup
+    """The pipelined 8-wavefront kernel on 16x16x32 matrix instructions (default), its 4-wavefront and
+    32x32x16-instruction forms and the plain one-tile-at-a-time kernel share the arithmetic but not the
+    schedule, the operand layouts, the tile transport, the rescale bookkeeping or the workgroup
     shape; at the full shape they must agree on every one of the 168 M outputs to well within the
     parity bar (each is held to the oracle on sampled rows elsewhere)."""
     import torch
@@ -85,9 +86,11 @@ def test_two_schedules_agree_on_every_row():
                            flags=B.DIT_FLAG_SIMPLE_SCHEDULE)
     c = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32,
                            flags=B.DIT_FLAG_SMALL_WORKGROUP)
+    d = B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out_dtype=torch.float32,
+                           flags=B.DIT_FLAG_MFMA_32X32)
     torch.cuda.synchronize()
     rms = a.double().pow(2).mean().sqrt().item()
-    for name, other in (("plain", b), ("4-wavefront", c)):
+    for name, other in (("plain", b), ("4-wavefront", c), ("32x32x16-instruction", d)):
         diff = (a - other).abs().max().item()
         print("default vs %s kernel, all rows: max|a - b| / RMS = %.3e" % (name, diff / rms))
         assert diff <= 2e-3 * rms

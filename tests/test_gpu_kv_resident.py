@@ -27,7 +27,7 @@ def workspace(nbytes=96 << 20):
     return torch.empty(nbytes, dtype=torch.uint8, device="cuda")
 
 
-@pytest.mark.parametrize("shape", [0, B.DIT_FLAG_SIMPLE_SCHEDULE, B.DIT_FLAG_BIG_WORKGROUP])
+@pytest.mark.parametrize("shape", [0, B.DIT_FLAG_SIMPLE_SCHEDULE, B.DIT_FLAG_BIG_WORKGROUP, B.DIT_FLAG_MFMA_32X32])
 @pytest.mark.parametrize("mode", [None, "token"])
 def test_self_attention_second_query_set(shape, mode):
     """6,240 tokens x 4 heads: the first call packs K, V; the second one runs other queries with

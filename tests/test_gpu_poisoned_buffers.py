@@ -30,7 +30,8 @@ def twice(call, ws_bytes, out_shape, out_dtype):
     return results
 
 
-@pytest.mark.parametrize("flags", [0, B.DIT_FLAG_BIG_WORKGROUP, B.DIT_FLAG_SIMPLE_SCHEDULE])
+@pytest.mark.parametrize("flags", [0, B.DIT_FLAG_BIG_WORKGROUP, B.DIT_FLAG_SIMPLE_SCHEDULE,
+                                   B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_BIG_WORKGROUP])
 @pytest.mark.parametrize("mode", [None, "token"])
 def test_self_attention_ignores_stale_workspace(flags, mode):
     import torch

@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 
 EPS = 1e-6
 SHAPES = {"auto": 0, "8w": B.DIT_FLAG_BIG_WORKGROUP, "plain": B.DIT_FLAG_SIMPLE_SCHEDULE,
-          "plain_wide": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE}
+          "plain_wide": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
+          "m32_8w": B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_BIG_WORKGROUP}
 
 
 def dev_norm(mode, gq, gk, eps=EPS):

@@ -50,6 +50,9 @@ SHAPES = {
     "qb1_4w": B.DIT_FLAG_SMALL_WORKGROUP,
     "qb2_4w": B.DIT_FLAG_WIDE_QTILE,
     "qb1_8w": B.DIT_FLAG_BIG_WORKGROUP,
+    # the same pipeline on 32x32x16 matrix instructions (the default runs on 16x16x32)
+    "m32_4w": B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_SMALL_WORKGROUP,
+    "m32_8w": B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_BIG_WORKGROUP,
     "simple_qb1": B.DIT_FLAG_SIMPLE_SCHEDULE,
     "simple_qb2": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
 }
@@ -117,7 +120,7 @@ def test_ragged_sizes(grid, D):
         assert np.max(np.abs(to_f64(lse) - ref_lse)) < 5e-3
 
 
-@pytest.mark.parametrize("name", ["qb1_8w", "qb1_4w", "qb2_4w", "simple_qb1"])
+@pytest.mark.parametrize("name", ["qb1_8w", "qb1_4w", "m32_8w", "m32_4w", "qb2_4w", "simple_qb1"])
 def test_head_dim_64_steady_state_all_rows(name):
     """head_dim 64 over 68 key tiles and 17 (8-wavefront) or 34 query tiles per head: the key loop of each form
     in steady state (the ragged cases above end after seven tiles), every row against the oracle, fp32 inputs

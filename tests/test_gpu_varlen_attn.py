@@ -10,7 +10,9 @@ from gpu_util import compare, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = {"auto": 0, "4w": B.DIT_FLAG_SMALL_WORKGROUP, "8w": B.DIT_FLAG_BIG_WORKGROUP}
+SHAPES = {"auto": 0, "4w": B.DIT_FLAG_SMALL_WORKGROUP, "8w": B.DIT_FLAG_BIG_WORKGROUP,
+          "m32_4w": B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_SMALL_WORKGROUP,
+          "m32_8w": B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_BIG_WORKGROUP}
 
 
 def compare_per_request(got, ref, grids, what, **kw):
