@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS_16BIT_DENSE = 2500.0  # MI355X published dense bf16/fp16 MFMA peak
 PEAK_TFLOPS_8BIT_DENSE = 5000.0   # published dense fp8 MFMA peak
 
-COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "attn_fwd_pipe_kernel_dit14b_counters.txt")
+COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "attn_fwd_pipe16_kernel_dit14b_counters.txt")
 
 
 def traffic_bytes_for(version):

@@ -710,6 +710,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 10200; }  // 1.2.0
+int dit_attn_version(void) { return 10300; }  // 1.3.0
 
 }  // extern "C"

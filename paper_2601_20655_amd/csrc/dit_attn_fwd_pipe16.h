@@ -185,8 +185,12 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
             for (int r = 0; r < 16; ++r) O[og][qb][r] = 0.f;
     }
 
-    const int kread_off = i16 * G::KROW + g4 * 16;
-    const int vread_off = i16 * G::VROW + g4 * 16;
+    // Rows 4..11 of every 16 hold neighbouring 16-byte chunks in swapped pairs (pack_tile, layout 1): with that,
+    // the lanes the LDS serves in one cycle of a 128-bit read fall into distinct banks (plain rows gave two-way
+    // conflicts on every operand read).
+    const int gsw = g4 ^ (((i16 >> 2) ^ (i16 >> 3)) & 1);
+    const int kread_off = i16 * G::KROW + gsw * 16;
+    const int vread_off = i16 * G::VROW + gsw * 16;
     // K' fragment f = 4 ks + kb: keys 16 kb .. +15, channels 32 ks .. +31 (the lane: key i, channels 8g .. +7)
     auto k_operand = [&](const uint8_t* kt, int f) {
         return *reinterpret_cast<const u32x4*>(kt + (f & 3) * 16 * G::KROW + (f >> 2) * 64);
@@ -272,7 +276,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     };
 
 #ifndef DIT_PIPE16_LA
-#define DIT_PIPE16_LA 3
+#define DIT_PIPE16_LA 6
 #endif
     constexpr int LA = DIT_PIPE16_LA;  // LDS fragment reads issued this many fragments ahead of their MFMAs
     constexpr int NCH = 16;            // softmax slices: two scores -> one dword of P

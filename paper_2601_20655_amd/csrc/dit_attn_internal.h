@@ -86,7 +86,7 @@ struct PackArgs {
     const float2* tab;     // nullable (no rotation)
     int B, H, Lk, nKT;
     int in_f32;
-    int v_layout;  // key order inside the V^T rows: 0 for kernels on 32x32x16 MFMAs, 1 for 16x16x32 (see pack_tile)
+    int v_layout;  // tile layout: 0 for kernels on 32x32x16 MFMAs, 1 for 16x16x32 (key order in V^T rows, chunk swizzle; see pack_tile)
     int64_t sk_b, sk_t, sk_h, sv_b, sv_t, sv_h;
     RopeGeom rg;
     NormArgs kn;  // normalisation of k rows (rstd indexed by b*Lk + key, packed requests: by token)
