@@ -23,19 +23,6 @@
 
 namespace dit {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-template <int OP>
-__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
-    if constexpr (OP == OP_F16) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
-                                                      0);
-    } else {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
-                                                       0, 0);
-    }
-}
-
 // The 16x16 results are kept four to a 16-register block (the scores of a query block: quarter kb = key block;
 // the output: quarter = channel block within a group of four) and the MFMA works on one quarter of the block.
 // Element-wise changes on the rare paths are then sub-register writes of one wide value, which the register
