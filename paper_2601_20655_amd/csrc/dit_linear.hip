@@ -58,7 +58,8 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     constexpr int BR = 16;       // rows of an MFMA block
     constexpr int FB = 4;        // 16-feature blocks per wavefront
     constexpr int TB = 8;        // 16-token blocks per wavefront
-    constexpr int NCH = 32 / NW;  // 1 KiB chunks (8 rows) per wavefront and tile
+    constexpr int NLW = 4;        // wavefronts that issue the loads (the first four: see below)
+    constexpr int NCH = 32 / NLW;  // 1 KiB chunks (8 rows) per loading wavefront and tile
     constexpr int ROWB = 128;  // bytes per row of a tile
     constexpr int NKS = 2;     // contraction slices (32 indices) per step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -70,58 +71,97 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     const int lr = lane & 15, lg = lane >> 4;  // row of a block, 16-byte piece of a slice
     const int wt = wave & 1, wf = wave >> 1;
 
-    // Workgroup order.  Workgroups are dealt to the 8 XCDs round-robin; each XCD is given a contiguous
-    // range of logical ids, and logical ids run feature tile by feature tile through groups of 8
-    // token tiles, so the 32 workgroups an XCD holds at a time share 8 x tiles and 4 w tiles in its L2.
-    int tm, tn;
+    // Persistent workgroups: the grid holds one workgroup per compute unit (or one per tile, if there are
+    // fewer tiles), and a workgroup walks its tiles one after the other as ONE stream of steps: the loads of
+    // a tile's first steps go out during the last steps of the tile before, and the only thing that
+    // happens between two tiles is the store of the accumulators.  (One workgroup per tile spent a tenth of
+    // the time between the end of one tile's loop and the start of the next one's on a compute unit:
+    // stores, workgroup launch, the first loads' round trip.)
+    // Tile order.  Workgroups are dealt to the 8 XCDs round-robin; each XCD is given a contiguous range of
+    // logical tile ids, which its workgroups take in turn, and logical ids run feature tile by feature
+    // tile through groups of 8 token tiles, so the 32 tiles an XCD works on at a time share 8 x tiles and
+    // 4 w tiles in its L2.
+    const int ntiles = a.nTM * a.nTN;
+    int first_tile, my_tiles, tile_stride;  // logical ids first_tile + i * tile_stride, i < my_tiles
     {
         const int nblk = gridDim.x, bid = blockIdx.x;
-        const int xcd = bid & 7, idx = bid >> 3;
-        const int chunk = nblk >> 3, rem = nblk & 7;
-        const int logical = xcd * chunk + (xcd < rem ? xcd : rem) + idx;
+        const int xcd = bid & 7, slot = bid >> 3;
+        const int chunk = ntiles >> 3, rem = ntiles & 7;
+        const int count = chunk + (xcd < rem ? 1 : 0);   // tiles of this XCD
+        tile_stride = (nblk - xcd + 7) >> 3;             // workgroups of this XCD
+        first_tile = xcd * chunk + (xcd < rem ? xcd : rem) + slot;
+        my_tiles = count > slot ? (count - slot + tile_stride - 1) / tile_stride : 0;
+    }
+    if (my_tiles == 0) return;
+    auto tile_coords = [&](int i, int& tm, int& tn) __attribute__((always_inline)) {
+        i = i < my_tiles ? i : my_tiles - 1;  // (past the end: the last tile again, for loads nobody uses)
+        const int logical = first_tile + i * tile_stride;
         const int per_group = kLinGroup * a.nTN;
         const int group = logical / per_group, within = logical - group * per_group;
         const int first = group * kLinGroup;
         const int gsz = a.nTM - first < kLinGroup ? a.nTM - first : kLinGroup;
         tm = first + within % gsz;
         tn = within / gsz;
-    }
+    };
 
-    // ---- DMA sources: wavefront w moves 1 KiB chunks w, w+8, w+16, w+24 of both tiles; a chunk is 8
-    // rows.  Rows past the end of x or w are clamped to the last one (their products are never stored).
-    // Per lane: 32-bit byte offsets from the tile's first row (the host checks that a tile's extent
-    // fits 32 bits); the tile base and the step's column offset are wavefront-uniform.
-    uint32_t xoff[NCH], woff[NCH];
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int r = 8 * (wave + NW * i) + (lane >> 3);
-        const int p = (lane & 7) ^ ((r >> 1) & 7);
-        int xr = tm * kLinBM + r, wr = tn * kLinBN + r;
-        xr = (xr < a.M ? xr : a.M - 1) - tm * kLinBM;
-        wr = (wr < a.N ? wr : a.N - 1) - tn * kLinBN;
-        xoff[i] = (uint32_t)xr * (uint32_t)(a.ldx * 2) + 16 * p;
-        woff[i] = (uint32_t)wr * (uint32_t)(a.ldw * 2) + 16 * p;
-    }
-    const uint8_t* const xtile = reinterpret_cast<const uint8_t*>(a.x + (int64_t)tm * kLinBM * a.ldx);
-    const uint8_t* const wtile = reinterpret_cast<const uint8_t*>(a.w + (int64_t)tn * kLinBN * a.ldw);
+    // ---- DMA sources: wavefront w of the first four moves 1 KiB chunks w, w+4, .., w+28 of both tiles; a
+    // chunk is 8 rows.  (The two wavefronts of a SIMD do not advance evenly: the older one is served first and
+    // reaches the step's barrier about a third of a step early, the younger one is the critical path.  So the
+    // older ones -- wavefronts 0..3, one per SIMD -- issue all the loads, and the younger ones only multiply.)
+    // Rows past the end of x or w are clamped to the last one (their products are never stored).
+    // A lane's byte offset from the tile's first row (32 bits: the host checks that a tile's extent fits) is
+    // worked out at each load from its row in chunk 0 and its 16-byte piece, which is the same for every
+    // chunk (chunks are 32 rows apart, the swizzle has period 16 rows): two registers instead of a table
+    // of sixteen.  The tile base and the step's column offset are wavefront-uniform.
+    // The loads run two steps ahead of the MFMAs, so they have a tile and a step of their own.
     const int nK = a.K / kLinBK;
-    // (a tile number past the end fetches the last tile again, into a buffer nobody reads any more:
-    // every step then has the same number of loads in flight, which the counted wait relies on; the
-    // empty asm keeps the compiler from folding base + offset into per-lane 64-bit pointers ahead of
-    // the loop, which would cost two registers per load)
-    auto dma_chunk = [&](const uint8_t* tile, uint32_t o, int kt, int lds_byte, int i) {
-        kt = kt < nK ? kt : nK - 1;
+    const int load_row0 = 8 * (wave & (NLW - 1)) + (lane >> 3);
+    const uint32_t load_piece = 16u * ((lane & 7) ^ ((load_row0 >> 1) & 7));
+    const uint32_t ldx2 = (uint32_t)(a.ldx * 2), ldw2 = (uint32_t)(a.ldw * 2);
+    const uint8_t *xtile, *wtile;
+    int xrow_max, wrow_max;  // last valid row of the tile being loaded, from the tile's first row
+    int load_tile = 0, load_kt = 0;
+    auto set_load_tile = [&](int i) __attribute__((always_inline)) {
+        int tm, tn;
+        tile_coords(i, tm, tn);
+        xrow_max = a.M - 1 - tm * kLinBM;
+        wrow_max = a.N - 1 - tn * kLinBN;
+        xtile = reinterpret_cast<const uint8_t*>(a.x + (int64_t)tm * kLinBM * a.ldx);
+        wtile = reinterpret_cast<const uint8_t*>(a.w + (int64_t)tn * kLinBN * a.ldw);
+    };
+    set_load_tile(0);
+    auto next_load_step = [&]() __attribute__((always_inline)) {
+        if (++load_kt == nK) {
+            load_kt = 0;
+            set_load_tile(++load_tile);
+        }
+    };
+    // (the empty asm keeps the compiler from working the offsets out ahead of the loop and carrying them
+    // through it, and from folding base + offset into per-lane 64-bit pointers)
+    auto dma_chunk = [&](const uint8_t* tile, int row_max, uint32_t ld2, int lds_byte, int i) __attribute__((always_inline)) {
+        int r = load_row0;
+        asm volatile("" : "+v"(r));
+        r += 8 * NLW * i;
+        r = r < row_max ? r : row_max;
+        uint32_t o = (uint32_t)r * ld2 + load_piece;
         asm volatile("" : "+v"(o));
-        __builtin_amdgcn_global_load_lds((gptr_t)(tile + kt * (kLinBK * 2) + o),
-                                         (lptr_t)(smem + lds_byte + (wave + i * NW) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(tile + load_kt * (kLinBK * 2) + o),
+                                         (lptr_t)(smem + lds_byte + ((wave & (NLW - 1)) + i * NLW) * 1024), 16, 0, 0);
     };
-    auto dma_x = [&](int kt, int buf) {
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) dma_chunk(xtile, xoff[i], kt, buf * kLinTileBytes, i);
+    auto dma_x_chunk = [&](int buf, int i) __attribute__((always_inline)) { dma_chunk(xtile, xrow_max, ldx2, buf * kLinTileBytes, i); };
+    auto dma_w_chunk = [&](int buf, int i) __attribute__((always_inline)) {
+        dma_chunk(wtile, wrow_max, ldw2, kWBase + buf * kLinTileBytes, i);
     };
-    auto dma_w = [&](int kt, int buf) {
+    const bool loader = wave < NLW;
+    auto dma_x = [&](int buf) {
+        if (!loader) return;
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) dma_chunk(wtile, woff[i], kt, kWBase + buf * kLinTileBytes, i);
+        for (int i = 0; i < NCH; ++i) dma_x_chunk(buf, i);
+    };
+    auto dma_w = [&](int buf) {
+        if (!loader) return;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) dma_w_chunk(buf, i);
     };
 
     // ---- fragment addresses: row base + swizzled piece of contraction slice ks.  The same swizzle serves
@@ -158,11 +198,11 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     // MFMAs back to back followed by the rest leave the pipe idle for as long as the rest takes to issue.
     u32x4 W[2][FB], X[TB];
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    auto read_w = [&](u32x4& w, auto fb, int buf, int ks) {
+    auto read_w = [&](u32x4& w, auto fb, int buf, int ks) __attribute__((always_inline)) {
         const uint32_t wa = lds0 + buf * kLinTileBytes + wread + koff[ks];
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(w) : "v"(wa), "n"(decltype(fb)::value * BR * ROWB));
     };
-    auto read_x = [&](u32x4& x, auto tb, int buf, int ks) {
+    auto read_x = [&](u32x4& x, auto tb, int buf, int ks) __attribute__((always_inline)) {
         const uint32_t xa = lds0 + buf * kLinTileBytes + xread + koff[ks];
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(x) : "v"(xa), "n"(decltype(tb)::value * BR * ROWB));
     };
@@ -176,26 +216,109 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     // (the bare barrier instruction: __syncthreads() is a fence too, for which the compiler drains every
     // load in flight -- vmcnt(0) -- in front of the barrier, and the x tile that is meant to stay in
     // flight across it would be waited for after all)
-    auto sync_point = [&]() {
+    auto sync_point = [&]() __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NCH) : "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
+    // ---- store of a finished tile.  A lane holds token (column lr of block tb) and four consecutive features
+    // per accumulator (16 fb + 4 lg + e of its wavefront's 64), so stored from the accumulators a wavefront
+    // instruction would write sixteen 32-byte pieces, and a tile's 4,096 such pieces held the stream up for a
+    // tenth of the time.  So a wavefront passes its share through LDS, 4 KiB at a time, and stores whole
+    // output rows: 8 (bf16) or 16 (fp32) lanes per row of its 64 features, 16 bytes each.  The staging area is
+    // the x buffer of the step just finished: behind that step's barrier nobody reads it any more, and the
+    // loads that refill it are issued in the next step -- behind the barrier that ends the store, so that a
+    // loading wavefront that has stored cannot overwrite what another one still stages.  Pieces of a staged
+    // row are swizzled with the row number.  The accumulators start the next tile at zero.
+    auto store_tile = [&](int tm, int tn, int stage_buf) __attribute__((always_inline)) {
+        constexpr int ES = OUT_F32 ? 4 : 2;   // bytes per output element
+        constexpr int RB = 64 * ES;           // bytes per staged row (the wavefront's 64 features)
+        constexpr int PR = RB / 16;           // 16-byte pieces per row
+        constexpr int RP = 4096 / RB;         // rows per pass
+        constexpr int TBP = RP / BR;          // token blocks per pass
+        uint2 bb[FB];
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb) {
+            const int n0 = tn * kLinBN + wf * BR * FB + fb * BR + 4 * lg;
+            bb[fb] = make_uint2(0u, 0u);
+            if (a.bias && n0 < a.N) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n0);
+        }
+        uint8_t* const region = smem + stage_buf * kLinTileBytes + wave * 4096;
+        const int rrow = lane / PR, rp = lane % PR;
+        const int n = tn * kLinBN + wf * BR * FB + rp * (16 / ES);
+#pragma unroll
+        for (int pass = 0; pass < TB / TBP; ++pass) {
+#pragma unroll
+            for (int h = 0; h < TBP; ++h) {
+                const int tb = pass * TBP + h;
+                const int row = BR * h + lr;
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) {
+                    const float b0 = __uint_as_float(bb[fb].x << 16), b1 = __uint_as_float(bb[fb].x & 0xffff0000u);
+                    const float b2 = __uint_as_float(bb[fb].y << 16), b3 = __uint_as_float(bb[fb].y & 0xffff0000u);
+                    const float y0 = acc[fb][tb][0] + b0, y1 = acc[fb][tb][1] + b1;
+                    const float y2 = acc[fb][tb][2] + b2, y3 = acc[fb][tb][3] + b3;
+                    const int col = (BR * fb + 4 * lg) * ES;
+                    uint8_t* const dst = region + row * RB + (((col >> 4) ^ (row & (PR - 1))) << 4) + (col & 15);
+                    if constexpr (OUT_F32) *reinterpret_cast<float4*>(dst) = make_float4(y0, y1, y2, y3);
+                    else *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<OP_BF16>(y0, y1), pack2<OP_BF16>(y2, y3));
+                }
+            }
+            auto staged = [&](int k) __attribute__((always_inline)) {
+                const int row = k * (64 / PR) + rrow;
+                return *reinterpret_cast<const uint4*>(region + row * RB + ((rp ^ (row & (PR - 1))) << 4));
+            };
+            auto put = [&](int k, uint4 v) __attribute__((always_inline)) {
+                const int m = tm * kLinBM + wt * BR * TB + pass * RP + k * (64 / PR) + rrow;
+                // N is a multiple of 8: a piece of a row is inside or outside as a whole
+                if (m < a.M && n < a.N)
+                    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.y) + ((int64_t)m * a.ldy + n) * ES) = v;
+            };
+            // (two at a time: the loop around this leaves few registers free)
+            {
+                const uint4 v0 = staged(0), v1 = staged(1);
+                put(0, v0);
+                put(1, v1);
+            }
+            {
+                const uint4 v2 = staged(2), v3 = staged(3);
+                put(2, v2);
+                put(3, v3);
+            }
+        }
+        // (zeroed here, not as they are staged: the registers of staged accumulators serve as temporaries)
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[fb][tb][r] = 0.f;
+        __builtin_amdgcn_s_barrier();
+    };
+
     // Prologue: tiles x(0), w(0), x(1) in a burst; the first barrier; then what a last slice would
     // have sent behind it (the w tile of step 1); the loop sends the rest.
-    dma_x(0, 0);
-    dma_w(0, 0);
-    dma_x(1, 1);
+    dma_x(0);
+    dma_w(0);
+    next_load_step();
+    dma_x(1);
     sync_point();
-    dma_w(1, 1);
+    dma_w(1);
+    next_load_step();
     int xb = 0, wb = 0;  // buffers of the step being multiplied
     static_for<0, FB>([&](auto fb) { read_w(W[0][decltype(fb)::value], fb, wb, 0); });
     static_for<0, TB - 1>([&](auto tb) { read_x(X[decltype(tb)::value], tb, xb, 0); });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    for (int kt = 0; kt < nK; ++kt) {
+    int tile = 0, kt = 0;  // the step being multiplied
+    int tm, tn;
+    tile_coords(0, tm, tn);
+    const int nsteps = my_tiles * nK;
+    auto run = [&](auto loads) __attribute__((always_inline)) {
+    constexpr bool LOADS = decltype(loads)::value;
+    for (int step = 0; step < nsteps; ++step) {
         const int xb_next = xb + 1 == SX ? 0 : xb + 1, wb_next = wb ^ 1;
-        const int xb_prev = xb == 0 ? SX - 1 : xb - 1, wb_prev = wb ^ 1;
-        auto block = [&](auto ksc, auto tbc) {
+        const int xb_prev = xb == 0 ? SX - 1 : xb - 1;
+        auto block = [&](auto ksc, auto tbc) __attribute__((always_inline)) {
             constexpr int ks = decltype(ksc)::value, T = decltype(tbc)::value;
             constexpr bool last = ks + 1 == NKS;
             constexpr int cur = ks & 1, nxt = cur ^ 1;
@@ -205,9 +328,6 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
             // reads issued behind the youngest fragment this block needs (its x fragment; in the first
             // block of a slice the slice's last w fragment), from the issue order below
             constexpr int YOUNGER = last ? (T < 2 ? 6 : T == 2 ? 8 : 10) : (T == 0 ? 5 : 10);
-            if constexpr (DIT_LIN_PRIO == 1) {
-                if constexpr (T % 2 == 0) __builtin_amdgcn_s_setprio((T & 2) ? 0 : 1);
-            }
             if constexpr (T == 0) {
                 asm volatile("s_waitcnt lgkmcnt(%5)"
                              : "+v"(W[cur][0]), "+v"(W[cur][1]), "+v"(W[cur][2]), "+v"(W[cur][3]), "+v"(X[T])
@@ -217,7 +337,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
             }
             acc[0][T] = mfma16<OP_BF16>(W[cur][0], X[T], acc[0][T]);
             __builtin_amdgcn_sched_barrier(0);
-            // (after the last tile the loads and reads behind this barrier go to buffers nobody uses:
+            // (after the last step the loads and reads behind this barrier go to buffers nobody uses:
             // uniform control flow)
             if constexpr (last && T == 1) sync_point();
             // the x fragment of the block before: its MFMAs have issued
@@ -226,12 +346,15 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
             __builtin_amdgcn_sched_barrier(0);
             acc[1][T] = mfma16<OP_BF16>(W[cur][1], X[T], acc[1][T]);
             __builtin_amdgcn_sched_barrier(0);
-            // this block's share of the loads (q = token blocks since the barrier)
+            // this block's share of the loads (q = token blocks since the barrier); both tiles are those
+            // of the step two ahead
+            // (the w tile, needed a step from now, two chunks a block; the x tile, needed two steps from now, one)
             constexpr int q = last ? T - 1 : TB - 1 + T;
-            if constexpr (q >= 0 && q < NCH) {
-                dma_chunk(wtile, woff[q], kt + SW, kWBase + wb * kLinTileBytes, q);
-            } else if constexpr (q >= TB - 1 && q - (TB - 1) < NCH) {
-                dma_chunk(xtile, xoff[q - (TB - 1)], kt + SX - 1, xb_prev * kLinTileBytes, q - (TB - 1));
+            if constexpr (LOADS && q >= 0 && 2 * q < NCH) {
+                dma_w_chunk(wb, 2 * q);
+                dma_w_chunk(wb, 2 * q + 1);
+            } else if constexpr (LOADS && q >= TB - 1 && q - (TB - 1) < NCH) {
+                dma_x_chunk(xb_prev, q - (TB - 1));
             }
             __builtin_amdgcn_sched_barrier(0);
             acc[2][T] = mfma16<OP_BF16>(W[cur][2], X[T], acc[2][T]);
@@ -246,48 +369,22 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
             acc[3][T] = mfma16<OP_BF16>(W[cur][3], X[T], acc[3][T]);
             __builtin_amdgcn_sched_barrier(0);
         };
-        static_for<0, NKS>([&](auto ksc) { static_for<0, TB>([&](auto tbc) { block(ksc, tbc); }); });
+        static_for<0, NKS>([&](auto ksc) __attribute__((always_inline)) {
+            static_for<0, TB>([&](auto tbc) __attribute__((always_inline)) { block(ksc, tbc); });
+        });
         xb = xb_next;
         wb = wb_next;
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
-
-    // ---- epilogue: lane holds token (column lr of block tb) and four consecutive features per accumulator:
-    // 16 fb + 4 lg + e of its wavefront's share.
-    // All bias values are fetched before the first store: a load waited for behind stores would wait
-    // for the stores too (one counter tracks both), several round trips in a row.
-    auto feature0 = [&](int fb) { return tn * kLinBN + wf * BR * FB + fb * BR + 4 * lg; };
-    uint2 bb[FB];
-#pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
-        const int n0 = feature0(fb);
-        bb[fb] = make_uint2(0u, 0u);
-        if (a.bias && n0 < a.N) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n0);
-    }
-    // (the wait for them happens here, once: the empty statement reads every value)
-#pragma unroll
-    for (int fb = 0; fb < FB; ++fb) asm volatile("" : "+v"(bb[fb].x), "+v"(bb[fb].y));
-#pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
-        const int n0 = feature0(fb);
-        if (n0 >= a.N) continue;  // N is a multiple of 8: a quad is inside or outside as a whole
-        const float b0 = __uint_as_float(bb[fb].x << 16), b1 = __uint_as_float(bb[fb].x & 0xffff0000u);
-        const float b2 = __uint_as_float(bb[fb].y << 16), b3 = __uint_as_float(bb[fb].y & 0xffff0000u);
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb) {
-            const int m = tm * kLinBM + wt * BR * TB + tb * BR + lr;
-            if (m >= a.M) continue;
-            const float y0 = acc[fb][tb][0] + b0, y1 = acc[fb][tb][1] + b1;
-            const float y2 = acc[fb][tb][2] + b2, y3 = acc[fb][tb][3] + b3;
-            const int64_t o = (int64_t)m * a.ldy + n0;
-            if constexpr (OUT_F32) {
-                *reinterpret_cast<float4*>(static_cast<float*>(a.y) + o) = make_float4(y0, y1, y2, y3);
-            } else {
-                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.y) + o) =
-                    make_uint2(pack2<OP_BF16>(y0, y1), pack2<OP_BF16>(y2, y3));
-            }
+        if constexpr (LOADS) next_load_step();
+        if (++kt == nK) {
+            store_tile(tm, tn, xb == 0 ? SX - 1 : xb - 1);
+            kt = 0;
+            tile_coords(++tile, tm, tn);
         }
     }
+    };
+    if (loader) run(std::true_type());
+    else run(std::false_type());
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
 }
 
 template <bool OUT_F32>
@@ -297,7 +394,14 @@ hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
     static std::atomic<uint64_t> attr_set{0};
     hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)a.nTM * a.nTN)), dim3(64 * kLinWaves), smem, s, a);
+    // one workgroup per compute unit (a workgroup takes all of a unit's LDS), fewer if there are fewer tiles
+    int dev = 0, cus = 0;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    const int64_t ntiles = (int64_t)a.nTM * a.nTN;
+    const unsigned grid = (unsigned)(ntiles < cus ? ntiles : cus);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kLinWaves), smem, s, a);
     return hipGetLastError();
 }
 
