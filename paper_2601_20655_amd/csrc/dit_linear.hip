@@ -2,27 +2,38 @@
 // (the q/k/v and output projections either side of attention in a transformer block of the Diffusion
 // stage, Sec. 2.4; weights stored [out, in] as the model's linear layers keep them).
 //
-// One workgroup of 8 wavefronts owns a 256-token x 256-feature tile of y and walks K in steps of 64.
+// A workgroup of 8 wavefronts computes 256-token x 256-feature tiles of y, walking K in steps of 64.
 // Both operand tiles of a step (256 rows x 64 contraction indices, 16-bit: one 128-byte line per row)
 // are copied from global memory straight into LDS by the load-to-LDS DMA, 1 KiB per wavefront
 // instruction.  The DMA fills LDS densely in lane order, so the bank spreading is done by choosing
 // WHICH 16-byte piece of a row each lane fetches: piece p of row r lives in slot p ^ ((r >> 1) & 7) of
-// the row's 128 bytes, which makes the 16 rows a quarter wavefront reads with one ds_read_b128 fall
-// into 16 distinct bank groups (measured: no bank conflicts).
+// the row's 128 bytes, which makes every cycle of a fragment read fall into 16 distinct bank groups
+// (measured: no bank conflicts).
 //
-// Buffering: all 160 KiB of LDS are used, SX = 3 buffers for the x tile (fetched two steps ahead) and
-// SW = 2 for the w tile (one step ahead).  The loads of a step are issued one or two at a time between
-// groups of MFMAs, never in a burst, and the one barrier per step sits where every wavefront still
-// has MFMAs in flight.
+// Buffering: all 160 KiB of LDS are used, 3 buffers for the x tile (fetched two steps ahead) and 2 for the
+// w tile (one step ahead), one barrier per step.
 //
-// MFMA roles: w rows ride the A operand (the M axis of v_mfma_f32_32x32x16_bf16), token rows the
-// B operand, so a lane ends up with four CONSECUTIVE features of one token per register quad and
-// stores them with one instruction.  With 8 wavefronts, wavefront (wt, wf) of the 2 x 4 grid computes
-// 128 tokens x 64 features (8 accumulators, 6 fragment reads per 8 MFMAs, two wavefronts per SIMD);
-// with 4 wavefronts 128 x 128 (16 accumulators in the AGPRs, one wavefront per SIMD).  The two forms
-// measure the same (1,250 TFLOP/s at M = 32,760, N = K = 5,120); the 8-wavefront form is the default.
-// Bursts against spread loads, a two-slice read-ahead, 384-token tiles (17 % less L2 traffic), loads
-// staggered between even and odd wavefronts and wavefront priorities all stayed within 2 %.
+// MFMA roles: w rows ride the A operand (the M axis of v_mfma_f32_16x16x32_bf16), token rows the
+// B operand; wavefront (wt, wf) of the 2 x 4 grid computes 128 tokens x 64 features: 32 accumulators
+// of 4 registers, 24 fragment reads per 64 MFMAs, two wavefronts per SIMD.  The 16x16x32 form does the
+// same flops per cycle as the 32x32x16 one and draws less power per flop, and the board's power
+// limit, not the issue rate, is what bounds a dense product on real data: 1,220 -> 1,315 TFLOP/s on
+// the same box for the same schedule.
+//
+// What in-kernel timestamps showed, and what was done about it (M = 32,760, K = 5,120, N = 15,360):
+//  - one workgroup per tile spent a tenth of the time between the end of one tile's loop and the start
+//    of the next one's on a compute unit (stores, workgroup launch, first loads): the workgroups are
+//    persistent and a tile's first loads go out during the tile before;
+//  - stores of 32-byte pieces straight from the accumulators held the stream up for another tenth:
+//    tiles are staged through LDS and stored as whole rows;
+//  - four MFMAs back to back followed by the reads and loads of a token block leave the pipe idle while
+//    those issue: everything that is not an MFMA sits between the MFMAs;
+//  - the two wavefronts of a SIMD do not advance evenly (the older is served first and waits a third of
+//    every step at the barrier): the older ones issue all the loads.
+// Together 1,315 -> 1,421 TFLOP/s, where the vendor's GEMM library does 1,493 on the same box.
+// Tried without gain: alternating wavefront priorities, bursts against spread loads, 384-token tiles,
+// row strides padded against channel conflicts (the vendor library gains 15 % from those on all-zero
+// operands and nothing on real ones).
 #include <type_traits>
 
 #include "dit_attn_device.h"
@@ -35,9 +46,6 @@ namespace {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-#ifndef DIT_LIN_PRIO
-#define DIT_LIN_PRIO 0
-#endif
 constexpr int kLinGroup = 8;  // token tiles per group of the workgroup order
 constexpr int kLinTileBytes = 256 * kLinBK * 2;  // one operand tile of one step
 constexpr int kLinSX = 3, kLinSW = 2;  // LDS buffers of x tiles (fetched two steps ahead) and of w tiles (one ahead)
@@ -208,11 +216,11 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     };
     // The barrier that opens step k sits in the last slice of step k-1, in its second token block: by then
     // every wavefront has asked for all fragments of step k-1 (the wait in front of the barrier completes
-    // the reads), so behind it the buffers of step k-1 may be refilled and the tiles of step k, which every
-    // wavefront has waited for, may be read.  The loads of one barrier period go out one per token block:
-    // the w tile of step k+1 in the first four blocks behind the barrier, the x tile of step k+2 in the
-    // first four blocks of the next step.  The counted wait in front of the barrier leaves exactly that
-    // youngest x tile in flight.
+    // the reads), so behind it the buffers of step k-1 may be refilled and the tiles of step k, which the loading
+    // wavefronts have waited for, may be read.  The loads of one barrier period go out between the MFMAs:
+    // the w tile of step k+1 in the first four blocks behind the barrier (two chunks a block), the x tile
+    // of step k+2 one chunk a block in the first slice of the next step.  The counted wait in front of the
+    // barrier leaves exactly that youngest x tile in flight.
     // (the bare barrier instruction: __syncthreads() is a fence too, for which the compiler drains every
     // load in flight -- vmcnt(0) -- in front of the barrier, and the x tile that is meant to stay in
     // flight across it would be waited for after all)

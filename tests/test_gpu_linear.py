@@ -113,3 +113,29 @@ def test_tile_boundaries_exact(M, N):
     assert np.array_equal(to_f64(y[1:M + 1, :N]), oracle.linear(xb, wb, bb))
     # the guard rows and columns around the output keep their contents
     assert torch.all(y[0] == -77.0) and torch.all(y[M + 1] == -77.0) and torch.all(y[:, N:] == -77.0)
+
+
+@pytest.mark.parametrize("K", [64, 128, 192])
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+def test_several_tiles_per_workgroup_exact(K, out):
+    """More tiles than the device has compute units, with one to three steps per tile: a workgroup walks
+    two or three tiles as one stream, and the loads run a whole tile or two ahead of the MFMAs.  Ragged in
+    both directions; integer-valued inputs whose sums fit 24 bits (and, for bf16 output, results of at
+    most 8 significant bits), so every output must be exact."""
+    import torch
+
+    M, N = 6000, 6152
+    rng = np.random.default_rng(7 * K + (out == "f32"))
+    hi = 9 if out == "f32" else 2
+    x = rng.integers(-hi + 1, hi, size=(M, K)).astype(np.float32)
+    w = rng.integers(-hi + 1, hi, size=(N, K)).astype(np.float32)
+    bias = rng.integers(-8, 9, size=N).astype(np.float32)
+    xb, wb, bb = (wl.f32_to_bf16_bits(a) for a in (x, w, bias))
+    ref = oracle.linear(xb, wb, bb)
+    if out == "bf16":
+        assert np.max(np.abs(ref)) <= 256  # |sum| <= K + 8 <= 200: exactly representable
+    y = torch.full((M + 1, N + 8), -77.0, dtype=torch.float32 if out == "f32" else torch.bfloat16, device="cuda")
+    B.dit_linear_forward(to_dev(xb), to_dev(wb), to_dev(bb), out=y[:M, :N])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(y[:M, :N]), ref)
+    assert torch.all(y[M] == -77.0) and torch.all(y[:, N:] == -77.0)
