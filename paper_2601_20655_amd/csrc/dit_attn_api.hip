@@ -101,12 +101,15 @@ bool self_attn_uses_mfma16(const Flags& fl) {
 }
 
 // Attention kernel launch, bracketed by the caller's timing events when the hook is set.
-dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused, bool mfma16, hipStream_t s) {
+dit_status run_attn(const dit::AttnArgs& aa, int D, const Flags& fl, bool fused, bool mfma16, hipStream_t s,
+                    bool chain16 = false) {
     const bool timed = g_ev_before && g_ev_after;
     hipError_t e;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
     if (aa.tile_count_a) {
         e = dit::launch_attn_split(aa, D, fl.qk_op, fl.pv_op, s);
+    } else if (chain16) {
+        e = dit::launch_attn_pipe16_chain(aa, D, fl.qk_op, fl.pv_op, fl.nw, s);
     } else if (mfma16) {
         e = dit::launch_attn_pipe16(aa, D, fl.qk_op, fl.pv_op, fl.nw, s);
     } else if (!fused && !fl.simple) {
@@ -343,6 +346,7 @@ dit_status plan_varlen(const dit_varlen_attn_params* p, VarlenPlan* pl) {
 
 struct CrossPlan {
     Flags fl;
+    bool chain16;  // the chained 16x16x32 kernel (joint softmax, default)
     int nKT, nQT;
     int split, nTA;  // decoupled form: first key of the second sequence, tiles of the first (0, 0: joint)
     size_t mask_off, list_off, count_off, count_a_off, keysrc_off, tiles_off, rstd_off, total;
@@ -371,8 +375,16 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     if (pl->fl.nw == 8 && pl->fl.qb == 2) return DIT_ERR_UNSUPPORTED;
     // the pipelined kernel keeps the list of non-empty tiles in the 64 lanes of a wavefront
     if (pl->fl.pipelined && pl->nKT > 64) return DIT_ERR_UNSUPPORTED;
-    if (!pl->fl.pipelined) pl->fl.simple = true;  // cross-attention default: the plain kernel
-    if (pl->fl.simple || pl->fl.qb == 2) {
+    // Default for one joint softmax: the pipelined 16x16x32 kernel, each workgroup chaining several query tiles.
+    // The plain kernel serves the decoupled form and DIT_FLAG_SIMPLE_SCHEDULE (also with DIT_FLAG_MFMA_32X32
+    // or 64 rows per wavefront); DIT_FLAG_PIPELINED_SCHEDULE asks for the listed 32x32x16 pipelined kernel.
+    // (the chained kernel takes 16-bit query rows as they are: fp32 rows or a normalisation go to the plain kernel)
+    pl->chain16 = pl->split == 0 && !pl->fl.simple && !pl->fl.pipelined && !pl->fl.mfma32 && pl->fl.qb == 1 &&
+                  p->in_dtype == DIT_BF16 && p->norm.mode == DIT_NORM_NONE;
+    if (!pl->fl.pipelined && !pl->chain16) pl->fl.simple = true;
+    if (pl->chain16) {
+        if (pl->fl.nw == 0) pl->fl.nw = (int64_t)((p->Lq + 255) / 256) * p->B * p->H >= 512 ? 8 : 4;
+    } else if (pl->fl.simple || pl->fl.qb == 2) {
         pl->fl.nw = 4;
     } else if (pl->fl.nw == 0) {
         // few key tiles per query tile: two small workgroups per CU overlap each other's
@@ -528,6 +540,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.split = pl.split;
     pa.nTA = pl.nTA;
     pa.tab = nullptr;
+    pa.v_layout = pl.chain16 ? 1 : 0;
     pa.B = p->B; pa.H = p->H; pa.Lk = p->Lk; pa.nKT = pl.nKT;
     pa.in_f32 = p->in_dtype == DIT_F32;
     pa.sk_b = p->sk.batch; pa.sk_t = p->sk.token; pa.sk_h = p->sk.head;
@@ -556,7 +569,7 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     aa.so_b = p->so.batch; aa.so_t = p->so.token; aa.so_h = p->so.head;
     aa.qscale = scale * dit::kLog2e;
     aa.qn = qn;
-    return run_attn(aa, p->D, pl.fl, false, false, s);
+    return run_attn(aa, p->D, pl.fl, false, false, s, pl.chain16);
 }
 
 size_t dit_attn_varlen_workspace_bytes(const dit_varlen_attn_params* p) {

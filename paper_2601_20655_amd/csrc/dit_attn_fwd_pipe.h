@@ -75,6 +75,8 @@ struct PipeView {
     int64_t lse_off;       // index of row 0 in lse
     int64_t stat_off;      // index of row 0 in the per-token normalisation table
     int Hg, Wg;            // latent grid of this sequence
+    int qt_count;          // chained form (attn_pipe16_body<.., CHAIN>): consecutive query tiles taken, from qt
+    uint64_t last_mask;    // chained form: key mask of the sequence's last tile
 };
 
 // NW = wavefronts per workgroup (4 or 8); the workgroup owns NW*QB*32 query rows that share every

@@ -71,7 +71,24 @@ __device__ __forceinline__ float q_row_rstd16(const NormArgs& n, const void* q, 
 
 // NW = wavefronts per workgroup (4 or 8); a wavefront owns 32 query rows (two blocks of 16), the workgroup's
 // NW * 32 rows share every K/V tile in LDS.
-template <int D, int QK_OP, int PV_OP, int NW>
+// The chained form keeps, behind the tile buffers, one area per wavefront the size of its 32 query rows in 16
+// bits.  The rows of the NEXT query tile are copied into it (global -> LDS) while the current one is in its loop;
+// at the boundary they are converted into operand registers, and the area then serves as the staging area of the
+// output rows (below) before the rows after next are requested.  Held in registers across the store instead, the
+// raw rows pushed the operand registers into scratch memory, eight reloads waited for one by one per query tile.
+template <int D>
+constexpr int chain_stage_bytes() { return 32 * D * 2; }
+template <int D, int NW>
+constexpr int chain_lds_bytes() { return 4 * TileGeom<D>::PART_KIB * 1024 + NW * chain_stage_bytes<D>(); }
+
+// CHAIN: the workgroup takes pv.qt_count consecutive query tiles of its (sequence, head), one after the other,
+// against ONE stream of key tiles that wraps around at the end of the sequence: the tiles of the next query
+// tile's first steps arrive during the last steps of the one before, and between two query tiles there is
+// only the store of the output, the conversion of the next query rows (requested before the store) and the
+// first score tile.  For sequences of a few key tiles (cross-attention: 8 to 13) the start-up of a workgroup
+// -- query rows and first tiles from memory, one after the other -- is otherwise as long as its loop.  The
+// chained form keeps every wavefront on the same side of the barrier (no stagger).
+template <int D, int QK_OP, int PV_OP, int NW, bool CHAIN = false>
 __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeView& pv) {
     using G = TileGeom<D>;
     constexpr int NKS = D / 32;        // MFMAs of one score chain
@@ -83,7 +100,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     static_assert(G::PART_KIB - NW * NI == 2, "two odd pieces per tile part");
     static_assert(QK_OP != OP_FP8, "16-bit score operands only");
 
-    constexpr bool STAG = pipe_staggered<NW>();
+    constexpr bool STAG = pipe_staggered<NW>() && !CHAIN;
     constexpr int VST = STAG ? 3 : 2;  // V^T buffers
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     uint8_t* const kbuf = smem;  // K buffers 0/1, then the V buffers
@@ -93,7 +110,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, g4 = lane >> 4;
-    const int qt = pv.qt;
+    int qt = pv.qt;
     RopeGeom rg = a.rg;
     rg.Hg = pv.Hg;
     rg.Wg = pv.Wg;
@@ -103,30 +120,68 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     u32x4 Qf[2][NKS];
     u32x4 qraw[2][NKS];
     int qrow[2];
-    if (!a.in_f32) {
+    uint8_t* const qarea = smem + 4 * G::K_BYTES + wave * chain_stage_bytes<D>();  // chained form only
+    constexpr int QPR = D / 8;  // 16-byte pieces per 16-bit query row
+    // chained form: this wavefront's 32 rows of query tile `qtile` -> its area, piece p of row r in slot
+    // p ^ (r % QPR) (the copy fills LDS in lane order, so the swizzle is in which piece a lane fetches)
+    // (In the three pieces of code that run once per query tile of a chain -- this copy, the conversion and the
+    // store -- every per-lane offset is worked out from a lane number the compiler cannot see through: left to
+    // itself it works them all out ahead of the chain, cannot keep them in registers through the key loop, and
+    // reloads some seventy of them from scratch memory at every query tile.)
+    auto opaque_lane = [&]() {
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        return l;
+    };
+    auto request_q_lds = [&](int qtile) {
+        const int ln = opaque_lane();
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int row = qt * BQ + wave * 32 + qb * 16 + i16;
+        for (int k = 0; k < 32 * QPR / 64; ++k) {
+            const int r = k * (64 / QPR) + ln / QPR, slot = ln % QPR;
+            const int row = qtile * BQ + wave * 32 + r;
             const int qr = row < pv.Lq ? row : pv.Lq - 1;
-            const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks)
-                qraw[qb][ks] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + base +
-                                                              8 * (4 * ks + g4));
+            const uint16_t* src = static_cast<const uint16_t*>(a.q) + pv.q_off + (int64_t)qr * a.sq_t +
+                                  8 * (slot ^ (r & (QPR - 1)));
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(qarea + k * 1024), 16, 0, 0);
         }
-    }
+    };
+    auto request_q = [&](int qtile) {
+        if constexpr (CHAIN) {
+            request_q_lds(qtile);
+        } else if (!a.in_f32) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const int row = qtile * BQ + wave * 32 + qb * 16 + i16;
+                const int qr = row < pv.Lq ? row : pv.Lq - 1;
+                const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks)
+                    qraw[qb][ks] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + base +
+                                                                  8 * (4 * ks + g4));
+            }
+        }
+    };
+    request_q(qt);
 
     // ---- tile streaming (as in attn_pipe_body): a tile part is PART_KIB pieces of 1 KiB; wavefront w moves
     // pieces w, w+NW, ... of both parts; the two odd pieces of the K part go to wavefronts 0 and 1, those of
     // the V part to wavefronts 2 and 3.
     const uint8_t* const tiles = pv.tiles;  // wavefront-uniform
-    const uint32_t lane_off = lane * 16;
     const int n_steps = pv.nKT;
     const int last = n_steps - 1;
     const int tail = pv.Lk - (pv.nKT - 1) * kBK;  // valid keys of the last tile (1..64)
-    auto tile_of = [&](int j) -> int { return j < last ? j : last; };  // past the end: the last tile again
+    // past the end: the last tile again; chained: the stream wraps around to the sequence's first tiles
+    auto tile_of = [&](int j) -> int {
+        if constexpr (CHAIN) {
+            j = j >= n_steps ? j - n_steps : j;
+            return j >= n_steps ? j - n_steps : j;  // j <= n_steps + 1, and a sequence may have one tile
+        } else {
+            return j < last ? j : last;
+        }
+    };
     auto mask_of = [&](int j) -> uint64_t {
-        return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
+        if constexpr (CHAIN) return j == last ? pv.last_mask : ~0ull;
+        else return (j == last && tail < kBK) ? ((1ull << tail) - 1ull) : ~0ull;
     };
     constexpr int NDMA = 2 * NI + 1;
     auto dma_piece = [&](int i, int tk, int kb_, int tv, int vb_) {
@@ -134,6 +189,10 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
         const uint8_t* vsrc = tiles + (size_t)tv * G::TILE_BYTES + G::K_BYTES;
         uint8_t* kdst = kbuf + kb_ * G::K_BYTES;
         uint8_t* vdst = vbuf + vb_ * G::V_BYTES;
+        // (chained form: the empty statement keeps the compiler from carrying per-lane 64-bit addresses through
+        // the loop, two registers each, which it spilled there; uniform base + 32-bit lane offset instead)
+        uint32_t lane_off = lane * 16;
+        if constexpr (CHAIN) asm volatile("" : "+v"(lane_off));
         if (i < 2 * NI) {
             const int c = (wave + NW * (i >> 1)) * 1024;
             if ((i & 1) == 0) {
@@ -162,15 +221,18 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     f32x16 O[NOG][2];
     f32x4 negm[2];  // every element = -m_run: the accumulator a score MFMA chain starts from
     float m_run[2], l_run[2];
+    auto reset_state = [&]() {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        m_run[qb] = 0.f;
-        l_run[qb] = 0.f;
+        for (int qb = 0; qb < 2; ++qb) {
+            m_run[qb] = 0.f;
+            l_run[qb] = 0.f;
 #pragma unroll
-        for (int og = 0; og < NOG; ++og)
+            for (int og = 0; og < NOG; ++og)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) O[og][qb][r] = 0.f;
-    }
+                for (int r = 0; r < 16; ++r) O[og][qb][r] = 0.f;
+        }
+    };
+    reset_state();
 
     // Rows 4..11 of every 16 hold neighbouring 16-byte chunks in swapped pairs (pack_tile, layout 1): with that,
     // the lanes the LDS serves in one cycle of a 128-bit read fall into distinct banks (plain rows gave two-way
@@ -265,7 +327,9 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
 #ifndef DIT_PIPE16_LA
 #define DIT_PIPE16_LA 6
 #endif
-    constexpr int LA = DIT_PIPE16_LA;  // LDS fragment reads issued this many fragments ahead of their MFMAs
+    // LDS fragment reads issued this many fragments ahead of their MFMAs (chained form: one fewer, which is what
+    // keeps its loop free of spilled registers)
+    constexpr int LA = CHAIN ? DIT_PIPE16_LA - 1 : DIT_PIPE16_LA;
     constexpr int NCH = 16;            // softmax slices: two scores -> one dword of P
     constexpr int CPA = NCH / NKF;     // slices per K' fragment (pair of score MFMAs): 1 at d128, 2 at d64
     constexpr int CPB = NCH / NVF;     // maxima slices per V^T fragment
@@ -279,7 +343,14 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
 
     const bool late = STAG && wave >= NW / 2;
     auto next_vslot = [](int s) { return s + 1 == VST ? 0 : s + 1; };
-    auto dma_interval = [&](int j, int vs) { dma_tiles(tile_of(j + 2), j & 1, tile_of(j + 1), next_vslot(vs)); };
+    // chained: parity of the number of key-tile steps taken before this query tile (the K' buffers alternate
+    // along the whole stream, not per query tile)
+    int par = 0;
+    auto kslot = [&](int j) -> int {
+        if constexpr (CHAIN) return (j + par) & 1;
+        else return j & 1;
+    };
+    auto dma_interval = [&](int j, int vs) { dma_tiles(tile_of(j + 2), kslot(j), tile_of(j + 1), next_vslot(vs)); };
 
     // One pipelined iteration: Sc holds the relative scores of tile j (all <= threshold), Sn receives those of
     // tile j + 1.  vs = j % VST, the buffer V^T(j) sits in.  LATE (compile-time) selects where the barrier sits.
@@ -289,7 +360,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     auto iteration = [&](auto late_tag, auto masked_tag, f32x16 (&Sc)[2], f32x16 (&Sn)[2], int j, int vs) {
         constexpr bool LATE = decltype(late_tag)::value;
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint8_t* kt = kbuf + ((j + 1) & 1) * G::K_BYTES + kread_off;
+        const uint8_t* kt = kbuf + kslot(j + 1) * G::K_BYTES + kread_off;
         const uint8_t* vt = vbuf + vs * G::V_BYTES + vread_off;
 
         if constexpr (STAG && DIT_PIPE_PRIO == 1) __builtin_amdgcn_s_setprio(1);
@@ -420,35 +491,66 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
         dma_tiles(t1, 1, 0, 1);  // K'(1); its V part lands in a buffer iteration 0 refills anyway
     }
 
+    int vs_run = 0;  // chained: the V^T buffer of the stream's current step
+    const int n_qt = CHAIN ? pv.qt_count : 1;
+    // chained form: the rows in this wavefront's area -> operand registers.  It takes 16-bit query rows as they
+    // are (the host sends anything else -- fp32 rows, a normalisation, a rotation -- to the other kernels):
+    // nothing here but widen, scale, round.
+    auto convert_q_area = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the copy into the area (long done, except at the start)
+        const int ln = opaque_lane();
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                float x[8];
+                const int r = 16 * qb + (ln & 15);
+                widen8(*reinterpret_cast<const u32x4*>(qarea + r * (D * 2) + (((4 * ks + (ln >> 4)) ^ (r & (QPR - 1))) << 4)), x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
+                Qf[qb][ks] = pack8<QK_OP>(x);
+            }
+    };
+    for (int it = 0; it < n_qt; ++it) {  // one pass unless chained
+    if constexpr (CHAIN) {
+        // the operands of this query tile were converted at the end of the one before; its area is free for
+        // the rows of the next one, which arrive while this one is in its loop
+        if (it == 0) convert_q_area();
+        else reset_state();
+        if (it + 1 < n_qt) request_q(qt + 1);
+    }
     // ---- Q: rotate, fold scale*log2(e), round once, keep as B operands ----
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         qrow[qb] = qt * BQ + wave * 32 + qb * 16 + i16;
         const int qr = qrow[qb] < pv.Lq ? qrow[qb] : pv.Lq - 1;
         const int64_t base = pv.q_off + (int64_t)qr * a.sq_t;
-        int pt = 0, ph = 0, pw = 0;
-        if (a.tab) token_pos(qr, rg, pt, ph, pw);
-        float rs = 1.f;
-        if (a.qn.mode) rs = q_row_rstd16<D>(a.qn, a.q, base, a.in_f32, g4, pv.stat_off + qr);
+        if constexpr (!CHAIN) {
+            int pt = 0, ph = 0, pw = 0;
+            if (a.tab) token_pos(qr, rg, pt, ph, pw);
+            float rs = 1.f;
+            if (a.qn.mode) rs = q_row_rstd16<D>(a.qn, a.q, base, a.in_f32, g4, pv.stat_off + qr);
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const int c = 4 * ks + g4;
-            float x[8];
-            if (a.in_f32) load8(a.q, base + 8 * c, 1, x);
-            else widen8(qraw[qb][ks], x);
-            if (a.qn.mode) norm8(x, a.qn, rs, pv.h, D, c);
-            if (a.tab) rope8(x, c, rg, a.tab, pt, ph, pw);
+            for (int ks = 0; ks < NKS; ++ks) {
+                const int c = 4 * ks + g4;
+                float x[8];
+                if (a.in_f32) load8(a.q, base + 8 * c, 1, x);
+                else widen8(qraw[qb][ks], x);
+                if (a.qn.mode) norm8(x, a.qn, rs, pv.h, D, c);
+                if (a.tab) rope8(x, c, rg, a.tab, pt, ph, pw);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
-            Qf[qb][ks] = pack8<QK_OP>(x);
+                for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
+                Qf[qb][ks] = pack8<QK_OP>(x);
+            }
         }
     }
 
     if (n_steps > 0) {
         // scores of tile 0 become the first running maximum
-        dma_wait_and_sync();
+        // (chained, later query tiles: the tiles are there, and the barrier that ended the step before has been passed)
+        if (!CHAIN || it == 0) dma_wait_and_sync();
         f32x16 S0[2], S1[2];
-        qk_tile(S0, 0);
+        qk_tile(S0, kslot(0));
         __syncthreads();  // every wavefront has read K'(0) before iteration 0 streams K'(2) over it
         if constexpr (STAG) {
             if (late) dma_interval(0, 0);
@@ -465,7 +567,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
         }
 
         auto key_loop = [&](auto late_tag) {
-            int j = 0, vs = 0;
+            int j = 0, vs = CHAIN ? vs_run : 0;
             // iteration j produces the scores of tile j + 1: unmasked while j + 1 < last
             for (; j + 3 < n_steps; j += 2) {
                 iteration(late_tag, std::false_type{}, S0, S1, j, vs);
@@ -484,7 +586,11 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
                 vs = next_vslot(vs);
                 ++j;
             }
-            if (j < n_steps) iteration(late_tag, std::true_type{}, S0, S1, j, vs);
+            if (j < n_steps) {
+                iteration(late_tag, std::true_type{}, S0, S1, j, vs);
+                vs = next_vslot(vs);
+            }
+            if constexpr (CHAIN) vs_run = vs;
         };
         if (late) {
             key_loop(std::true_type{});
@@ -495,6 +601,68 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     }
 
     // ---- epilogue: the lane holds channels 16 cb + 4 g + r of its two queries ----
+    if constexpr (CHAIN) {
+        // Stored from the accumulators a wavefront instruction writes sixteen 32-byte pieces of sixteen rows; with
+        // an output as large as the input and a loop of eight steps that was a third of a query tile's time.  The
+        // wavefront passes its 32 rows through a staging area of its own behind the tile buffers, STG bytes at a
+        // time, and stores whole rows, 16 bytes a lane (pieces of a staged row swizzled with the row number).
+        constexpr int STG = chain_stage_bytes<D>();
+        uint8_t* const region = qarea;
+        const int ln = opaque_lane();
+        const int li = ln & 15, lg = ln >> 4;
+        float inv[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float l = l_run[qb];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            inv[qb] = l > 0.f ? 1.0f / l : 0.f;
+            const int row = qt * BQ + wave * 32 + qb * 16 + li;
+            if (a.lse && lg == 0 && row < pv.Lq) {
+                const float v = l > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
+                a.lse[pv.lse_off + row] = v;
+            }
+        }
+        auto stage_and_store = [&](auto es_tag) {
+            constexpr int ES = decltype(es_tag)::value;  // bytes per output element
+            constexpr int RB = D * ES;                   // bytes per staged row
+            constexpr int PR = RB / 16;                  // 16-byte pieces per row
+            constexpr int RPP = STG / RB < 16 ? STG / RB : 16;  // rows per pass: at most one 16-row block
+            static_assert(RPP >= 1 && 16 % RPP == 0 && PR <= 64 && 64 % PR == 0 && (RPP * RB) % 1024 == 0,
+                          "staging geometry");
+            const int row0 = qt * BQ + wave * 32;
+#pragma unroll
+            for (int pass = 0; pass < 32 / RPP; ++pass) {
+                const int qb = pass * RPP / 16;
+                const int rr = li - (pass * RPP) % 16;  // this lane's row within the pass, if it has one
+                if (rr >= 0 && rr < RPP) {
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb) {
+                        const int e = 4 * (cb % 4);
+                        const float o0 = O[cb / 4][qb][e] * inv[qb], o1 = O[cb / 4][qb][e + 1] * inv[qb];
+                        const float o2 = O[cb / 4][qb][e + 2] * inv[qb], o3 = O[cb / 4][qb][e + 3] * inv[qb];
+                        const int col = (16 * cb + 4 * lg) * ES;
+                        uint8_t* const dst = region + rr * RB + (((col >> 4) ^ (rr & (PR - 1))) << 4) + (col & 15);
+                        if constexpr (ES == 4) *reinterpret_cast<float4*>(dst) = make_float4(o0, o1, o2, o3);
+                        else *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<OP_BF16>(o0, o1), pack2<OP_BF16>(o2, o3));
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < RPP * RB / 1024; ++k) {
+                    const int r = k * (64 / PR) + ln / PR, pc = ln % PR;
+                    const uint4 v = *reinterpret_cast<const uint4*>(region + r * RB + ((pc ^ (r & (PR - 1))) << 4));
+                    const int row = row0 + pass * RPP + r;
+                    if (row < pv.Lq)
+                        *reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.out) +
+                                                  (pv.o_off + (int64_t)row * a.so_t) * ES + pc * 16) = v;
+                }
+            }
+        };
+        // the next query tile's operands out of the area, then the area is the staging area
+        if (it + 1 < n_qt) convert_q_area();
+        if (a.out_f32) stage_and_store(std::integral_constant<int, 4>());
+        else stage_and_store(std::integral_constant<int, 2>());
+    } else {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         float l = l_run[qb];
@@ -522,6 +690,12 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
             }
         }
     }
+    }
+    if constexpr (CHAIN) {
+        ++qt;
+        par ^= n_steps & 1;
+    }
+    }  // query tiles
 }
 
 // One sequence per batch entry, all of the same length.
@@ -576,6 +750,59 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_fwd_pipe16_varlen_kernel(cons
     pv.Hg = rq.Hg;
     pv.Wg = rq.Wg;
     attn_pipe16_body<D, QK_OP, PV_OP, NW>(a, pv);
+}
+
+// Cross-attention with one joint softmax per request: workgroups chain `qch` query tiles of one (request, head).
+// The pre-pack leaves a request's attending keys densely in its tiles 0 .. count-1 (key_compact_kernel; without a
+// byte mask all keys attend), so only the last of them is partial; count and that tile's mask come from the
+// workspace.  Workgroup order: request fastest, then chunk, then head, so that the workgroups an XCD holds at a
+// time share a handful of (request, head) tile sets in its L2 and requests of different lengths are interleaved.
+template <int D, int QK_OP, int PV_OP, int NW>
+__global__ void __launch_bounds__(64 * NW, 2) attn_fwd_pipe16_chain_kernel(const AttnArgs a, int qch) {
+    const int logical = xcd_contiguous_block();
+    const int nch = (a.nQT + qch - 1) / qch;
+    PipeView pv;
+    pv.b = logical % a.B;
+    const int rest = logical / a.B;
+    const int ch = rest % nch;
+    pv.h = rest / nch;
+    pv.qt = ch * qch;
+    pv.qt_count = a.nQT - pv.qt < qch ? a.nQT - pv.qt : qch;
+    const int bh = pv.b * a.H + pv.h;
+    const int count = a.tile_count[pv.b];
+    pv.Lq = a.Lq;
+    pv.Lk = a.Lk;
+    pv.nKT = count;
+    pv.last_mask = count > 0 ? a.tile_mask[(size_t)pv.b * a.nKT + count - 1] : 0ull;
+    pv.tiles = a.tiles + (size_t)bh * a.nKT * TileGeom<D>::TILE_BYTES;
+    pv.q_off = (int64_t)pv.b * a.sq_b + (int64_t)pv.h * a.sq_h;
+    pv.o_off = (int64_t)pv.b * a.so_b + (int64_t)pv.h * a.so_h;
+    pv.lse_off = ((int64_t)pv.b * a.H + pv.h) * a.Lq;
+    pv.stat_off = (int64_t)pv.b * a.Lq;
+    pv.Hg = a.rg.Hg;
+    pv.Wg = a.rg.Wg;
+    attn_pipe16_body<D, QK_OP, PV_OP, NW, true>(a, pv);
+}
+
+template <int D, int QK_OP, int PV_OP, int NW>
+hipError_t launch_attn_pipe16_chain_inst(const AttnArgs& a, hipStream_t s) {
+    auto kern = attn_fwd_pipe16_chain_kernel<D, QK_OP, PV_OP, NW>;
+    constexpr int smem = chain_lds_bytes<D, NW>();
+    static std::atomic<uint64_t> attr_set{0};
+    hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
+    if (e != hipSuccess) return e;
+    // query tiles per workgroup: long enough chains that a workgroup's start-up is a small part of its life,
+    // enough workgroups (about five per compute unit) that requests of different lengths even out
+    int dev = 0, cus = 0;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    const int64_t total_qt = (int64_t)a.nQT * a.B * a.H;
+    int64_t qch = total_qt / (5 * (int64_t)(cus > 0 ? cus : 1));
+    qch = qch < 1 ? 1 : (qch > 16 ? 16 : qch);
+    const int64_t nch = (a.nQT + qch - 1) / qch;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(nch * a.B * a.H)), dim3(64 * NW), smem, s, a, (int)qch);
+    return hipGetLastError();
 }
 
 template <int D, int QK_OP, int PV_OP, int NW>

@@ -162,6 +162,7 @@ hipError_t launch_prepack(const PackArgs& a, int D, int qk_op, int pv_op, hipStr
 hipError_t launch_attn_pipe16(const AttnArgs& a, int D, int qk_op, int pv_op, int nw, hipStream_t s);
 hipError_t launch_attn_pipe16_varlen(const AttnArgs& a, const VarlenTable& vt, int D, int qk_op, int pv_op, int nw,
                                      hipStream_t s);
+hipError_t launch_attn_pipe16_chain(const AttnArgs& a, int D, int qk_op, int pv_op, int nw, hipStream_t s);
 // before launch_prepack when a.valid is set: the valid keys of every batch entry (of each key group) in
 // ascending order, densely over the tile slots
 hipError_t launch_key_compact(const PackArgs& a, hipStream_t s);

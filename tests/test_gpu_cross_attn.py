@@ -24,6 +24,8 @@ SHAPES = {
     "pipe_qb1_4w": B.DIT_FLAG_PIPELINED_SCHEDULE | B.DIT_FLAG_SMALL_WORKGROUP,
     "pipe_qb1_8w": B.DIT_FLAG_PIPELINED_SCHEDULE | B.DIT_FLAG_BIG_WORKGROUP,
     "pipe_qb2_4w": B.DIT_FLAG_PIPELINED_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
+    "chain_4w": B.DIT_FLAG_SMALL_WORKGROUP,
+    "chain_8w": B.DIT_FLAG_BIG_WORKGROUP,
     "simple_qb1": B.DIT_FLAG_SIMPLE_SCHEDULE,
     "simple_qb2": B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_WIDE_QTILE,
 }
@@ -177,3 +179,31 @@ def test_scattered_key_masks_are_compacted(split, shape):
     torch.cuda.synchronize()
     ref2 = oracle.cross_attn_decoupled(q2, k, v, split, valid) if split else oracle.cross_attn(q2, k, v, valid)
     compare(to_f64(out2), ref2, what="scattered masks, resident call")
+
+
+@pytest.mark.parametrize("D,shape", [(64, "chain_4w"), (128, "chain_4w"), (128, "chain_8w")])
+def test_chained_query_tiles_all_rows(D, shape):
+    """Enough query tiles that the default kernel's workgroups take two or three in a row (about five
+    workgroups per compute unit), with requests of 0, 1, 2 and 3 key tiles -- odd and even numbers of steps,
+    so that the wrap-around of the key-tile stream starts the next query tile in either K' buffer -- and a
+    ragged last query tile.  Every row of every request against the oracle, output and log-sum-exp."""
+    import torch
+
+    # 202 query tiles x 4 requests x 6 heads over 256 compute units: chains of three (the last one shorter);
+    # 151 x 4 x 6: chains of two
+    Lq = 128 * 201 + 37 if shape == "chain_4w" else 256 * 150 + 37
+    H = 6
+    cfg = dict(B=4, Lq=Lq, n_text=150, n_image=42, H=H, D=D, dtype="bf16", min_text=5, seed=77 + D)
+    q, k, v, valid, _ = wl.cross_attn_inputs(cfg)
+    valid[:] = 0
+    valid[1, 3:43] = 1                   # 40 keys: one tile
+    valid[2, 0:150:2] = 1                # 75 scattered keys + 25 below: two tiles
+    valid[2, 150:175] = 1
+    valid[3, :] = 1                      # 192 keys: three full tiles
+    ref, ref_lse = oracle.cross_attn(q, k, v, valid, want_lse=True)
+    out, lse = run_cross(q, k, v, valid, out_dtype=torch.float32, want_lse=True, flags=SHAPES[shape])
+    o, l = to_f64(out), to_f64(lse)
+    assert np.all(o[0] == 0.0) and np.all(np.isneginf(l[0]))
+    for b in (1, 2, 3):
+        compare(o[b], ref[b], what="chained, request %d, %s" % (b, shape))
+        assert np.allclose(l[b], ref_lse[b], rtol=0, atol=2e-3)
