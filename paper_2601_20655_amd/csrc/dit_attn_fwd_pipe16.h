@@ -329,7 +329,10 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
 #endif
     // LDS fragment reads issued this many fragments ahead of their MFMAs (chained form: one fewer, which is what
     // keeps its loop free of spilled registers)
-    constexpr int LA = CHAIN ? DIT_PIPE16_LA - 1 : DIT_PIPE16_LA;
+#ifndef DIT_CHAIN_LA
+#define DIT_CHAIN_LA (DIT_PIPE16_LA - 1)
+#endif
+    constexpr int LA = CHAIN ? DIT_CHAIN_LA : DIT_PIPE16_LA;
     constexpr int NCH = 16;            // softmax slices: two scores -> one dword of P
     constexpr int CPA = NCH / NKF;     // slices per K' fragment (pair of score MFMAs): 1 at d128, 2 at d64
     constexpr int CPB = NCH / NVF;     // maxima slices per V^T fragment
@@ -798,8 +801,14 @@ hipError_t launch_attn_pipe16_chain_inst(const AttnArgs& a, hipStream_t s) {
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
     const int64_t total_qt = (int64_t)a.nQT * a.B * a.H;
-    int64_t qch = total_qt / (5 * (int64_t)(cus > 0 ? cus : 1));
-    qch = qch < 1 ? 1 : (qch > 16 ? 16 : qch);
+#ifndef DIT_CHAIN_PER_CU
+#define DIT_CHAIN_PER_CU 5
+#endif
+#ifndef DIT_CHAIN_MAX
+#define DIT_CHAIN_MAX 16
+#endif
+    int64_t qch = total_qt / (DIT_CHAIN_PER_CU * (int64_t)(cus > 0 ? cus : 1));
+    qch = qch < 1 ? 1 : (qch > DIT_CHAIN_MAX ? DIT_CHAIN_MAX : qch);
     const int64_t nch = (a.nQT + qch - 1) / qch;
     hipLaunchKernelGGL(kern, dim3((unsigned)(nch * a.B * a.H)), dim3(64 * NW), smem, s, a, (int)qch);
     return hipGetLastError();
