@@ -225,6 +225,26 @@ dit_status dit_cross_attn_forward(const void *q, const void *k, const void *v,
                                   const dit_cross_attn_params *p, void *workspace,
                                   size_t workspace_bytes, void *stream);
 
+/* The same computation for batched requests whose conditioning sequences differ in LENGTH (Sec. 4.3: in
+ * Individual Mode the requests of a queue are handed to a worker as one batch; Sec. 2.4: a text sequence
+ * padded to a fixed length followed by an image sequence), with the lengths themselves instead of a byte
+ * mask: the keys that attend in request b are the first kv_len[2b] keys of [0, second_start) and the first
+ * kv_len[2b + 1] keys of [second_start, Lk).
+ *   kv_len        DEVICE pointer, int32 [B, 2], 4-byte aligned, read by the pre-pack pass on `stream`; counts
+ *                 outside their range are clamped to it (negative: 0).  May be NULL with
+ *                 DIT_FLAG_KV_RESIDENT (the tiles of an earlier call are reused and nothing key-side is read).
+ *   second_start  0 .. Lk; with p->Lk_split in (0, Lk) (one softmax per sequence) it must equal Lk_split,
+ *                 else DIT_ERR_INVALID_ARG.
+ * Everything else -- q, k, v, out, lse, params, flags, workspace (same size: dit_cross_attn_workspace_bytes),
+ * errors -- as dit_cross_attn_forward.  No mask is read and no key list is built: the pre-pack pass places each
+ * key from the two counts, so two small passes of the mask form (key compaction, tile list) do not run.
+ * A request with both counts 0 gets out = 0 and lse = -inf.  Ownership: the caller keeps kv_len alive and
+ * unchanged until the work enqueued on `stream` has finished. */
+dit_status dit_cross_attn_forward_lengths(const void *q, const void *k, const void *v,
+                                          const int32_t *kv_len, int32_t second_start, void *out,
+                                          float *lse, const dit_cross_attn_params *p, void *workspace,
+                                          size_t workspace_bytes, void *stream);
+
 /*
  * dit_cross_attn_forward for callers that cannot allocate device memory or take a workspace from
  * an allocator: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.

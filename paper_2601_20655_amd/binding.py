@@ -42,6 +42,7 @@ EXPORTS = (
     "dit_cross_attn_workspace_bytes",
     "dit_cross_attn_forward",
     "dit_cross_attn_forward_static",
+    "dit_cross_attn_forward_lengths",
     "dit_attn_varlen_workspace_bytes",
     "dit_attn_varlen_forward",
     "dit_linear_forward",
@@ -153,6 +154,9 @@ def lib():
         L.dit_cross_attn_forward.restype = ctypes.c_int
         L.dit_cross_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(dit_cross_attn_params),
                                              vp, ctypes.c_size_t, vp]
+        L.dit_cross_attn_forward_lengths.restype = ctypes.c_int
+        L.dit_cross_attn_forward_lengths.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp, vp,
+                                                     ctypes.POINTER(dit_cross_attn_params), vp, ctypes.c_size_t, vp]
         L.dit_cross_attn_forward_static.restype = ctypes.c_int
         L.dit_cross_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(dit_cross_attn_params), vp]
         L.dit_attn_varlen_workspace_bytes.restype = ctypes.c_size_t
@@ -395,6 +399,46 @@ def dit_cross_attn_forward(q, k, v, kv_valid=None, out=None, lse=None, scale=0.0
                                       workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if st != DIT_OK:
         raise DitError(st, "dit_cross_attn_forward")
+    return (out, lse) if lse is not None else out
+
+
+def dit_cross_attn_forward_lengths(q, k, v, kv_len, second_start, out=None, lse=None, scale=0.0, flags=0,
+                                   out_dtype=None, workspace=None, stream=None, want_lse=False, split=0, norm=None):
+    """Cross-attention with per-request key counts: kv_len int32 [B, 2] on the device; the keys that attend are
+    the first kv_len[b, 0] of [0, second_start) and the first kv_len[b, 1] of [second_start, Lk)."""
+    import torch
+
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("dit_cross_attn_forward_lengths: q must be [B, Lq, H, D] and k, v [B, Lk, H, D]")
+    B, Lq, H, D = q.shape
+    Lk = k.shape[1]
+    resident = bool(flags & DIT_FLAG_KV_RESIDENT)
+    if kv_len is None:
+        if not resident:
+            raise ValueError("kv_len is required (it may only be None with DIT_FLAG_KV_RESIDENT)")
+    else:
+        if kv_len.dtype != torch.int32 or tuple(kv_len.shape) != (B, 2) or not kv_len.is_contiguous():
+            raise ValueError("kv_len must be a contiguous int32 tensor of shape [B, 2]")
+    _check_tensors("dit_cross_attn_forward_lengths", q, k, v, out, lse, (B, Lk, H, D), (B, H, Lq), resident)
+    if kv_len is not None and kv_len.device != q.device:
+        raise ValueError("kv_len must be on the device of q")
+    if out is None:
+        out = torch.empty((B, Lq, H, D), dtype=out_dtype or q.dtype, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, H, Lq), dtype=torch.float32, device=q.device)
+    p = cross_attn_params(q, k, v, out, scale, flags, split, norm)
+    need = dit_cross_attn_workspace_bytes(p)
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    _check_workspace("dit_cross_attn_forward_lengths", workspace, need, q.device)
+    st = lib().dit_cross_attn_forward_lengths(q.data_ptr(), k.data_ptr() if k is not None else None,
+                                              v.data_ptr() if v is not None else None,
+                                              kv_len.data_ptr() if kv_len is not None else None, int(second_start),
+                                              out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                              ctypes.byref(p), workspace.data_ptr(),
+                                              workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_cross_attn_forward_lengths")
     return (out, lse) if lse is not None else out
 
 

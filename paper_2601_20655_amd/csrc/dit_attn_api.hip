@@ -502,12 +502,24 @@ dit_status dit_attn_forward(const void* q, const void* k, const void* v, void* o
     return run_attn(aa, p->D, pl.fl, pl.fl.fused, self_attn_uses_mfma16(pl.fl), s);
 }
 
-dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, const uint8_t* kv_valid,
-                                  void* out, float* lse, const dit_cross_attn_params* p, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Both cross-attention entry points: which keys attend comes as a byte mask (kv_valid, nullable) or as two counts
+// per request (kv_len with second_start; use_len).
+dit_status cross_forward(const void* q, const void* k, const void* v, const uint8_t* kv_valid, bool use_len,
+                         const int32_t* kv_len, int32_t second_start, void* out, float* lse,
+                         const dit_cross_attn_params* p, void* workspace, size_t workspace_bytes, void* stream) {
     CrossPlan pl;
     dit_status st = plan_cross(p, &pl);
     if (st != DIT_OK) return st;
+    if (use_len) {
+        if (second_start < 0 || second_start > p->Lk) return DIT_ERR_INVALID_ARG;
+        if (pl.split > 0 && second_start != pl.split) return DIT_ERR_INVALID_ARG;
+        if (!pl.fl.resident && !kv_len) return DIT_ERR_INVALID_ARG;
+        if (kv_len && (reinterpret_cast<uintptr_t>(kv_len) & 3u)) return DIT_ERR_ALIGNMENT;
+    }
     if (!q || !out) return DIT_ERR_INVALID_ARG;
     if (!pl.fl.resident && (!k || !v)) return DIT_ERR_INVALID_ARG;
     if (!aligned16(q, p->sq, p->in_dtype) || !aligned16(out, p->so, p->out_dtype)) return DIT_ERR_ALIGNMENT;
@@ -537,6 +549,8 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     pa.tile_count = reinterpret_cast<int*>(ws + pl.count_off);
     pa.tile_count_a = pl.split > 0 ? reinterpret_cast<int*>(ws + pl.count_a_off) : nullptr;
     pa.key_src = kv_valid ? reinterpret_cast<int*>(ws + pl.keysrc_off) : nullptr;
+    pa.kv_len = use_len ? kv_len : nullptr;
+    pa.second_start = second_start;
     pa.split = pl.split;
     pa.nTA = pl.nTA;
     pa.tab = nullptr;
@@ -550,8 +564,10 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
         if (pa.key_src && (e = dit::launch_key_compact(pa, s)) != hipSuccess) return hip_fail(e, "key_compact_kernel");
         e = dit::launch_prepack(pa, p->D, pl.fl.qk_op, pl.fl.pv_op, s);
         if (e != hipSuccess) return hip_fail(e, "kv_prepack_kernel");
-        e = dit::launch_tile_compact(pa, s);
-        if (e != hipSuccess) return hip_fail(e, "tile_compact_kernel");
+        if (!pa.kv_len) {  // (with key counts the pre-pack writes the tile list itself)
+            e = dit::launch_tile_compact(pa, s);
+            if (e != hipSuccess) return hip_fail(e, "tile_compact_kernel");
+        }
     }
 
     dit::AttnArgs aa;
@@ -570,6 +586,24 @@ dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, c
     aa.qscale = scale * dit::kLog2e;
     aa.qn = qn;
     return run_attn(aa, p->D, pl.fl, false, false, s, pl.chain16);
+}
+
+}  // namespace
+
+extern "C" {
+
+dit_status dit_cross_attn_forward(const void* q, const void* k, const void* v, const uint8_t* kv_valid,
+                                  void* out, float* lse, const dit_cross_attn_params* p, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+    return cross_forward(q, k, v, kv_valid, false, nullptr, 0, out, lse, p, workspace, workspace_bytes, stream);
+}
+
+dit_status dit_cross_attn_forward_lengths(const void* q, const void* k, const void* v, const int32_t* kv_len,
+                                          int32_t second_start, void* out, float* lse,
+                                          const dit_cross_attn_params* p, void* workspace, size_t workspace_bytes,
+                                          void* stream) {
+    return cross_forward(q, k, v, nullptr, true, kv_len, second_start, out, lse, p, workspace, workspace_bytes,
+                         stream);
 }
 
 size_t dit_attn_varlen_workspace_bytes(const dit_varlen_attn_params* p) {

@@ -77,6 +77,10 @@ struct PackArgs {
     const void* v;
     const uint8_t* valid;  // nullable [B, Lk]
     int* key_src;          // with valid: [B, nKT, 64] source key of every tile slot, -1 = empty (launch_key_compact)
+    const int* kv_len;     // nullable [B, 2] (instead of valid): the keys that attend are the first kv_len[b][0] of
+                           // [0, ...) and the first kv_len[b][1] of [second_start, Lk); the pre-pack works out every
+                           // slot's source key, the tile masks, the tile list and its counts from the two numbers
+    int second_start;      // with kv_len: first key of the second range (decoupled form: = split)
     uint8_t* tiles;        // [B*H, nKT, TILE_BYTES]
     uint64_t* tile_mask;   // nullable [B, nKT]
     int* tile_list;        // nullable [B, nKT], filled by launch_tile_compact

@@ -66,6 +66,10 @@ struct PackTile {
     int64_t k_off, v_off;  // element offset of key 0 of this sequence for this head
     int key0, key_end;   // keys [key0, key0 + 64) clipped to key_end
     const int* key_src;  // if set: slot r holds key key_src[r] (-1: empty) instead of key0 + r
+    // ranges (key counts instead of a mask): slot i = slot0 + r of the tile sequence holds key sa + i if i < la,
+    // key sb + (i - la) if i - la < lb, else nothing
+    bool ranges;
+    int slot0, la, sa, lb, sb;
     RopeGeom rg;         // with this sequence's grid
     int h;               // head (channel weights of the normalisation)
     int64_t stat_off;    // index of key 0 in the per-token normalisation table
@@ -84,8 +88,16 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int r = tid / CPR + i * ROWS_PER_PASS;
-        const int key = t.key_src ? t.key_src[r] : t.key0 + r;
-        const bool ok = t.key_src ? key >= 0 : key < t.key_end;
+        int key;
+        bool ok;
+        if (t.ranges) {
+            const int i_ = t.slot0 + r;
+            key = i_ < t.la ? t.sa + i_ : (i_ - t.la < t.lb ? t.sb + (i_ - t.la) : -1);
+            ok = key >= 0;
+        } else {
+            key = t.key_src ? t.key_src[r] : t.key0 + r;
+            ok = t.key_src ? key >= 0 : key < t.key_end;
+        }
         float xk[8], xv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) xk[e] = xv[e] = 0.f;
@@ -186,15 +198,49 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_kernel(const PackArgs a) 
     t.key0 = second ? a.split + (j - a.nTA) * kBK : j * kBK;
     t.key_end = (a.split > 0 && !second) ? a.split : a.Lk;
     t.key_src = a.key_src ? a.key_src + ((size_t)b * a.nKT + j) * kBK : nullptr;
+    t.ranges = a.kv_len != nullptr;
+    t.slot0 = t.la = t.sa = t.lb = t.sb = 0;
+    int ca = 0, cb = 0;  // ranges: tiles that hold a key, first and second key group (decoupled) or all (joint: ca)
+    if (t.ranges) {
+        // counts are clamped to the ranges they count in: whatever the caller wrote, every key index stays inside k, v
+        const int end0 = a.split > 0 ? a.split : a.second_start;
+        int len0 = a.kv_len[2 * b], len1 = a.kv_len[2 * b + 1];
+        len0 = len0 < 0 ? 0 : (len0 > end0 ? end0 : len0);
+        len1 = len1 < 0 ? 0 : (len1 > a.Lk - a.second_start ? a.Lk - a.second_start : len1);
+        if (a.split > 0) {  // two key groups, each in tiles of its own
+            t.slot0 = (second ? j - a.nTA : j) * kBK;
+            t.la = second ? len1 : len0;
+            t.sa = second ? a.split : 0;
+            ca = (len0 + kBK - 1) / kBK;
+            cb = (len1 + kBK - 1) / kBK;
+        } else {  // one softmax: the second range follows the first densely
+            t.slot0 = j * kBK;
+            t.la = len0; t.sa = 0; t.lb = len1; t.sb = a.second_start;
+            ca = (len0 + len1 + kBK - 1) / kBK;
+        }
+    }
     t.rg = a.rg;
     t.h = h;
     t.stat_off = (int64_t)b * a.Lk;
     pack_tile<D, QK_OP, PV_OP>(a, t, vs);
 
     if (a.tile_mask && h == 0 && tid < 64) {
-        const bool ok = t.key_src ? t.key_src[tid] >= 0 : t.key0 + tid < t.key_end;
+        bool ok;
+        if (t.ranges) ok = t.slot0 + tid < t.la + t.lb;
+        else ok = t.key_src ? t.key_src[tid] >= 0 : t.key0 + tid < t.key_end;
         const uint64_t m = __ballot(ok);
-        if (tid == 0) a.tile_mask[(size_t)b * a.nKT + j] = m;
+        if (tid == 0) {
+            a.tile_mask[(size_t)b * a.nKT + j] = m;
+            if (t.ranges) {
+                // the list of tiles that hold a key and its counts, which tile_compact_kernel otherwise derives from the masks
+                const int jj = second ? j - a.nTA : j;
+                if (m != 0ull) a.tile_list[(size_t)b * a.nKT + (second ? ca + jj : jj)] = j;
+                if (j == 0) {
+                    a.tile_count[b] = ca + cb;
+                    if (a.tile_count_a) a.tile_count_a[b] = ca;
+                }
+            }
+        }
     }
 }
 
@@ -215,6 +261,7 @@ __global__ void __launch_bounds__(kThreads) kv_prepack_varlen_kernel(const PackA
     t.key0 = j * kBK;
     t.key_end = q.L;
     t.key_src = nullptr;
+    t.ranges = false;
     t.rg = a.rg;
     t.rg.Hg = q.Hg;
     t.rg.Wg = q.Wg;

@@ -157,6 +157,29 @@ def test_cross_attn_rejects_bad_arguments():
     assert B.dit_last_hip_error() == ""
 
 
+def test_cross_attn_key_counts_rejections():
+    """dit_cross_attn_forward_lengths: everything is checked before any launch (no workspace is passed, so a
+    parameter set that got through the checks stops at DIT_ERR_WORKSPACE instead of touching the fake pointers)."""
+    f = B.lib().dit_cross_attn_forward_lengths
+
+    def call(p, kv_len=FAKE, second_start=512, q=FAKE):
+        return f(q, FAKE, FAKE, kv_len, second_start, FAKE, None, ctypes.byref(p), None, 0, None)
+
+    assert call(cross_params()) == B.DIT_ERR_WORKSPACE                      # accepted
+    assert call(cross_params(), second_start=0) == B.DIT_ERR_WORKSPACE
+    assert call(cross_params(), second_start=769) == B.DIT_ERR_WORKSPACE
+    assert call(cross_params(), second_start=-1) == B.DIT_ERR_INVALID_ARG
+    assert call(cross_params(), second_start=770) == B.DIT_ERR_INVALID_ARG
+    assert call(cross_params(), kv_len=None) == B.DIT_ERR_INVALID_ARG
+    assert call(cross_params(flags=B.DIT_FLAG_KV_RESIDENT), kv_len=None) == B.DIT_ERR_WORKSPACE
+    assert call(cross_params(), kv_len=FAKE + 2) == B.DIT_ERR_ALIGNMENT
+    # one softmax per sequence: the second range starts where the split is
+    assert call(cross_params(split=512), second_start=512) == B.DIT_ERR_WORKSPACE
+    assert call(cross_params(split=512), second_start=500) == B.DIT_ERR_INVALID_ARG
+    assert call(cross_params(D=32)) == B.DIT_ERR_UNSUPPORTED
+    assert call(cross_params(), q=0) == B.DIT_ERR_INVALID_ARG
+
+
 def test_qk_norm_arguments():
     L, H = 24, 2
     base = B.dit_attn_workspace_bytes(self_params())

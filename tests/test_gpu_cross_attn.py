@@ -207,3 +207,74 @@ def test_chained_query_tiles_all_rows(D, shape):
     for b in (1, 2, 3):
         compare(o[b], ref[b], what="chained, request %d, %s" % (b, shape))
         assert np.allclose(l[b], ref_lse[b], rtol=0, atol=2e-3)
+
+
+def _mask_from_lengths(kv_len, second_start, Lk):
+    valid = np.zeros((kv_len.shape[0], Lk), dtype=np.uint8)
+    for b, (l0, l1) in enumerate(kv_len):
+        valid[b, :l0] = 1
+        valid[b, second_start:second_start + l1] = 1
+    return valid
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("shape", ["auto", "chain_8w", "pipe_qb1_4w", "simple_qb1"])
+def test_key_counts_instead_of_mask(D, shape):
+    """dit_cross_attn_forward_lengths: two counts per request instead of a byte mask.  Against the oracle on the
+    mask the counts stand for, and bit for bit against the mask form of the library (same keys, same order)."""
+    import torch
+
+    n_text, n_image = 200, 77
+    cfg = dict(B=5, Lq=300, n_text=n_text, n_image=n_image, H=3, D=D, dtype="bf16", min_text=5, seed=31 + D)
+    q, k, v, _, _ = wl.cross_attn_inputs(cfg)
+    kv_len = np.array([[200, 77], [1, 0], [0, 0], [64, 64], [130, 5]], dtype=np.int32)
+    valid = _mask_from_lengths(kv_len, n_text, n_text + n_image)
+    ref, ref_lse = oracle.cross_attn(q, k, v, valid, want_lse=True)
+    flags = SHAPES[shape]
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    out, lse = B.dit_cross_attn_forward_lengths(dq, dk, dv, torch.from_numpy(kv_len).cuda(), n_text, flags=flags,
+                                                out_dtype=torch.float32, want_lse=True)
+    torch.cuda.synchronize()
+    o, l = to_f64(out), to_f64(lse)
+    for b in range(5):
+        if kv_len[b].sum() == 0:
+            assert np.all(o[b] == 0.0) and np.all(np.isneginf(l[b]))
+        else:
+            compare(o[b], ref[b], what="key counts, request %d, %s" % (b, shape))
+            assert np.allclose(l[b], ref_lse[b], rtol=0, atol=2e-3)
+    out_m = run_cross(q, k, v, valid, flags=flags, out_dtype=torch.float32)
+    assert torch.equal(out, out_m)
+    # counts outside their range are clamped, never read out of bounds
+    wild = torch.tensor([[10 ** 6, 10 ** 6], [-5, 3], [0, 0], [64, 64], [130, 5]], dtype=torch.int32).cuda()
+    out_w = B.dit_cross_attn_forward_lengths(dq, dk, dv, wild, n_text, flags=flags, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    clamped = _mask_from_lengths(np.array([[200, 77], [0, 3], [0, 0], [64, 64], [130, 5]]), n_text, n_text + n_image)
+    compare(to_f64(out_w)[1], oracle.cross_attn(q, k, v, clamped)[1], what="clamped counts")
+    assert torch.equal(out_w[0], out[0])
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_key_counts_decoupled_and_resident(D):
+    """The decoupled form (a softmax per sequence) from counts, then new queries against the tiles that call left."""
+    import torch
+
+    n_text, n_image = 150, 70
+    cfg = dict(B=3, Lq=200, n_text=n_text, n_image=n_image, H=2, D=D, dtype="bf16", min_text=5, seed=5 + D)
+    q, k, v, _, _ = wl.cross_attn_inputs(cfg)
+    kv_len = np.array([[150, 70], [33, 0], [0, 65]], dtype=np.int32)
+    valid = _mask_from_lengths(kv_len, n_text, n_text + n_image)
+    ref = oracle.cross_attn_decoupled(q, k, v, n_text, valid)
+    dlen = torch.from_numpy(kv_len).cuda()
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    out = B.dit_cross_attn_forward_lengths(to_dev(q), to_dev(k), to_dev(v), dlen, n_text, split=n_text,
+                                           out_dtype=torch.float32, workspace=ws)
+    torch.cuda.synchronize()
+    compare(to_f64(out), ref, what="decoupled from key counts")
+    with pytest.raises(B.DitError):  # the second range of the decoupled form starts at the split
+        B.dit_cross_attn_forward_lengths(to_dev(q), to_dev(k), to_dev(v), dlen, n_text - 1, split=n_text, workspace=ws)
+    q2 = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(q)[:, ::-1].copy())
+    nan = torch.full_like(to_dev(k), float("nan"))
+    out2 = B.dit_cross_attn_forward_lengths(to_dev(q2), nan, nan, None, n_text, split=n_text, workspace=ws,
+                                            flags=B.DIT_FLAG_KV_RESIDENT, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    compare(to_f64(out2), oracle.cross_attn_decoupled(q2, k, v, n_text, valid), what="resident tiles from key counts")
