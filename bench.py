@@ -221,10 +221,21 @@ def other_workload(args):
         io_bytes = 2.0 * q.numel() * q.element_size() + 2.0 * float(valid.sum()) * H * D * k.element_size()
         what = "%s cross-attention, B=%d, %d queries x (512 text masked to %s + 257 image) keys, %d heads, d%d" % (
             "decoupled" if split else "joint", cfg["B"], Lq, list(map(int, text_len)), H, D)
-        kernel = "attn_fwd_kernel"
+        plain = split or args.flags & (B.DIT_FLAG_SIMPLE_SCHEDULE | B.DIT_FLAG_MFMA_32X32 | B.DIT_FLAG_WIDE_QTILE)
+        kernel = ("attn_fwd_pipe_kernel" if args.flags & B.DIT_FLAG_PIPELINED_SCHEDULE else
+                  "attn_fwd_kernel" if plain else "attn_fwd_pipe16_chain_kernel")
+        # --key-counts: the same keys as two counts per request (text keys, image keys) instead of the byte mask
+        kv_len = torch.tensor([[int(t), cfg["n_image"]] for t in text_len], dtype=torch.int32, device="cuda")
+        if args.key_counts:
+            what += ", keys given as counts"
 
         def call():
-            B.dit_cross_attn_forward(q, k, v, vd, out=out, flags=args.flags, workspace=ws, stream=stream, split=split)
+            if args.key_counts:
+                B.dit_cross_attn_forward_lengths(q, k, v, kv_len, cfg["n_text"], out=out, flags=args.flags,
+                                                 workspace=ws, stream=stream, split=split)
+            else:
+                B.dit_cross_attn_forward(q, k, v, vd, out=out, flags=args.flags, workspace=ws, stream=stream,
+                                         split=split)
 
     if args.flags & B.DIT_FLAG_KV_RESIDENT:  # the timed calls reuse what one ordinary call packs first
         resident = args.flags
@@ -234,6 +245,22 @@ def other_workload(args):
     ms, kern_ms = time_calls(B, torch, call, args.steps, args.warmup)
     achieved = flops / (kern_ms * 1e-3) / 1e12
     extra = {}
+    if cfg["kind"] == "linear" and args.vendor_gemm:
+        # the vendor's GEMM library on the same tensors and box (context for the projection kernel, never the metric)
+        def vendor():
+            torch.addmm(b, x, w.t(), out=out)
+        for _ in range(args.warmup):
+            vendor()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            vendor()
+        e1.record()
+        torch.cuda.synchronize()
+        vms = e0.elapsed_time(e1) / args.steps
+        extra = {"vendor_gemm": {"what": "torch.addmm on the same tensors", "ms_per_call": round(vms, 4),
+                                 "tflops": round(flops / (vms * 1e-3) / 1e12, 1)}}
     if cfg["kind"] == "cross":
         # this shape is close enough to the HBM roofline that the streaming rate is reported beside the flops
         extra = {"tflops_dense_count": round(flops_dense / (ms * 1e-3) / 1e12, 2),
@@ -279,6 +306,10 @@ def main():
                          "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b, qkv_proj_14b, out_proj_14b, "
                          "mfma_peak (the MFMA-only micro-benchmark)")
     ap.add_argument("--decoupled", action="store_true", help="cross_14b: one softmax per conditioning sequence")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="qkv_proj_14b / out_proj_14b: also time the vendor GEMM library (torch.addmm) on the same tensors")
+    ap.add_argument("--key-counts", action="store_true",
+                    help="cross_14b: dit_cross_attn_forward_lengths (two key counts per request) instead of the byte mask")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU (all heads of one request on one MI355X, no "
