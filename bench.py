@@ -177,6 +177,42 @@ def other_workload(args):
 
         def call():
             B.dit_linear_forward(x, w, b, out=out, stream=stream)
+    elif cfg["kind"] == "qkv_attn":
+        # q/k/v projection, then self-attention on what it wrote.  Separate: the projection writes [L, 3 H D] bf16
+        # rows and the attention call packs its k and v columns into tile images.  --fused-qkv: the projection's
+        # epilogue writes the q rows and the tile images itself and the attention call runs on them as they are.
+        L = cfg["grid"][0] * cfg["grid"][1] * cfg["grid"][2]
+        HD = H * D
+        x, w, b = (dev(a) for a in wl.linear_inputs(dict(M=L, N=3 * HD, K=cfg["K"], seed=cfg["seed"])))
+        y = torch.empty((L, 3 * HD), dtype=torch.bfloat16, device="cuda")
+        yq, yk, yv = (y[:, i * HD:(i + 1) * HD].view(1, L, H, D) for i in range(3))
+        q_out = torch.empty((1, L, H, D), dtype=torch.bfloat16, device="cuda")
+        out = torch.empty_like(q_out)
+        ws = torch.empty(B.dit_attn_workspace_bytes(B.self_attn_params(q_out, q_out, q_out, out, cfg["grid"],
+                                                                        cfg["split"], flags=args.flags)),
+                         dtype=torch.uint8, device="cuda")
+        flops_proj = 2.0 * L * 3 * HD * cfg["K"]
+        flops = flops_proj + 4.0 * H * L * L * D
+        what = "q/k/v projection (%d tokens, %d -> %d features, %s) + self-attention (grid %dx%dx%d, %d heads, d%d)" % (
+            L, cfg["K"], 3 * HD, "epilogue writes the attention's tile images" if args.fused_qkv else
+            "separate calls", cfg["grid"][0], cfg["grid"][1], cfg["grid"][2], H, D)
+        kernel = "attn_fwd_pipe16_kernel"
+        mid = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+        def call():
+            mid[0].record(stream)
+            if args.fused_qkv:
+                B.dit_qkv_proj_forward(x, w, b, cfg["grid"], cfg["split"], H, q_out=q_out, flags=args.flags,
+                                       workspace=ws, stream=stream)
+                mid[1].record(stream)
+                B.dit_attn_forward(q_out, None, None, cfg["grid"], cfg["split"], out=out,
+                                   flags=args.flags | B.DIT_FLAG_KV_RESIDENT, workspace=ws, stream=stream)
+            else:
+                B.dit_linear_forward(x, w, b, out=y, stream=stream)
+                mid[1].record(stream)
+                B.dit_attn_forward(yq, yk, yv, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
+                                   stream=stream)
+            mid[2].record(stream)
     elif cfg["kind"] == "self":
         q, k, v = (dev(a) for a in wl.self_attn_inputs(cfg))
         out = torch.empty_like(q)
@@ -261,6 +297,12 @@ def other_workload(args):
         vms = e0.elapsed_time(e1) / args.steps
         extra = {"vendor_gemm": {"what": "torch.addmm on the same tensors", "ms_per_call": round(vms, 4),
                                  "tflops": round(flops / (vms * 1e-3) / 1e12, 1)}}
+    if cfg["kind"] == "qkv_attn":
+        # the last timed step's two calls on their own (events on the stream either side of each)
+        extra = {"projection_call_ms": round(mid[0].elapsed_time(mid[1]), 4),
+                 "attention_call_ms": round(mid[1].elapsed_time(mid[2]), 4),
+                 "projection_flops": flops_proj}
+        achieved = (flops - flops_proj) / (kern_ms * 1e-3) / 1e12
     if cfg["kind"] == "cross":
         # this shape is close enough to the HBM roofline that the streaming rate is reported beside the flops
         extra = {"tflops_dense_count": round(flops_dense / (ms * 1e-3) / 1e12, 2),
@@ -274,7 +316,8 @@ def other_workload(args):
     # 8-bit scores: half of the flops run at the 8-bit peak, half at the 16-bit peak
     peak = 2.0 / (1.0 / PEAK_TFLOPS_8BIT_DENSE + 1.0 / PEAK_TFLOPS_16BIT_DENSE) if fp8 else PEAK_TFLOPS_16BIT_DENSE
     print(json.dumps({
-        "metric": ("projection" if cfg["kind"] == "linear" else "attention") + " TFLOP/s, %s" % args.workload
+        "metric": ("projection" if cfg["kind"] == "linear" else "projection + attention" if cfg["kind"] == "qkv_attn"
+                   else "attention") + " TFLOP/s, %s" % args.workload
                   + (" (decoupled)" if args.decoupled else "")
                   + (" (8-bit score operands: outside the 16-bit parity contract)" if fp8 else ""),
         "value": round(flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -304,10 +347,13 @@ def main():
     ap.add_argument("--workload", default="step",
                     help="'step' (default: the headline metric) or one of the other shapes for a secondary "
                          "timing line: dit_1p3b, dit_14b, dit_14b_hires, cross_14b, varlen_14b, qkv_proj_14b, out_proj_14b, "
-                         "mfma_peak (the MFMA-only micro-benchmark)")
+                         "qkv_attn_14b (projection, then self-attention on its output), mfma_peak (the MFMA-only micro-benchmark)")
     ap.add_argument("--decoupled", action="store_true", help="cross_14b: one softmax per conditioning sequence")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="qkv_proj_14b / out_proj_14b: also time the vendor GEMM library (torch.addmm) on the same tensors")
+    ap.add_argument("--fused-qkv", action="store_true",
+                    help="qkv_attn_14b: dit_qkv_proj_forward (the projection writes the attention's tile images) and "
+                         "the attention call on them, instead of two separate calls")
     ap.add_argument("--key-counts", action="store_true",
                     help="cross_14b: dit_cross_attn_forward_lengths (two key counts per request) instead of the byte mask")
     args = ap.parse_args()

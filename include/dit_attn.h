@@ -363,6 +363,25 @@ enum { DIT_PROBE_BF16 = 0, DIT_PROBE_F16 = 1 };
 dit_status dit_mfma_probe(int32_t operand_dtype, int32_t bits_a, int32_t bits_b, int64_t mfma_per_wavefront,
                           float *sink, size_t sink_bytes, double *flops, void *stream);
 
+/* The fused q/k/v projection in front of self-attention (Sec. 2.4: a transformer block of the Diffusion stage projects
+ * its token rows to queries, keys and values and attends): y = x w^T + bias with the rows of w ordered [q; k; v],
+ * H*D rows each (N = 3*H*D).  The q rows are stored to q_out as they come out (bf16, strides ap->sq); the k rows are
+ * rotated (the RoPE of dit_attn_forward for ap's grid, sections, origin and base), rounded ONCE to the score operand
+ * type and written, with the v rows (rounded to the PV operand type, transposed), as the K'/V^T tile images that
+ * dit_attn_forward keeps in its workspace.  A following
+ *     dit_attn_forward(q_out, NULL, NULL, out, lse, ap' = ap with flags | DIT_FLAG_KV_RESIDENT, workspace, ...)
+ * on the same workspace then needs no pre-pack pass, and k and v never exist as rows in memory.
+ *   x [M, K] bf16 (row stride lp->ldx), w [3*H*D, K] bf16 (lp->ldw), bias [3*H*D] bf16 or NULL: DEVICE pointers.
+ *   lp: M = T*Hg*Wg of ap, N = 3*H*D, K a multiple of 64, out_dtype DIT_BF16, flags 0; ldy is ignored.
+ *   ap: the parameters of the attention call that follows, without DIT_FLAG_KV_RESIDENT.  Covered: B = 1,
+ *       D = 128, an even H, in_dtype DIT_BF16, no normalisation, flags that select the default attention kernel
+ *       (operand-type flags are honoured); anything else DIT_ERR_UNSUPPORTED.  sk, sv are ignored.
+ *   workspace: dit_attn_workspace_bytes(ap) bytes, 256-byte aligned; written: rotation table and every tile image.
+ * Errors as dit_linear_forward and dit_attn_forward; nothing is enqueued unless all checks pass. */
+dit_status dit_qkv_proj_forward(const void *x, const void *w, const void *bias, void *q_out,
+                                const dit_linear_params *lp, const dit_self_attn_params *ap,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 /* Static strings; never NULL. */
 const char *dit_strerror(dit_status s);
 /* Text of the last HIP error seen by the calling thread ("" if none). */

@@ -46,6 +46,7 @@ EXPORTS = (
     "dit_attn_varlen_workspace_bytes",
     "dit_attn_varlen_forward",
     "dit_linear_forward",
+    "dit_qkv_proj_forward",
     "dit_mfma_probe",
     "dit_attn_set_timing_events",
     "dit_strerror",
@@ -166,6 +167,9 @@ def lib():
                                               ctypes.c_size_t, vp]
         L.dit_linear_forward.restype = ctypes.c_int
         L.dit_linear_forward.argtypes = [vp, vp, vp, vp, ctypes.POINTER(dit_linear_params), vp]
+        L.dit_qkv_proj_forward.restype = ctypes.c_int
+        L.dit_qkv_proj_forward.argtypes = [vp, vp, vp, vp, ctypes.POINTER(dit_linear_params),
+                                           ctypes.POINTER(dit_self_attn_params), vp, ctypes.c_size_t, vp]
         L.dit_mfma_probe.restype = ctypes.c_int
         L.dit_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_size_t,
                                      ctypes.POINTER(ctypes.c_double), vp]
@@ -529,6 +533,46 @@ def dit_linear_forward(x, w, bias=None, out=None, out_dtype=None, stream=None):
     if st != DIT_OK:
         raise DitError(st, "dit_linear_forward")
     return out
+
+
+def dit_qkv_proj_forward(x, w, bias, grid, split, H, q_out=None, origin=(0, 0, 0), rope_base=10000.0, scale=0.0,
+                         flags=0, workspace=None, stream=None):
+    """Fused q/k/v projection in front of dit_attn_forward: x [L, K] bf16, w [3*H*128, K] bf16 (rows [q; k; v]),
+    bias [3*H*128] bf16 or None, L = T*Hg*Wg.  Returns (q_out [1, L, H, 128] bf16, workspace): the workspace then
+    holds the rotation table and the K'/V^T tile images, and
+        dit_attn_forward(q_out, k=None, v=None, grid, split, flags=flags | DIT_FLAG_KV_RESIDENT, workspace=workspace)
+    completes the attention (pass any [1, L, H, 128] tensor for k and v: they are not read)."""
+    import torch
+
+    D = 128
+    if x.dim() != 2 or w.dim() != 2 or x.stride(1) != 1 or w.stride(1) != 1:
+        raise ValueError("x and w must be 2-D with contiguous rows")
+    if not x.is_cuda or w.device != x.device:
+        raise ValueError("dit_qkv_proj_forward needs device tensors on one device")
+    if x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or (bias is not None and bias.dtype != torch.bfloat16):
+        raise TypeError("x, w and bias must be bfloat16")
+    L = grid[0] * grid[1] * grid[2]
+    if x.shape[0] != L or w.shape[0] != 3 * H * D or w.shape[1] != x.shape[1]:
+        raise ValueError("shapes do not fit: x [T*Hg*Wg, K], w [3*H*128, K]")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != 3 * H * D or bias.stride(0) != 1 or
+                             bias.device != x.device):
+        raise ValueError("bias must be a dense [3*H*128] tensor on the device of x")
+    if q_out is None:
+        q_out = torch.empty((1, L, H, D), dtype=torch.bfloat16, device=x.device)
+    if tuple(q_out.shape) != (1, L, H, D) or q_out.dtype != torch.bfloat16 or q_out.device != x.device:
+        raise ValueError("q_out must be a bfloat16 [1, L, H, 128] tensor on the device of x")
+    ap = self_attn_params(q_out, q_out, q_out, q_out, grid, split, origin, rope_base, scale, flags)
+    lp = dit_linear_params(L, 3 * H * D, x.shape[1], x.stride(0), w.stride(0), 3 * H * D, DIT_BF16, 0)
+    need = dit_attn_workspace_bytes(ap)
+    if workspace is None:
+        workspace = _workspace(need, x.device)
+    _check_workspace("dit_qkv_proj_forward", workspace, need, x.device)
+    st = lib().dit_qkv_proj_forward(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                    q_out.data_ptr(), ctypes.byref(lp), ctypes.byref(ap), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != DIT_OK:
+        raise DitError(st, "dit_qkv_proj_forward")
+    return q_out, workspace
 
 
 DIT_PROBE_BF16 = 0

@@ -738,6 +738,78 @@ dit_status dit_linear_forward(const void* x, const void* w, const void* bias, vo
     return DIT_OK;
 }
 
+dit_status dit_qkv_proj_forward(const void* x, const void* w, const void* bias, void* q_out,
+                                const dit_linear_params* lp, const dit_self_attn_params* ap, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    if (!x || !w || !q_out || !lp || !ap) return DIT_ERR_INVALID_ARG;
+    SelfPlan pl;
+    dit_status st = plan_self(ap, &pl);
+    if (st != DIT_OK) return st;
+    // what the fused form covers: one sequence, head_dim 128, an even number of heads (a 256-feature tile is two
+    // heads of one of q, k, v), 16-bit rows, no normalisation, the default attention kernel's tile images
+    if (ap->B != 1 || ap->D != 128 || (ap->H & 1) || ap->in_dtype != DIT_BF16 || ap->norm.mode != DIT_NORM_NONE ||
+        !self_attn_uses_mfma16(pl.fl) || pl.fl.resident)
+        return DIT_ERR_UNSUPPORTED;
+    if (lp->flags != 0 || lp->out_dtype != DIT_BF16) return DIT_ERR_INVALID_ARG;
+    if (lp->M != pl.L || lp->N != 3 * (int64_t)ap->H * ap->D || lp->K < 1) return DIT_ERR_INVALID_ARG;
+    if (lp->ldx < lp->K || lp->ldw < lp->K) return DIT_ERR_INVALID_ARG;
+    if (lp->K % dit::kLinBK != 0) return DIT_ERR_UNSUPPORTED;
+    if (lp->ldx > (int64_t)1 << 22 || lp->ldw > (int64_t)1 << 22) return DIT_ERR_UNSUPPORTED;
+    if ((uintptr_t)x % 16 || (uintptr_t)w % 16 || (lp->ldx * 2) % 16 || (lp->ldw * 2) % 16 || (uintptr_t)bias % 8)
+        return DIT_ERR_ALIGNMENT;
+    if (!aligned16(q_out, ap->sq, DIT_BF16)) return DIT_ERR_ALIGNMENT;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) || workspace_bytes < pl.total)
+        return DIT_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    dit::RopeGeom rg;
+    rg.hd[0] = ap->d_t / 2; rg.hd[1] = ap->d_h / 2; rg.hd[2] = ap->d_w / 2;
+    rg.off[0] = 0; rg.off[1] = ap->T * rg.hd[0]; rg.off[2] = rg.off[1] + ap->Hg * rg.hd[1];
+    rg.Hg = ap->Hg; rg.Wg = ap->Wg;
+    dit::TableArgs ta;
+    ta.tab = reinterpret_cast<float2*>(ws + pl.tab_off);
+    ta.n[0] = ap->T; ta.n[1] = ap->Hg; ta.n[2] = ap->Wg;
+    ta.origin[0] = ap->t0; ta.origin[1] = ap->h0; ta.origin[2] = ap->w0;
+    ta.rg = rg;
+    ta.base = (double)ap->rope_base;
+    ta.total = pl.table_entries;
+    hipError_t e = dit::launch_rope_table(ta, s);
+    if (e != hipSuccess) return hip_fail(e, "rope_table_kernel");
+
+    dit::LinearArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.w = static_cast<const uint16_t*>(w);
+    a.bias = static_cast<const uint16_t*>(bias);
+    a.y = q_out;
+    a.M = lp->M;
+    a.N = lp->N;
+    a.K = lp->K;
+    a.ldx = lp->ldx;
+    a.ldw = lp->ldw;
+    a.ldy = 0;
+    a.nTM = (lp->M + dit::kLinBM - 1) / dit::kLinBM;
+    a.nTN = lp->N / dit::kLinBN;
+    a.out_f32 = 0;
+    a.qkv = 1;
+    a.qkv_H = ap->H;
+    a.qkv_nKT = pl.nKT;
+    a.qkv_tiles = ws + pl.tiles_off;
+    a.qkv_tab = ta.tab;
+    a.qkv_rg = rg;
+    a.qkv_sq_t = ap->sq.token;
+    a.qkv_sq_h = ap->sq.head;
+    a.qkv_qk_f16 = pl.fl.qk_op == dit::OP_F16;
+    a.qkv_pv_f16 = pl.fl.pv_op == dit::OP_F16;
+    if ((int64_t)a.nTM * a.nTN > 0x7fffffff) return DIT_ERR_UNSUPPORTED;
+    const bool timed = g_ev_before && g_ev_after;
+    if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    e = dit::launch_linear(a, s);
+    if (e != hipSuccess) return hip_fail(e, "linear_kernel");
+    if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    return DIT_OK;
+}
+
 void dit_attn_set_timing_events(void* before, void* after) {
     g_ev_before = static_cast<hipEvent_t>(before);
     g_ev_after = static_cast<hipEvent_t>(after);

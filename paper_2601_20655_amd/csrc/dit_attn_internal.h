@@ -191,6 +191,17 @@ struct LinearArgs {
     int64_t ldx, ldw, ldy;
     int nTM, nTN;          // tiles along M and N
     int out_f32;
+    // Fused q/k/v form (qkv != 0; N = 3 H D, head_dim 128, the M tokens are ONE sequence): features [0, HD) are q
+    // rows and go to y as [token, head, channel] with the strides below; features [HD, 2 HD) are k rows, which are
+    // rotated, rounded to the score operand type and written as the K' parts of the attention kernel's tile images;
+    // features [2 HD, 3 HD) are v rows, rounded to the PV operand type and written transposed as the V^T parts.
+    int qkv;
+    int qkv_H, qkv_nKT;          // heads; key tiles = ceil(M / 64)
+    uint8_t* qkv_tiles;          // [H, nKT, TILE_BYTES], layout of the 16x16x32 kernels (PackArgs::v_layout 1)
+    const float2* qkv_tab;       // rotation table
+    RopeGeom qkv_rg;
+    int64_t qkv_sq_t, qkv_sq_h;  // element strides of the q rows in y
+    int qkv_qk_f16, qkv_pv_f16;  // operand types of the two tile parts: fp16 (saturating) or bf16
 };
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 

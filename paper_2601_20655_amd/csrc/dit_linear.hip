@@ -59,8 +59,9 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-template <bool OUT_F32>
+template <bool OUT_F32, bool QKV>
 __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearArgs a) {
+    static_assert(!(OUT_F32 && QKV), "the fused q/k/v form writes 16-bit rows and tiles");
     static_assert(kLinBM == 256 && kLinBN == 256 && kLinBK == 64, "tile shape");
     constexpr int SX = kLinSX, SW = kLinSW, NW = kLinWaves;
     constexpr int BR = 16;       // rows of an MFMA block
@@ -304,6 +305,131 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
         __builtin_amdgcn_s_barrier();
     };
 
+    // ---- store of a finished tile, fused q/k/v form.  A wavefront's 64 features are half a head of ONE of q, k, v
+    // (a part starts on a multiple of 256 features).  Staged as 16-bit rows as above, 32 tokens a pass; what differs
+    // is what happens on the way in (k rows are rotated, each part is rounded to its own type, tokens past the end of
+    // the sequence become zeros in the k and v parts: they fill the last tile's slots) and where the rows go: q rows
+    // to y; k rows to the K' part of the token's tile image (row = key, its 16-byte chunks in the image's swizzled
+    // order); v rows transposed: a lane gathers, for one channel, the eight keys of a V^T chunk in the order the
+    // attention kernel's PV operand wants them (pack_tile, layout 1) and writes the chunk to the V^T part.
+    auto store_tile_qkv = [&](int tm, int tn, int stage_buf) __attribute__((always_inline)) {
+        using G = TileGeom<128>;
+        constexpr int RB = 128, PR = 8, RP = 32, TBP = 2;
+        // (every per-lane offset below comes from a lane number the compiler cannot see through: worked out ahead of
+        // the tile stream they do not fit the registers the loop leaves, and their reloads from scratch memory put
+        // a wait for ALL loads in flight into the loop)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int lr = ln & 15, lg = ln >> 4;
+        const int HD = a.qkv_H * 128;
+        const int n_wave = tn * kLinBN + wf * BR * FB;  // first feature of this wavefront's share
+        const int part = n_wave / HD;                   // 0: q, 1: k, 2: v
+        const int hd0 = n_wave - part * HD;
+        const int h = hd0 >> 7, c0 = hd0 & 127;         // head, first channel (0 or 64)
+        uint2 bb[FB];
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb) {
+            bb[fb] = make_uint2(0u, 0u);
+            if (a.bias) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n_wave + fb * BR + 4 * lg);
+        }
+        uint8_t* const region = smem + stage_buf * kLinTileBytes + wave * 4096;
+        uint8_t* const tiles_h = a.qkv_tiles + (size_t)h * a.qkv_nKT * G::TILE_BYTES;
+        const int rrow = ln / PR, rp = ln % PR;
+        const int tok_end = a.qkv_nKT * kBK;  // slots of the sequence's tiles
+#pragma unroll
+        for (int pass = 0; pass < TB / TBP; ++pass) {
+            const int tok0 = tm * kLinBM + wt * BR * TB + pass * RP;  // a multiple of 32: half a key tile
+#pragma unroll
+            for (int hh = 0; hh < TBP; ++hh) {
+                const int tb = pass * TBP + hh;
+                const int row = BR * hh + lr;
+                const int tok = tok0 + row;
+                int pt = 0, ph = 0, pw = 0;
+                if (part == 1) token_pos(tok < a.M ? tok : a.M - 1, a.qkv_rg, pt, ph, pw);
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) {
+                    const float b0 = __uint_as_float(bb[fb].x << 16), b1 = __uint_as_float(bb[fb].x & 0xffff0000u);
+                    const float b2 = __uint_as_float(bb[fb].y << 16), b3 = __uint_as_float(bb[fb].y & 0xffff0000u);
+                    float y0 = acc[fb][tb][0] + b0, y1 = acc[fb][tb][1] + b1;
+                    float y2 = acc[fb][tb][2] + b2, y3 = acc[fb][tb][3] + b3;
+                    if (part == 1) {  // the two rotation pairs of channels c0 + 16 fb + 4 lg .. + 3
+                        const RopeGeom& rg = a.qkv_rg;
+#pragma unroll
+                        for (int pp = 0; pp < 2; ++pp) {
+                            const int ip = ((c0 + BR * fb + 4 * lg) >> 1) + pp;
+                            int idx;
+                            if (ip < rg.hd[0]) idx = rg.off[0] + pt * rg.hd[0] + ip;
+                            else if (ip < rg.hd[0] + rg.hd[1]) idx = rg.off[1] + ph * rg.hd[1] + (ip - rg.hd[0]);
+                            else idx = rg.off[2] + pw * rg.hd[2] + (ip - rg.hd[0] - rg.hd[1]);
+                            const float2 cs = a.qkv_tab[idx];
+                            float& x0 = pp ? y2 : y0;
+                            float& x1 = pp ? y3 : y1;
+                            const float r0 = x0 * cs.x - x1 * cs.y, r1 = x0 * cs.y + x1 * cs.x;
+                            x0 = r0;
+                            x1 = r1;
+                        }
+                    }
+                    if (part != 0 && tok >= a.M) y0 = y1 = y2 = y3 = 0.f;
+                    const bool f16 = part == 1 ? a.qkv_qk_f16 != 0 : part == 2 ? a.qkv_pv_f16 != 0 : false;
+                    const uint2 packed = f16 ? make_uint2(pack2<OP_F16>(y0, y1), pack2<OP_F16>(y2, y3))
+                                             : make_uint2(pack2<OP_BF16>(y0, y1), pack2<OP_BF16>(y2, y3));
+                    const int col = (BR * fb + 4 * lg) * 2;
+                    *reinterpret_cast<uint2*>(region + row * RB + (((col >> 4) ^ (row & (PR - 1))) << 4) + (col & 15)) = packed;
+                }
+            }
+            if (part == 2) {
+                // V^T: lane = channel d of the wavefront's 64; chunk j of this half tile holds the keys (slots
+                // 4 g + e) 16 g + 4 j + e of the pass's 32
+                const int d = ln, dch = c0 + d;
+                const int tile = tok0 >> 6, half = (tok0 >> 5) & 1;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t w4[4];
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+#pragma unroll
+                        for (int e2 = 0; e2 < 2; ++e2) {
+                            const int r0 = 16 * g + 4 * j + 2 * e2, r1 = r0 + 1;
+                            const uint32_t lo = *reinterpret_cast<const uint16_t*>(
+                                region + r0 * RB + ((((d >> 3) ^ (r0 & (PR - 1)))) << 4) + (d & 7) * 2);
+                            const uint32_t hi = *reinterpret_cast<const uint16_t*>(
+                                region + r1 * RB + ((((d >> 3) ^ (r1 & (PR - 1)))) << 4) + (d & 7) * 2);
+                            w4[2 * g + e2] = lo | (hi << 16);
+                        }
+                    const int kc = 4 * half + j;
+                    const int kcs = kc ^ (((dch >> 2) ^ (dch >> 3)) & 1);
+                    if (tok0 < tok_end)
+                        *reinterpret_cast<uint4*>(tiles_h + (size_t)tile * G::TILE_BYTES + G::K_BYTES + dch * G::VROW +
+                                                  kcs * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int r = k * (64 / PR) + rrow;
+                    const uint4 v = *reinterpret_cast<const uint4*>(region + r * RB + ((rp ^ (r & (PR - 1))) << 4));
+                    const int tok = tok0 + r;
+                    if (part == 0) {
+                        if (tok < a.M)
+                            *reinterpret_cast<uint4*>(static_cast<uint16_t*>(a.y) + (int64_t)tok * a.qkv_sq_t +
+                                                      (int64_t)h * a.qkv_sq_h + c0 + rp * 8) = v;
+                    } else if (tok < tok_end) {
+                        const int tile = tok >> 6, rr = tok & 63;
+                        const int chunk = (c0 >> 3) + rp;
+                        const int cs = chunk ^ (((rr >> 2) ^ (rr >> 3)) & 1);
+                        *reinterpret_cast<uint4*>(tiles_h + (size_t)tile * G::TILE_BYTES + rr * G::KROW + cs * 16) = v;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[fb][tb][r] = 0.f;
+        __builtin_amdgcn_s_barrier();
+    };
+
     // Prologue: tiles x(0), w(0), x(1) in a burst; the first barrier; then what a last slice would
     // have sent behind it (the w tile of step 1); the loop sends the rest.
     dma_x(0);
@@ -384,7 +510,8 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
         wb = wb_next;
         if constexpr (LOADS) next_load_step();
         if (++kt == nK) {
-            store_tile(tm, tn, xb == 0 ? SX - 1 : xb - 1);
+            if constexpr (QKV) store_tile_qkv(tm, tn, xb == 0 ? SX - 1 : xb - 1);
+            else store_tile(tm, tn, xb == 0 ? SX - 1 : xb - 1);
             kt = 0;
             tile_coords(++tile, tm, tn);
         }
@@ -395,9 +522,9 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
 }
 
-template <bool OUT_F32>
+template <bool OUT_F32, bool QKV>
 hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
-    auto kern = linear_kernel<OUT_F32>;
+    auto kern = linear_kernel<OUT_F32, QKV>;
     constexpr int smem = (kLinSX + kLinSW) * kLinTileBytes;
     static std::atomic<uint64_t> attr_set{0};
     hipError_t e = allow_dynamic_lds(kern, smem, attr_set);
@@ -416,7 +543,8 @@ hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s) {
-    return a.out_f32 ? launch_linear_inst<true>(a, s) : launch_linear_inst<false>(a, s);
+    if (a.qkv) return launch_linear_inst<false, true>(a, s);
+    return a.out_f32 ? launch_linear_inst<true, false>(a, s) : launch_linear_inst<false, false>(a, s);
 }
 
 }  // namespace dit

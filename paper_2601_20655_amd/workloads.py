@@ -39,6 +39,9 @@ CONFIGS = {
     # q/k/v projection (three weights stacked along the output axis) and the output projection
     "qkv_proj_14b": dict(kind="linear", M=32760, N=3 * 5120, K=5120, seed=20655 + 10),
     "out_proj_14b": dict(kind="linear", M=32760, N=5120, K=5120, seed=20655 + 11),
+    # the front of a block at 14B width: the q/k/v projection of 32,760 token rows, then self-attention on its output
+    "qkv_attn_14b": dict(kind="qkv_attn", grid=(21, 30, 52), split=(44, 42, 42), H=40, D=128, K=5120,
+                         seed=20655 + 13),
     # all-elements comparison: two full tiles and a ragged one along both M and N, three K steps
     "proj_small": dict(kind="linear", M=600, N=520, K=192, seed=20655 + 12),
 }

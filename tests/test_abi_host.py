@@ -180,6 +180,44 @@ def test_cross_attn_key_counts_rejections():
     assert call(cross_params(), q=0) == B.DIT_ERR_INVALID_ARG
 
 
+def test_fused_qkv_projection_rejections():
+    """dit_qkv_proj_forward checks everything before any launch; an accepted parameter set stops at
+    DIT_ERR_WORKSPACE here because no workspace is passed."""
+    f = B.lib().dit_qkv_proj_forward
+
+    def call(ap, M=24, N=768, K=64, ldx=None, ldw=None, x=FAKE, w=FAKE, bias=FAKE, q=FAKE, out_dtype=B.DIT_BF16,
+             lflags=0):
+        lp = B.dit_linear_params(M, N, K, K if ldx is None else ldx, K if ldw is None else ldw, N, out_dtype, lflags)
+        return f(x, w, bias, q, ctypes.byref(lp), ctypes.byref(ap), None, 0, None)
+
+    assert call(self_params()) == B.DIT_ERR_WORKSPACE                                  # accepted
+    assert call(self_params(), bias=None) == B.DIT_ERR_WORKSPACE
+    assert call(self_params(flags=B.DIT_FLAG_QK_BF16 | B.DIT_FLAG_PV_BF16)) == B.DIT_ERR_WORKSPACE
+    assert call(self_params(), x=None) == B.DIT_ERR_INVALID_ARG
+    assert call(self_params(), q=None) == B.DIT_ERR_INVALID_ARG
+    assert call(self_params(), M=25) == B.DIT_ERR_INVALID_ARG                          # rows are not the grid's tokens
+    assert call(self_params(), N=512) == B.DIT_ERR_INVALID_ARG                         # not 3 H D features
+    assert call(self_params(), ldx=32) == B.DIT_ERR_INVALID_ARG
+    assert call(self_params(), out_dtype=B.DIT_F32) == B.DIT_ERR_INVALID_ARG
+    assert call(self_params(), lflags=1) == B.DIT_ERR_INVALID_ARG
+    assert call(self_params(), K=72, ldx=72, ldw=72) == B.DIT_ERR_UNSUPPORTED          # K is not a multiple of 64
+    assert call(self_params(), x=FAKE + 2) == B.DIT_ERR_ALIGNMENT
+    assert call(self_params(), ldw=68) == B.DIT_ERR_ALIGNMENT
+    assert call(self_params(), bias=FAKE + 2) == B.DIT_ERR_ALIGNMENT
+    # what the fused form does not cover: several sequences, an odd number of heads, head_dim 64, fp32 rows,
+    # normalised q/k, the other attention kernels, tiles that are already resident
+    assert call(self_params(B_=2)) == B.DIT_ERR_UNSUPPORTED
+    assert call(self_params(H=3), N=1152) == B.DIT_ERR_UNSUPPORTED
+    assert call(self_params(D=64, split=(22, 20, 22)), N=384) == B.DIT_ERR_UNSUPPORTED
+    assert call(self_params(in_dtype=B.DIT_F32)) == B.DIT_ERR_UNSUPPORTED
+    for fl in (B.DIT_FLAG_KV_RESIDENT, B.DIT_FLAG_MFMA_32X32, B.DIT_FLAG_SIMPLE_SCHEDULE, B.DIT_FLAG_KV_FUSED,
+               B.DIT_FLAG_QK_FP8, B.DIT_FLAG_WIDE_QTILE):
+        assert call(self_params(flags=fl)) == B.DIT_ERR_UNSUPPORTED, fl
+    p = self_params()
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, 1e-6, None, None)
+    assert call(p) == B.DIT_ERR_UNSUPPORTED
+
+
 def test_qk_norm_arguments():
     L, H = 24, 2
     base = B.dit_attn_workspace_bytes(self_params())

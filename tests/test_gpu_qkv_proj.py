@@ -1,0 +1,89 @@
+"""GPU parity of the fused q/k/v projection (dit_qkv_proj_forward) followed by self-attention on the tile images
+it leaves in the workspace (dit_attn_forward with DIT_FLAG_KV_RESIDENT, k = v = None).
+
+What is compared, all against the CPU fp64 oracle: y = oracle.linear(x, w, bias) in float64; its q columns,
+rounded to bf16 as the library stores them, against q_out; and oracle.self_attn on (that rounded q, the k and v
+columns of y as they are) against the attention output -- k and v are never rounded to bf16 on the fused path, they
+are rounded once to the operand type, so the ordinary 16-bit bar applies.  A second check compares with the library's
+own unfused route on fp32 rows (projection with fp32 output, then attention on fp32 q, k, v), which differs from the
+fused one only in where the rounding to the operand type happens: tight agreement, and it localises a failure."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2601_20655_amd import binding as B
+from paper_2601_20655_amd import workloads as wl
+from gpu_util import TOL, compare, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+SPLIT = (44, 42, 42)
+
+
+def inputs(L, H, K, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((L, K)).astype(np.float32)
+    w = (rng.standard_normal((3 * H * D, K)) / np.sqrt(K)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(3 * H * D)).astype(np.float32)
+    return tuple(wl.f32_to_bf16_bits(a) for a in (x, w, b))
+
+
+@pytest.mark.parametrize("grid,H,K", [((3, 10, 26), 2, 256), ((2, 9, 25), 4, 192), ((1, 8, 8), 2, 64),
+                                      ((5, 12, 23), 6, 128)])
+@pytest.mark.parametrize("flags", [0, B.DIT_FLAG_QK_BF16 | B.DIT_FLAG_PV_BF16])
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_fused_projection_then_attention(grid, H, K, flags, with_bias):
+    import torch
+
+    L = grid[0] * grid[1] * grid[2]
+    xb, wb, bb = inputs(L, H, K, seed=L + H + K)
+    y = oracle.linear(xb, wb, bb if with_bias else None)                         # [L, 3 H D] float64
+    HD = H * D
+    q_ref = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(y[:, :HD].astype(np.float32)))  # as stored
+    k_ref = y[:, HD:2 * HD].astype(np.float32)
+    v_ref = y[:, 2 * HD:].astype(np.float32)
+    shape = (1, L, H, D)
+    ref = oracle.self_attn(q_ref.reshape(shape), k_ref.reshape(shape), v_ref.reshape(shape), grid, SPLIT)
+
+    x, w = to_dev(xb), to_dev(wb)
+    bias = to_dev(bb) if with_bias else None
+    q_out, ws = B.dit_qkv_proj_forward(x, w, bias, grid, SPLIT, H, flags=flags)
+    torch.cuda.synchronize()
+    # q rows: the projection's own bar (fp32 accumulation of K terms, half a bf16 unit for the store)
+    compare(to_f64(q_out).reshape(L, HD), y[:, :HD], bf16_out=True, tol=2.0 ** -22 * K ** 0.5, what="q rows")
+    out = B.dit_attn_forward(q_out, None, None, grid, SPLIT, flags=flags | B.DIT_FLAG_KV_RESIDENT, workspace=ws,
+                             out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    bf16_ops = bool(flags & B.DIT_FLAG_QK_BF16)
+    compare(to_f64(out), ref, tol=2 * TOL if bf16_ops else TOL, what="fused projection + attention, flags %d" % flags)
+
+    # the unfused route on fp32 rows: same values into the same kernels, rounded at the same point
+    y32 = B.dit_linear_forward(x, w, bias, out_dtype=torch.float32)
+    k32 = y32[:, HD:2 * HD].reshape(shape)
+    v32 = y32[:, 2 * HD:].reshape(shape)
+    out2 = B.dit_attn_forward(q_out.float(), k32, v32, grid, SPLIT, flags=flags, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    diff = float((out - out2).abs().max()) / rms
+    print("fused vs unfused fp32 route: max diff %.2e x RMS" % diff)
+    assert diff <= (8e-3 if bf16_ops else 1e-3)
+
+
+def test_fused_projection_rejections():
+    import torch
+
+    grid, H, K = (1, 8, 8), 2, 64
+    xb, wb, bb = inputs(64, H, K, seed=3)
+    x, w, b = to_dev(xb), to_dev(wb), to_dev(bb)
+    for bad in (B.DIT_FLAG_KV_RESIDENT, B.DIT_FLAG_MFMA_32X32, B.DIT_FLAG_SIMPLE_SCHEDULE, B.DIT_FLAG_QK_FP8):
+        with pytest.raises(B.DitError):
+            B.dit_qkv_proj_forward(x, w, b, grid, SPLIT, H, flags=bad)
+    with pytest.raises(ValueError):
+        B.dit_qkv_proj_forward(x, w[:-8], b, grid, SPLIT, H)
+    with pytest.raises(ValueError):
+        B.dit_qkv_proj_forward(x, w, b, (1, 8, 9), SPLIT, H)
+    xb3, wb3, bb3 = inputs(64, 3, K, seed=4)   # an odd number of heads: a 256-feature tile would straddle q and k
+    with pytest.raises(B.DitError):
+        B.dit_qkv_proj_forward(to_dev(xb3), to_dev(wb3), to_dev(bb3), grid, SPLIT, 3)
+    torch.cuda.synchronize()
