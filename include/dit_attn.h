@@ -374,8 +374,12 @@ dit_status dit_mfma_probe(int32_t operand_dtype, int32_t bits_a, int32_t bits_b,
  *   x [M, K] bf16 (row stride lp->ldx), w [3*H*D, K] bf16 (lp->ldw), bias [3*H*D] bf16 or NULL: DEVICE pointers.
  *   lp: M = T*Hg*Wg of ap, N = 3*H*D, K a multiple of 64, out_dtype DIT_BF16, flags 0; ldy is ignored.
  *   ap: the parameters of the attention call that follows, without DIT_FLAG_KV_RESIDENT.  Covered: B = 1,
- *       D = 128, an even H, in_dtype DIT_BF16, no normalisation, flags that select the default attention kernel
- *       (operand-type flags are honoured); anything else DIT_ERR_UNSUPPORTED.  sk, sv are ignored.
+ *       D = 128, an even H, in_dtype DIT_BF16, flags that select the default attention kernel (operand-type
+ *       flags are honoured), norm.mode DIT_NORM_NONE or DIT_NORM_HEAD; anything else DIT_ERR_UNSUPPORTED.
+ *       sk, sv are ignored.  With DIT_NORM_HEAD the k rows are normalised here, in fp32 on the accumulators
+ *       (norm.eps, norm.k_gamma), before the rotation; the q rows are stored as they are and the attention call,
+ *       given the same norm, normalises them as it reads them.  DIT_NORM_TOKEN is not covered: its mean runs
+ *       over all heads of a token, which no single output tile of the projection holds.
  *   workspace: dit_attn_workspace_bytes(ap) bytes, 256-byte aligned; written: rotation table and every tile image.
  * Errors as dit_linear_forward and dit_attn_forward; nothing is enqueued unless all checks pass. */
 dit_status dit_qkv_proj_forward(const void *x, const void *w, const void *bias, void *q_out,

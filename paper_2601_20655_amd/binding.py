@@ -536,12 +536,13 @@ def dit_linear_forward(x, w, bias=None, out=None, out_dtype=None, stream=None):
 
 
 def dit_qkv_proj_forward(x, w, bias, grid, split, H, q_out=None, origin=(0, 0, 0), rope_base=10000.0, scale=0.0,
-                         flags=0, workspace=None, stream=None):
+                         flags=0, workspace=None, stream=None, norm=None):
     """Fused q/k/v projection in front of dit_attn_forward: x [L, K] bf16, w [3*H*128, K] bf16 (rows [q; k; v]),
     bias [3*H*128] bf16 or None, L = T*Hg*Wg.  Returns (q_out [1, L, H, 128] bf16, workspace): the workspace then
     holds the rotation table and the K'/V^T tile images, and
         dit_attn_forward(q_out, k=None, v=None, grid, split, flags=flags | DIT_FLAG_KV_RESIDENT, workspace=workspace)
-    completes the attention (pass any [1, L, H, 128] tensor for k and v: they are not read)."""
+    completes the attention (k and v are not read).  norm: None or ("head", eps, q_gamma, k_gamma): the k rows are
+    normalised here; pass the same norm to dit_attn_forward, which normalises the q rows as it reads them."""
     import torch
 
     D = 128
@@ -561,7 +562,7 @@ def dit_qkv_proj_forward(x, w, bias, grid, split, H, q_out=None, origin=(0, 0, 0
         q_out = torch.empty((1, L, H, D), dtype=torch.bfloat16, device=x.device)
     if tuple(q_out.shape) != (1, L, H, D) or q_out.dtype != torch.bfloat16 or q_out.device != x.device:
         raise ValueError("q_out must be a bfloat16 [1, L, H, 128] tensor on the device of x")
-    ap = self_attn_params(q_out, q_out, q_out, q_out, grid, split, origin, rope_base, scale, flags)
+    ap = self_attn_params(q_out, q_out, q_out, q_out, grid, split, origin, rope_base, scale, flags, norm)
     lp = dit_linear_params(L, 3 * H * D, x.shape[1], x.stride(0), w.stride(0), 3 * H * D, DIT_BF16, 0)
     need = dit_attn_workspace_bytes(ap)
     if workspace is None:

@@ -746,8 +746,9 @@ dit_status dit_qkv_proj_forward(const void* x, const void* w, const void* bias, 
     dit_status st = plan_self(ap, &pl);
     if (st != DIT_OK) return st;
     // what the fused form covers: one sequence, head_dim 128, an even number of heads (a 256-feature tile is two
-    // heads of one of q, k, v), 16-bit rows, no normalisation, the default attention kernel's tile images
-    if (ap->B != 1 || ap->D != 128 || (ap->H & 1) || ap->in_dtype != DIT_BF16 || ap->norm.mode != DIT_NORM_NONE ||
+    // heads of one of q, k, v), 16-bit rows, the default attention kernel's tile images; of the q/k normalisations
+    // the per-head one (a head's channels are inside a tile; a token-wide mean spans every tile of the k part)
+    if (ap->B != 1 || ap->D != 128 || (ap->H & 1) || ap->in_dtype != DIT_BF16 || ap->norm.mode == DIT_NORM_TOKEN ||
         !self_attn_uses_mfma16(pl.fl) || pl.fl.resident)
         return DIT_ERR_UNSUPPORTED;
     if (lp->flags != 0 || lp->out_dtype != DIT_BF16) return DIT_ERR_INVALID_ARG;
@@ -801,6 +802,9 @@ dit_status dit_qkv_proj_forward(const void* x, const void* w, const void* bias, 
     a.qkv_sq_h = ap->sq.head;
     a.qkv_qk_f16 = pl.fl.qk_op == dit::OP_F16;
     a.qkv_pv_f16 = pl.fl.pv_op == dit::OP_F16;
+    a.qkv_norm = ap->norm.mode == DIT_NORM_HEAD;
+    a.qkv_eps = ap->norm.eps;
+    a.qkv_kgamma = ap->norm.k_gamma;
     if ((int64_t)a.nTM * a.nTN > 0x7fffffff) return DIT_ERR_UNSUPPORTED;
     const bool timed = g_ev_before && g_ev_after;
     if (timed && (e = hipEventRecord(g_ev_before, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");

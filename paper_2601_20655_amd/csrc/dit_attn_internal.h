@@ -202,6 +202,9 @@ struct LinearArgs {
     RopeGeom qkv_rg;
     int64_t qkv_sq_t, qkv_sq_h;  // element strides of the q rows in y
     int qkv_qk_f16, qkv_pv_f16;  // operand types of the two tile parts: fp16 (saturating) or bf16
+    int qkv_norm;                // 1: k rows are RMS-normalised over the head's channels before the rotation
+    float qkv_eps;
+    const float* qkv_kgamma;     // nullable [H*128]
 };
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
 

@@ -59,8 +59,9 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-template <bool OUT_F32, bool QKV>
+template <bool OUT_F32, int QKV>
 __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearArgs a) {
+    // QKV: 0 plain rows; 1 the fused q/k/v form; 2 the same with the k rows RMS-normalised per head
     static_assert(!(OUT_F32 && QKV), "the fused q/k/v form writes 16-bit rows and tiles");
     static_assert(kLinBM == 256 && kLinBN == 256 && kLinBK == 64, "tile shape");
     constexpr int SX = kLinSX, SW = kLinSW, NW = kLinWaves;
@@ -312,6 +313,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     // to y; k rows to the K' part of the token's tile image (row = key, its 16-byte chunks in the image's swizzled
     // order); v rows transposed: a lane gathers, for one channel, the eight keys of a V^T chunk in the order the
     // attention kernel's PV operand wants them (pack_tile, layout 1) and writes the chunk to the V^T part.
+    // With the per-head RMS normalisation the k rows are scaled first (hd0 + ... indexes the [H*128] weights).
     auto store_tile_qkv = [&](int tm, int tn, int stage_buf) __attribute__((always_inline)) {
         using G = TileGeom<128>;
         constexpr int RB = 128, PR = 8, RP = 32, TBP = 2;
@@ -330,15 +332,65 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb) {
             bb[fb] = make_uint2(0u, 0u);
-            if (a.bias) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n_wave + fb * BR + 4 * lg);
+            if (QKV != 2 && a.bias) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n_wave + fb * BR + 4 * lg);
         }
         uint8_t* const region = smem + stage_buf * kLinTileBytes + wave * 4096;
+        // RMS normalisation of the k rows over the head's 128 channels, in fp32 on the accumulators (a tile is one
+        // part, so the whole workgroup takes this branch or none of it does).  This wavefront holds 64 of a head's
+        // channels and wavefront wave ^ 2 the other 64: pass by pass the two exchange the sums of squares of the
+        // pass's 32 tokens through the staging regions (two at a time: the tile stream leaves few registers), and
+        // the rows are scaled as they are staged.
+        const bool normed = QKV == 2 && part == 1;
+        if constexpr (QKV == 2) {
+            // (the bias goes into the accumulators first: its registers are needed below)
+#pragma unroll
+            for (int fb = 0; fb < FB; ++fb) {
+                uint2 b = make_uint2(0u, 0u);
+                if (a.bias) b = *reinterpret_cast<const uint2*>(a.bias + n_wave + fb * BR + 4 * lg);
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    acc[fb][tb][0] += __uint_as_float(b.x << 16);
+                    acc[fb][tb][1] += __uint_as_float(b.x & 0xffff0000u);
+                    acc[fb][tb][2] += __uint_as_float(b.y << 16);
+                    acc[fb][tb][3] += __uint_as_float(b.y & 0xffff0000u);
+                }
+            }
+        }
         uint8_t* const tiles_h = a.qkv_tiles + (size_t)h * a.qkv_nKT * G::TILE_BYTES;
         const int rrow = ln / PR, rp = ln % PR;
         const int tok_end = a.qkv_nKT * kBK;  // slots of the sequence's tiles
 #pragma unroll
         for (int pass = 0; pass < TB / TBP; ++pass) {
             const int tok0 = tm * kLinBM + wt * BR * TB + pass * RP;  // a multiple of 32: half a key tile
+            float rs2[TBP] = {1.f, 1.f};
+            if (normed) {
+                float* const mine = reinterpret_cast<float*>(region);
+                const float* const theirs =
+                    reinterpret_cast<const float*>(smem + stage_buf * kLinTileBytes + (wave ^ 2) * 4096);
+#pragma unroll
+                for (int hh = 0; hh < TBP; ++hh) {
+                    const int tb = pass * TBP + hh;
+                    float ss = 0.f;
+#pragma unroll
+                    for (int fb = 0; fb < FB; ++fb) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ss = fmaf(acc[fb][tb][e], acc[fb][tb][e], ss);
+                    }
+                    ss += __shfl_xor(ss, 16);
+                    ss += __shfl_xor(ss, 32);
+                    if (lg == 0) mine[hh * BR + lr] = ss;
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int hh = 0; hh < TBP; ++hh)
+                    rs2[hh] = 1.0f / sqrtf((mine[hh * BR + lr] + theirs[hh * BR + lr]) * (1.0f / 128.0f) + a.qkv_eps);
+                // the partner has read this region before the staging below overwrites it
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
 #pragma unroll
             for (int hh = 0; hh < TBP; ++hh) {
                 const int tb = pass * TBP + hh;
@@ -350,8 +402,22 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                 for (int fb = 0; fb < FB; ++fb) {
                     const float b0 = __uint_as_float(bb[fb].x << 16), b1 = __uint_as_float(bb[fb].x & 0xffff0000u);
                     const float b2 = __uint_as_float(bb[fb].y << 16), b3 = __uint_as_float(bb[fb].y & 0xffff0000u);
-                    float y0 = acc[fb][tb][0] + b0, y1 = acc[fb][tb][1] + b1;
-                    float y2 = acc[fb][tb][2] + b2, y3 = acc[fb][tb][3] + b3;
+                    float y0 = acc[fb][tb][0], y1 = acc[fb][tb][1], y2 = acc[fb][tb][2], y3 = acc[fb][tb][3];
+                    if constexpr (QKV != 2) {
+                        y0 += b0;
+                        y1 += b1;
+                        y2 += b2;
+                        y3 += b3;
+                    }
+                    if (normed) {
+                        float4 g = make_float4(1.f, 1.f, 1.f, 1.f);
+                        if (a.qkv_kgamma) g = *reinterpret_cast<const float4*>(a.qkv_kgamma + hd0 + fb * BR + 4 * lg);
+                        const float rs = rs2[hh];
+                        y0 *= rs * g.x;
+                        y1 *= rs * g.y;
+                        y2 *= rs * g.z;
+                        y3 *= rs * g.w;
+                    }
                     if (part == 1) {  // the two rotation pairs of channels c0 + 16 fb + 4 lg .. + 3
                         const RopeGeom& rg = a.qkv_rg;
 #pragma unroll
@@ -522,7 +588,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the surplus loads of the last steps
 }
 
-template <bool OUT_F32, bool QKV>
+template <bool OUT_F32, int QKV>
 hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
     auto kern = linear_kernel<OUT_F32, QKV>;
     constexpr int smem = (kLinSX + kLinSW) * kLinTileBytes;
@@ -543,7 +609,7 @@ hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s) {
-    if (a.qkv) return launch_linear_inst<false, true>(a, s);
+    if (a.qkv) return a.qkv_norm ? launch_linear_inst<false, 2>(a, s) : launch_linear_inst<false, 1>(a, s);
     return a.out_f32 ? launch_linear_inst<true, false>(a, s) : launch_linear_inst<false, false>(a, s);
 }
 

@@ -215,6 +215,10 @@ def test_fused_qkv_projection_rejections():
         assert call(self_params(flags=fl)) == B.DIT_ERR_UNSUPPORTED, fl
     p = self_params()
     p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, 1e-6, None, None)
+    assert call(p) == B.DIT_ERR_WORKSPACE                                              # accepted: tile-local
+    p.norm = B.dit_qk_norm(B.DIT_NORM_HEAD, 1e-6, None, 0x20004)
+    assert call(p) == B.DIT_ERR_ALIGNMENT
+    p.norm = B.dit_qk_norm(B.DIT_NORM_TOKEN, 1e-6, None, None)
     assert call(p) == B.DIT_ERR_UNSUPPORTED
 
 

@@ -70,6 +70,38 @@ def test_fused_projection_then_attention(grid, H, K, flags, with_bias):
     assert diff <= (8e-3 if bf16_ops else 1e-3)
 
 
+@pytest.mark.parametrize("grid,H,K", [((3, 10, 26), 2, 256), ((2, 9, 25), 4, 128)])
+@pytest.mark.parametrize("with_gamma", [True, False])
+def test_fused_projection_with_head_norm(grid, H, K, with_gamma):
+    """Per-head RMS normalisation: k in the projection's epilogue, q in the attention kernel."""
+    import torch
+
+    L = grid[0] * grid[1] * grid[2]
+    xb, wb, bb = inputs(L, H, K, seed=7 * L + H)
+    rng = np.random.default_rng(L)
+    gq = (1.0 + 0.3 * rng.standard_normal(H * D)).astype(np.float32) if with_gamma else None
+    gk = (1.0 + 0.3 * rng.standard_normal(H * D)).astype(np.float32) if with_gamma else None
+    eps = 1e-6
+    y = oracle.linear(xb, wb, bb)
+    HD = H * D
+    shape = (1, L, H, D)
+    q_ref = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(y[:, :HD].astype(np.float32))).reshape(shape)
+    k_ref = y[:, HD:2 * HD].reshape(shape)
+    v_ref = y[:, 2 * HD:].reshape(shape)
+    ref = oracle.self_attn_normed(q_ref, k_ref, v_ref, grid, SPLIT,
+                                  q_gamma=None if gq is None else gq.reshape(H, D),
+                                  k_gamma=None if gk is None else gk.reshape(H, D), eps=eps, mode="head")
+    norm = ("head", eps, None if gq is None else torch.from_numpy(gq).cuda(),
+            None if gk is None else torch.from_numpy(gk).cuda())
+    q_out, ws = B.dit_qkv_proj_forward(to_dev(xb), to_dev(wb), to_dev(bb), grid, SPLIT, H, norm=norm)
+    out = B.dit_attn_forward(q_out, None, None, grid, SPLIT, flags=B.DIT_FLAG_KV_RESIDENT, workspace=ws,
+                             out_dtype=torch.float32, norm=norm)
+    torch.cuda.synchronize()
+    compare(to_f64(out), ref, what="fused projection with per-head normalisation")
+    with pytest.raises(B.DitError):   # the token-wide mean spans all of a token's heads: not a tile's to compute
+        B.dit_qkv_proj_forward(to_dev(xb), to_dev(wb), to_dev(bb), grid, SPLIT, H, norm=("token", eps, None, None))
+
+
 def test_fused_projection_rejections():
     import torch
 
