@@ -473,10 +473,9 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
         if constexpr (!LATE) dma_wait_and_sync();
         if constexpr (MASKED) {
             const uint64_t mnext = mask_of(j + 1);
-            if (mnext != ~0ull) {
-                mask_apply(Sn, mnext);
-                need = true;
-            }
+            // (the maxima above were taken before the mask: they can only call for a shift that is not needed,
+            // never miss one, and a masked score is -inf, which every path below takes as it is)
+            if (mnext != ~0ull) mask_apply(Sn, mnext);
             // after the last tile these are scores of a stale buffer: never let them touch the state
             need = need && j < last;
         }
