@@ -633,6 +633,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
             static_assert(RPP >= 1 && 16 % RPP == 0 && PR <= 64 && 64 % PR == 0 && (RPP * RB) % 1024 == 0,
                           "staging geometry");
             const int row0 = qt * BQ + wave * 32;
+            const bool full = row0 + 32 <= pv.Lq;  // wavefront-uniform
 #pragma unroll
             for (int pass = 0; pass < 32 / RPP; ++pass) {
                 const int qb = pass * RPP / 16;
@@ -649,14 +650,36 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
                         else *reinterpret_cast<uint2*>(dst) = make_uint2(pack2<OP_BF16>(o0, o1), pack2<OP_BF16>(o2, o3));
                     }
                 }
+                // all of a pass's pieces are read back before the first is stored, and a tile that lies inside the
+                // sequence stores without a row test: with a test per store each read sat in a branch of its own
+                // and was waited for there, sixteen LDS round trips one after the other per query tile
+                constexpr int NK = RPP * RB / 1024;
+                static_assert(NK == 2 || NK % 4 == 0, "pieces are read back two or four at a time");
+                u32x4 v[NK];
 #pragma unroll
-                for (int k = 0; k < RPP * RB / 1024; ++k) {
+                for (int k = 0; k < NK; ++k) {
                     const int r = k * (64 / PR) + ln / PR, pc = ln % PR;
-                    const uint4 v = *reinterpret_cast<const uint4*>(region + r * RB + ((pc ^ (r & (PR - 1))) << 4));
-                    const int row = row0 + pass * RPP + r;
-                    if (row < pv.Lq)
-                        *reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.out) +
-                                                  (pv.o_off + (int64_t)row * a.so_t) * ES + pc * 16) = v;
+                    v[k] = *reinterpret_cast<const u32x4*>(region + r * RB + ((pc ^ (r & (PR - 1))) << 4));
+                }
+                // (four values the compiler must hold at once: left alone it sinks each read to its store)
+                if constexpr (NK == 2) {
+                    asm volatile("" : "+v"(v[0]), "+v"(v[1])::"memory");
+                } else {
+#pragma unroll
+                    for (int k = 0; k < NK; k += 4)
+                        asm volatile("" : "+v"(v[k]), "+v"(v[k + 1]), "+v"(v[k + 2]), "+v"(v[k + 3])::"memory");
+                }
+                uint8_t* const obase = static_cast<uint8_t*>(a.out) +
+                                       (pv.o_off + (int64_t)(row0 + pass * RPP + ln / PR) * a.so_t) * ES + (ln % PR) * 16;
+                const int64_t kstride = (int64_t)(64 / PR) * a.so_t * ES;
+                if (full) {
+#pragma unroll
+                    for (int k = 0; k < NK; ++k) *reinterpret_cast<u32x4*>(obase + k * kstride) = v[k];
+                } else {
+#pragma unroll
+                    for (int k = 0; k < NK; ++k)
+                        if (row0 + pass * RPP + k * (64 / PR) + ln / PR < pv.Lq)
+                            *reinterpret_cast<u32x4*>(obase + k * kstride) = v[k];
                 }
             }
         };
