@@ -50,6 +50,14 @@ __device__ __forceinline__ float max_across_rows16(float x) {
     return max_across_halves(fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])));
 }
 
+// The same for a sum (x of (i, g) + x of (i, g ^ 1), then the two halves): no trip through the LDS crossbar.
+__device__ __forceinline__ float sum_across_rows16(float x) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float s = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+    return __uint_as_float(h[0]) + __uint_as_float(h[1]);
+}
+
 // Multiplier 1/sqrt(mean(x^2) + eps) of one q row whose D channels are read by the four lanes (i, 0..3), lane
 // row g taking the 16-byte chunks 4 ks + g.
 template <int D>
@@ -615,9 +623,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
         float inv[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            float l = l_run[qb];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
+            const float l = sum_across_rows16(l_run[qb]);
             inv[qb] = l > 0.f ? 1.0f / l : 0.f;
             const int row = qt * BQ + wave * 32 + qb * 16 + li;
             if (a.lse && lg == 0 && row < pv.Lq) {
