@@ -464,6 +464,8 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                         }
                     const int kc = 4 * half + j;
                     const int kcs = kc ^ (((dch >> 2) ^ (dch >> 3)) & 1);
+                    // (the rows' 16 pad bytes stay unwritten here: writing them, which takes a third off the
+                    // stand-alone pre-pack pass, measured level in this epilogue and costs it registers)
                     if (tok0 < tok_end)
                         *reinterpret_cast<uint4*>(tiles_h + (size_t)tile * G::TILE_BYTES + G::K_BYTES + dch * G::VROW +
                                                   kcs * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);

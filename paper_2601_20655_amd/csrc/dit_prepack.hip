@@ -141,11 +141,15 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
             // channels of q' finds it: contraction step c / 8, lane half c % 2, slot (c / 2) % 4
             const int off = (c >> 3) * 64 + (c & 1) * 32 + ((c >> 1) & 3) * 8;
             *reinterpret_cast<uint2*>(t.dst + r * G::KROW8 + off) = pack8_fp8(xk);
+            if (c == CPR - 1) *reinterpret_cast<u32x4*>(t.dst + r * G::KROW8 + D) = mk4(0u, 0u, 0u, 0u);  // the pad, see below
             if (c == 0) t.dst[G::KSCALE_OFF + r] = (uint8_t)(127 - ex);
         } else {
             // (layout 1: rows 4..11 of every 16 keep their 16-byte chunks in swapped pairs, see below)
             const int cs = a.v_layout ? c ^ (((r >> 2) ^ (r >> 3)) & 1) : c;
             *reinterpret_cast<u32x4*>(t.dst + r * G::KROW + cs * 16) = pack8<QK_OP>(xk);
+            // the 16 pad bytes behind the row are written too (zeros): a part is then a run of fully written
+            // 32-byte sectors, and none of them has to be read back from memory to be completed
+            if (c == CPR - 1) *reinterpret_cast<u32x4*>(t.dst + r * G::KROW + D * 2) = mk4(0u, 0u, 0u, 0u);
         }
         const u32x4 pv = pack8<PV_OP>(xv);
         uint32_t* row = reinterpret_cast<uint32_t*>(vs + r * VS + 8 * c);
@@ -178,6 +182,7 @@ __device__ __forceinline__ void pack_tile(const PackArgs& a, const PackTile& t, 
         // instead of 4); with the swap each cycle's 16 lanes cover the 16 bank groups once.
         const int kcs = a.v_layout ? kc ^ (((d >> 2) ^ (d >> 3)) & 1) : kc;
         *reinterpret_cast<u32x4*>(t.dst + G::K_BYTES + d * G::VROW + kcs * 16) = mk4(w[0], w[1], w[2], w[3]);
+        if (kc == 7) *reinterpret_cast<u32x4*>(t.dst + G::K_BYTES + d * G::VROW + kBK * 2) = mk4(0u, 0u, 0u, 0u);
     }
 }
 
