@@ -833,6 +833,6 @@ const char* dit_strerror(dit_status s) {
 
 const char* dit_last_hip_error(void) { return g_hip_error; }
 
-int dit_attn_version(void) { return 10400; }  // 1.4.0
+int dit_attn_version(void) { return 10500; }  // 1.5.0
 
 }  // extern "C"

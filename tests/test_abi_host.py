@@ -30,7 +30,7 @@ def test_header_symbols_are_exported():
 def test_version_and_strerror():
     ver = B.dit_attn_version()  # major*10000 + minor*100 + patch, as the header documents
     major, minor, patch = ver // 10000, ver // 100 % 100, ver % 100
-    assert major >= 1 and 0 <= minor < 100 and 0 <= patch < 100 and ver >= 10400
+    assert major >= 1 and 0 <= minor < 100 and 0 <= patch < 100 and ver >= 10500
     assert B.dit_strerror(B.DIT_OK) == "ok"
     for code in (-1, -2, -3, -4, -5):
         assert B.dit_strerror(code) not in ("", "ok", "unknown status")
