@@ -365,18 +365,21 @@ dit_status dit_mfma_probe(int32_t operand_dtype, int32_t bits_a, int32_t bits_b,
 
 /* The fused q/k/v projection in front of self-attention (Sec. 2.4: a transformer block of the Diffusion stage projects
  * its token rows to queries, keys and values and attends): y = x w^T + bias with the rows of w ordered [q; k; v],
- * H*D rows each (N = 3*H*D).  The q rows are stored to q_out as they come out (bf16, strides ap->sq); the k rows are
- * rotated (the RoPE of dit_attn_forward for ap's grid, sections, origin and base), rounded ONCE to the score operand
- * type and written, with the v rows (rounded to the PV operand type, transposed), as the K'/V^T tile images that
- * dit_attn_forward keeps in its workspace.  A following
+ * H*D rows each (N = 3*H*D).  The q rows are stored to q_out as they come out (bf16, strides ap->sq); the k and v
+ * values are rounded to bf16 as the rows of dit_linear_forward would be, the k values then rotated (the RoPE of
+ * dit_attn_forward for ap's grid, sections, origin and base) and rounded to the score operand type, the v values
+ * rounded to the PV operand type and transposed, and both written as the K'/V^T tile images that dit_attn_forward
+ * keeps in its workspace.  A following
  *     dit_attn_forward(q_out, NULL, NULL, out, lse, ap' = ap with flags | DIT_FLAG_KV_RESIDENT, workspace, ...)
- * on the same workspace then needs no pre-pack pass, and k and v never exist as rows in memory.
+ * on the same workspace then needs no pre-pack pass, k and v never exist as rows in memory, and (without a
+ * normalisation) its result is bit for bit that of dit_linear_forward with bf16 output followed by
+ * dit_attn_forward on the q, k, v columns of that output.
  *   x [M, K] bf16 (row stride lp->ldx), w [3*H*D, K] bf16 (lp->ldw), bias [3*H*D] bf16 or NULL: DEVICE pointers.
  *   lp: M = T*Hg*Wg of ap, N = 3*H*D, K a multiple of 64, out_dtype DIT_BF16, flags 0; ldy is ignored.
  *   ap: the parameters of the attention call that follows, without DIT_FLAG_KV_RESIDENT.  Covered: B = 1,
  *       D = 128, an even H, in_dtype DIT_BF16, flags that select the default attention kernel (operand-type
  *       flags are honoured), norm.mode DIT_NORM_NONE or DIT_NORM_HEAD; anything else DIT_ERR_UNSUPPORTED.
- *       sk, sv are ignored.  With DIT_NORM_HEAD the k rows are normalised here, in fp32 on the accumulators
+ *       sk, sv are ignored.  With DIT_NORM_HEAD the k rows are normalised here, in fp32 on the bf16-rounded values
  *       (norm.eps, norm.k_gamma), before the rotation; the q rows are stored as they are and the attention call,
  *       given the same norm, normalises them as it reads them.  DIT_NORM_TOKEN is not covered: its mean runs
  *       over all heads of a token, which no single output tile of the projection holds.

@@ -539,7 +539,7 @@ def dit_qkv_proj_forward(x, w, bias, grid, split, H, q_out=None, origin=(0, 0, 0
                          flags=0, workspace=None, stream=None, norm=None):
     """Fused q/k/v projection in front of dit_attn_forward: x [L, K] bf16, w [3*H*128, K] bf16 (rows [q; k; v]),
     bias [3*H*128] bf16 or None, L = T*Hg*Wg.  Returns (q_out [1, L, H, 128] bf16, workspace): the workspace then
-    holds the rotation table and the K'/V^T tile images, and
+    holds the rotation table and the K'/V^T tile images (k and v rounded to bf16 first, as dit_linear_forward's rows), and
         dit_attn_forward(q_out, k=None, v=None, grid, split, flags=flags | DIT_FLAG_KV_RESIDENT, workspace=workspace)
     completes the attention (k and v are not read).  norm: None or ("head", eps, q_gamma, k_gamma): the k rows are
     normalised here; pass the same norm to dit_attn_forward, which normalises the q rows as it reads them."""

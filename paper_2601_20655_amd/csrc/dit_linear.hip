@@ -182,8 +182,8 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
     int koff[NKS];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) koff[ks] = ((4 * ks + lg) ^ sw) * 16;
-    const int xread = (wt * BR * TB + lr) * ROWB;
-    const int wread = kWBase + (wf * BR * FB + lr) * ROWB;
+    int xread = (wt * BR * TB + lr) * ROWB;
+    int wread = kWBase + (wf * BR * FB + lr) * ROWB;
 
     f32x4 acc[FB][TB];
 #pragma unroll
@@ -341,6 +341,13 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
         // pass's 32 tokens through the staging regions (two at a time: the tile stream leaves few registers), and
         // the rows are scaled as they are staged.
         const bool normed = QKV == 2 && part == 1;
+        // k and v values pass through bf16 first, as the rows of the plain projection would: what the attention call
+        // then computes is, bit for bit, what it computes from those rows
+        auto as_bf16_row = [](float& y0, float& y1) __attribute__((always_inline)) {
+            const uint32_t u = pack2<OP_BF16>(y0, y1);
+            y0 = __uint_as_float(u << 16);
+            y1 = __uint_as_float(u & 0xffff0000u);
+        };
         if constexpr (QKV == 2) {
             // (the bias goes into the accumulators first: its registers are needed below)
 #pragma unroll
@@ -353,6 +360,15 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                     acc[fb][tb][1] += __uint_as_float(b.x & 0xffff0000u);
                     acc[fb][tb][2] += __uint_as_float(b.y << 16);
                     acc[fb][tb][3] += __uint_as_float(b.y & 0xffff0000u);
+                    if (part != 0) {
+                        float y0 = acc[fb][tb][0], y1 = acc[fb][tb][1], y2 = acc[fb][tb][2], y3 = acc[fb][tb][3];
+                        as_bf16_row(y0, y1);
+                        as_bf16_row(y2, y3);
+                        acc[fb][tb][0] = y0;
+                        acc[fb][tb][1] = y1;
+                        acc[fb][tb][2] = y2;
+                        acc[fb][tb][3] = y3;
+                    }
                 }
             }
         }
@@ -417,6 +433,10 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                         y1 *= rs * g.y;
                         y2 *= rs * g.z;
                         y3 *= rs * g.w;
+                    }
+                    if (QKV != 2 && part != 0) {
+                        as_bf16_row(y0, y1);
+                        as_bf16_row(y2, y3);
                     }
                     if (part == 1) {  // the two rotation pairs of channels c0 + 16 fb + 4 lg .. + 3
                         const RopeGeom& rg = a.qkv_rg;
@@ -580,6 +600,20 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
         if (++kt == nK) {
             if constexpr (QKV) store_tile_qkv(tm, tn, xb == 0 ? SX - 1 : xb - 1);
             else store_tile(tm, tn, xb == 0 ? SX - 1 : xb - 1);
+            if constexpr (QKV != 0) {
+                // The fused forms work the per-lane fragment offsets out again behind every store of a tile, from
+                // a lane number the compiler cannot see through: they are then new values here, not values that
+                // have to survive the store, which has no register to spare for them (kept across it, one of them
+                // was spilled and reloaded INSIDE the step loop, and a reload from scratch memory there makes the
+                // compiler wait for every load in flight).
+                int l = lane;
+                asm volatile("" : "+v"(l));
+                const int r = l & 15, g = l >> 4;
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) koff[ks] = ((4 * ks + g) ^ ((r >> 1) & 7)) * 16;
+                xread = (wt * BR * TB + r) * ROWB;
+                wread = kWBase + (wf * BR * FB + r) * ROWB;
+            }
             kt = 0;
             tile_coords(++tile, tm, tn);
         }
