@@ -378,11 +378,13 @@ dit_status dit_mfma_probe(int32_t operand_dtype, int32_t bits_a, int32_t bits_b,
  *   lp: M = T*Hg*Wg of ap, N = 3*H*D, K a multiple of 64, out_dtype DIT_BF16, flags 0; ldy is ignored.
  *   ap: the parameters of the attention call that follows, without DIT_FLAG_KV_RESIDENT.  Covered: B = 1,
  *       D = 128, an even H, in_dtype DIT_BF16, flags that select the default attention kernel (operand-type
- *       flags are honoured), norm.mode DIT_NORM_NONE or DIT_NORM_HEAD; anything else DIT_ERR_UNSUPPORTED.
- *       sk, sv are ignored.  With DIT_NORM_HEAD the k rows are normalised here, in fp32 on the bf16-rounded values
- *       (norm.eps, norm.k_gamma), before the rotation; the q rows are stored as they are and the attention call,
- *       given the same norm, normalises them as it reads them.  DIT_NORM_TOKEN is not covered: its mean runs
- *       over all heads of a token, which no single output tile of the projection holds.
+ *       flags are honoured); anything else DIT_ERR_UNSUPPORTED.  sk, sv are ignored.  With a q/k normalisation the
+ *       k rows are normalised here, in fp32 on the bf16-rounded values (norm.eps, norm.k_gamma), before the rotation;
+ *       the q rows are stored as they are and the attention call, given the same norm, normalises them as it reads
+ *       them.  DIT_NORM_HEAD is done in the projection's epilogue.  DIT_NORM_TOKEN, whose mean runs over all heads
+ *       of a token and so over every output tile of the k part, takes a second, memory-bound pass over the K' images
+ *       (k_rescale_kernel): the epilogue applies the weights and leaves each head's sum of squares in the spare
+ *       bytes of the tile images, the pass multiplies each token's K' rows by its factor (K' is rounded twice).
  *   workspace: dit_attn_workspace_bytes(ap) bytes, 256-byte aligned; written: rotation table and every tile image.
  * Errors as dit_linear_forward and dit_attn_forward; nothing is enqueued unless all checks pass. */
 dit_status dit_qkv_proj_forward(const void *x, const void *w, const void *bias, void *q_out,

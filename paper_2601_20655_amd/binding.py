@@ -541,7 +541,7 @@ def dit_qkv_proj_forward(x, w, bias, grid, split, H, q_out=None, origin=(0, 0, 0
     bias [3*H*128] bf16 or None, L = T*Hg*Wg.  Returns (q_out [1, L, H, 128] bf16, workspace): the workspace then
     holds the rotation table and the K'/V^T tile images (k and v rounded to bf16 first, as dit_linear_forward's rows), and
         dit_attn_forward(q_out, k=None, v=None, grid, split, flags=flags | DIT_FLAG_KV_RESIDENT, workspace=workspace)
-    completes the attention (k and v are not read).  norm: None or ("head", eps, q_gamma, k_gamma): the k rows are
+    completes the attention (k and v are not read).  norm: None or (mode, eps, q_gamma, k_gamma): the k rows are
     normalised here; pass the same norm to dit_attn_forward, which normalises the q rows as it reads them."""
     import torch
 

@@ -746,10 +746,11 @@ dit_status dit_qkv_proj_forward(const void* x, const void* w, const void* bias, 
     dit_status st = plan_self(ap, &pl);
     if (st != DIT_OK) return st;
     // what the fused form covers: one sequence, head_dim 128, an even number of heads (a 256-feature tile is two
-    // heads of one of q, k, v), 16-bit rows, the default attention kernel's tile images; of the q/k normalisations
-    // the per-head one (a head's channels are inside a tile; a token-wide mean spans every tile of the k part)
-    if (ap->B != 1 || ap->D != 128 || (ap->H & 1) || ap->in_dtype != DIT_BF16 || ap->norm.mode == DIT_NORM_TOKEN ||
-        !self_attn_uses_mfma16(pl.fl) || pl.fl.resident)
+    // heads of one of q, k, v), 16-bit rows, the default attention kernel's tile images.  Of the q/k normalisations
+    // the per-head one is done in the epilogue (a head's channels are inside a tile); the per-token one takes a second
+    // pass over the K' images, because a token-wide mean spans every tile of the k part.
+    if (ap->B != 1 || ap->D != 128 || (ap->H & 1) || ap->in_dtype != DIT_BF16 || !self_attn_uses_mfma16(pl.fl) ||
+        pl.fl.resident)
         return DIT_ERR_UNSUPPORTED;
     if (lp->flags != 0 || lp->out_dtype != DIT_BF16) return DIT_ERR_INVALID_ARG;
     if (lp->M != pl.L || lp->N != 3 * (int64_t)ap->H * ap->D || lp->K < 1) return DIT_ERR_INVALID_ARG;
@@ -802,7 +803,7 @@ dit_status dit_qkv_proj_forward(const void* x, const void* w, const void* bias, 
     a.qkv_sq_h = ap->sq.head;
     a.qkv_qk_f16 = pl.fl.qk_op == dit::OP_F16;
     a.qkv_pv_f16 = pl.fl.pv_op == dit::OP_F16;
-    a.qkv_norm = ap->norm.mode == DIT_NORM_HEAD;
+    a.qkv_norm = ap->norm.mode == DIT_NORM_HEAD ? 1 : ap->norm.mode == DIT_NORM_TOKEN ? 2 : 0;
     a.qkv_eps = ap->norm.eps;
     a.qkv_kgamma = ap->norm.k_gamma;
     if ((int64_t)a.nTM * a.nTN > 0x7fffffff) return DIT_ERR_UNSUPPORTED;
@@ -811,6 +812,17 @@ dit_status dit_qkv_proj_forward(const void* x, const void* w, const void* bias, 
     e = dit::launch_linear(a, s);
     if (e != hipSuccess) return hip_fail(e, "linear_kernel");
     if (timed && (e = hipEventRecord(g_ev_after, s)) != hipSuccess) return hip_fail(e, "hipEventRecord");
+    if (ap->norm.mode == DIT_NORM_TOKEN) {
+        dit::KRescaleArgs ra;
+        ra.tiles = a.qkv_tiles;
+        ra.H = ap->H;
+        ra.nKT = pl.nKT;
+        ra.L = (int)pl.L;
+        ra.eps = ap->norm.eps;
+        ra.qk_f16 = a.qkv_qk_f16;
+        e = dit::launch_k_rescale(ra, s);
+        if (e != hipSuccess) return hip_fail(e, "k_rescale_kernel");
+    }
     return DIT_OK;
 }
 

@@ -202,10 +202,23 @@ struct LinearArgs {
     RopeGeom qkv_rg;
     int64_t qkv_sq_t, qkv_sq_h;  // element strides of the q rows in y
     int qkv_qk_f16, qkv_pv_f16;  // operand types of the two tile parts: fp16 (saturating) or bf16
-    int qkv_norm;                // 1: k rows are RMS-normalised over the head's channels before the rotation
+    int qkv_norm;                // 1: k rows are RMS-normalised over the head's channels before the rotation;
+                                 // 2: over all heads of the token -- the weights here, the factor in k_rescale_kernel
     float qkv_eps;
     const float* qkv_kgamma;     // nullable [H*128]
 };
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s);
+
+// Second half of the per-token normalisation of the fused q/k/v projection: the projection's epilogue left, in the
+// spare bytes behind the K' rows of every tile image, one float per key slot = the sum of squares of that token's k
+// row over the head's channels; this pass adds the heads' shares, and multiplies the token's K' rows of all heads by
+// 1/sqrt(sum / (H*D) + eps).
+struct KRescaleArgs {
+    uint8_t* tiles;  // [H, nKT, TILE_BYTES], head_dim 128
+    int H, nKT, L;   // heads, key tiles, tokens
+    float eps;
+    int qk_f16;      // K' rows hold fp16 (else bf16)
+};
+hipError_t launch_k_rescale(const KRescaleArgs& a, hipStream_t s);
 
 }  // namespace dit

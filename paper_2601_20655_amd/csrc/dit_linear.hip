@@ -61,7 +61,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 template <bool OUT_F32, int QKV>
 __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearArgs a) {
-    // QKV: 0 plain rows; 1 the fused q/k/v form; 2 the same with the k rows RMS-normalised per head
+    // QKV: 0 plain rows; 1 the fused q/k/v form; 2 the same with the k rows RMS-normalised per head; 3 with the
+    // per-token normalisation's first half (weights applied, sums of squares left for k_rescale_kernel)
     static_assert(!(OUT_F32 && QKV), "the fused q/k/v form writes 16-bit rows and tiles");
     static_assert(kLinBM == 256 && kLinBN == 256 && kLinBK == 64, "tile shape");
     constexpr int SX = kLinSX, SW = kLinSW, NW = kLinWaves;
@@ -332,7 +333,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
 #pragma unroll
         for (int fb = 0; fb < FB; ++fb) {
             bb[fb] = make_uint2(0u, 0u);
-            if (QKV != 2 && a.bias) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n_wave + fb * BR + 4 * lg);
+            if (QKV < 2 && a.bias) bb[fb] = *reinterpret_cast<const uint2*>(a.bias + n_wave + fb * BR + 4 * lg);
         }
         uint8_t* const region = smem + stage_buf * kLinTileBytes + wave * 4096;
         // RMS normalisation of the k rows over the head's 128 channels, in fp32 on the accumulators (a tile is one
@@ -340,7 +341,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
         // channels and wavefront wave ^ 2 the other 64: pass by pass the two exchange the sums of squares of the
         // pass's 32 tokens through the staging regions (two at a time: the tile stream leaves few registers), and
         // the rows are scaled as they are staged.
-        const bool normed = QKV == 2 && part == 1;
+        const bool normed = QKV >= 2 && part == 1;
         // k and v values pass through bf16 first, as the rows of the plain projection would: what the attention call
         // then computes is, bit for bit, what it computes from those rows
         auto as_bf16_row = [](float& y0, float& y1) __attribute__((always_inline)) {
@@ -348,7 +349,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
             y0 = __uint_as_float(u << 16);
             y1 = __uint_as_float(u & 0xffff0000u);
         };
-        if constexpr (QKV == 2) {
+        if constexpr (QKV >= 2) {
             // (the bias goes into the accumulators first: its registers are needed below)
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) {
@@ -400,8 +401,18 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
 #pragma unroll
-                for (int hh = 0; hh < TBP; ++hh)
-                    rs2[hh] = 1.0f / sqrtf((mine[hh * BR + lr] + theirs[hh * BR + lr]) * (1.0f / 128.0f) + a.qkv_eps);
+                for (int hh = 0; hh < TBP; ++hh) {
+                    const float ssq = mine[hh * BR + lr] + theirs[hh * BR + lr];
+                    if constexpr (QKV == 2) {
+                        rs2[hh] = 1.0f / sqrtf(ssq * (1.0f / 128.0f) + a.qkv_eps);
+                    } else {
+                        // per-token mean: this head's share goes into the spare bytes behind the K' rows of the
+                        // token's tile (one float per key slot), where k_rescale_kernel adds up the heads' shares
+                        const int tok = tok0 + hh * BR + lr;
+                        if (c0 == 0 && lg == 0 && tok < tok_end)
+                            reinterpret_cast<float*>(tiles_h + (size_t)(tok >> 6) * G::TILE_BYTES + kBK * G::KROW)[tok & 63] = ssq;
+                    }
+                }
                 // the partner has read this region before the staging below overwrites it
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
@@ -419,7 +430,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                     const float b0 = __uint_as_float(bb[fb].x << 16), b1 = __uint_as_float(bb[fb].x & 0xffff0000u);
                     const float b2 = __uint_as_float(bb[fb].y << 16), b3 = __uint_as_float(bb[fb].y & 0xffff0000u);
                     float y0 = acc[fb][tb][0], y1 = acc[fb][tb][1], y2 = acc[fb][tb][2], y3 = acc[fb][tb][3];
-                    if constexpr (QKV != 2) {
+                    if constexpr (QKV < 2) {
                         y0 += b0;
                         y1 += b1;
                         y2 += b2;
@@ -434,7 +445,7 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                         y2 *= rs * g.z;
                         y3 *= rs * g.w;
                     }
-                    if (QKV != 2 && part != 0) {
+                    if (QKV < 2 && part != 0) {
                         as_bf16_row(y0, y1);
                         as_bf16_row(y2, y3);
                     }
@@ -645,7 +656,10 @@ hipError_t launch_linear_inst(const LinearArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_linear(const LinearArgs& a, hipStream_t s) {
-    if (a.qkv) return a.qkv_norm ? launch_linear_inst<false, 2>(a, s) : launch_linear_inst<false, 1>(a, s);
+    if (a.qkv) {
+        if (a.qkv_norm == 2) return launch_linear_inst<false, 3>(a, s);
+        return a.qkv_norm ? launch_linear_inst<false, 2>(a, s) : launch_linear_inst<false, 1>(a, s);
+    }
     return a.out_f32 ? launch_linear_inst<true, false>(a, s) : launch_linear_inst<false, false>(a, s);
 }
 

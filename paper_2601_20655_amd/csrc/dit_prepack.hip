@@ -60,6 +60,44 @@ hipError_t launch_token_rstd(const RstdArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+// One workgroup per (tile, head): four lanes a key row, 64 bytes each.
+__global__ void __launch_bounds__(256) k_rescale_kernel(const KRescaleArgs a) {
+    using G = TileGeom<128>;
+    const int h = blockIdx.x % a.H, j = blockIdx.x / a.H;
+    const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
+    const int tok = j * kBK + r;
+    if (tok >= a.L) return;  // slots past the sequence hold zeros and stay as they are
+    float ssq = 0.f;
+    for (int hh = 0; hh < a.H; ++hh)  // in head order, whichever workgroup adds them up: every head's rows get the same factor
+        ssq += reinterpret_cast<const float*>(a.tiles + ((size_t)hh * a.nKT + j) * G::TILE_BYTES + kBK * G::KROW)[r];
+    const float rs = 1.0f / sqrtf(ssq / (float)(a.H * 128) + a.eps);
+    uint8_t* const row = a.tiles + ((size_t)h * a.nKT + j) * G::TILE_BYTES + r * G::KROW + part * 64;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(row + c * 16);
+        float x[8];
+        if (a.qk_f16) {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const f16x2 p = __builtin_bit_cast(f16x2, w[e]);
+                x[2 * e] = (float)p.x;
+                x[2 * e + 1] = (float)p.y;
+            }
+        } else {
+            widen8(v, x);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= rs;
+        *reinterpret_cast<u32x4*>(row + c * 16) = a.qk_f16 ? pack8<OP_F16>(x) : pack8<OP_BF16>(x);
+    }
+}
+
+hipError_t launch_k_rescale(const KRescaleArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(k_rescale_kernel, dim3((unsigned)(a.H * a.nKT)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 // What one workgroup packs: 64 keys of one (batch or request, head).
 struct PackTile {
     uint8_t* dst;        // tile image
