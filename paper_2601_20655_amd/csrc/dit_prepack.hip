@@ -71,10 +71,11 @@ __global__ void __launch_bounds__(256) k_rescale_kernel(const KRescaleArgs a) {
     for (int hh = 0; hh < a.H; ++hh)  // in head order, whichever workgroup adds them up: every head's rows get the same factor
         ssq += reinterpret_cast<const float*>(a.tiles + ((size_t)hh * a.nKT + j) * G::TILE_BYTES + kBK * G::KROW)[r];
     const float rs = 1.0f / sqrtf(ssq / (float)(a.H * 128) + a.eps);
-    uint8_t* const row = a.tiles + ((size_t)h * a.nKT + j) * G::TILE_BYTES + r * G::KROW + part * 64;
+    // chunk 4 c + part: the four lanes of a row move 64 contiguous bytes per instruction
+    uint8_t* const row = a.tiles + ((size_t)h * a.nKT + j) * G::TILE_BYTES + r * G::KROW + part * 16;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(row + c * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(row + c * 64);
         float x[8];
         if (a.qk_f16) {
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -89,8 +90,10 @@ __global__ void __launch_bounds__(256) k_rescale_kernel(const KRescaleArgs a) {
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] *= rs;
-        *reinterpret_cast<u32x4*>(row + c * 16) = a.qk_f16 ? pack8<OP_F16>(x) : pack8<OP_BF16>(x);
+        *reinterpret_cast<u32x4*>(row + c * 64) = a.qk_f16 ? pack8<OP_F16>(x) : pack8<OP_BF16>(x);
     }
+    // the pad behind the row too, so that the pass leaves no sector partly written (see pack_tile)
+    if (part == 3) *reinterpret_cast<u32x4*>(row + 256 - 48) = mk4(0u, 0u, 0u, 0u);
 }
 
 hipError_t launch_k_rescale(const KRescaleArgs& a, hipStream_t s) {
