@@ -60,44 +60,57 @@ hipError_t launch_token_rstd(const RstdArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// One workgroup per (tile, head): four lanes a key row, 64 bytes each.
+// One workgroup per (tile, group of up to kRescaleHeads heads): four lanes a key row.  The lanes of a row first add
+// up the heads' shares of the row's sum of squares, each lane every fourth head and then the four partial sums in a
+// fixed order, so that every workgroup -- whichever heads it then scales -- arrives at the same factor for a token.
+constexpr int kRescaleHeads = 8;
 __global__ void __launch_bounds__(256) k_rescale_kernel(const KRescaleArgs a) {
     using G = TileGeom<128>;
-    const int h = blockIdx.x % a.H, j = blockIdx.x / a.H;
+    const int groups = (a.H + kRescaleHeads - 1) / kRescaleHeads;
+    const int hg = blockIdx.x % groups, j = blockIdx.x / groups;
     const int r = threadIdx.x >> 2, part = threadIdx.x & 3;
     const int tok = j * kBK + r;
-    if (tok >= a.L) return;  // slots past the sequence hold zeros and stay as they are
+    const bool live = tok < a.L;  // slots past the sequence hold zeros and stay as they are
     float ssq = 0.f;
-    for (int hh = 0; hh < a.H; ++hh)  // in head order, whichever workgroup adds them up: every head's rows get the same factor
+    for (int hh = part; hh < a.H; hh += 4)
         ssq += reinterpret_cast<const float*>(a.tiles + ((size_t)hh * a.nKT + j) * G::TILE_BYTES + kBK * G::KROW)[r];
+    ssq += __shfl_xor(ssq, 1);
+    ssq += __shfl_xor(ssq, 2);
     const float rs = 1.0f / sqrtf(ssq / (float)(a.H * 128) + a.eps);
-    // chunk 4 c + part: the four lanes of a row move 64 contiguous bytes per instruction
-    uint8_t* const row = a.tiles + ((size_t)h * a.nKT + j) * G::TILE_BYTES + r * G::KROW + part * 16;
+    if (!live) return;
+    const int h_end = (hg + 1) * kRescaleHeads < a.H ? (hg + 1) * kRescaleHeads : a.H;
+    for (int h = hg * kRescaleHeads; h < h_end; ++h) {
+        // chunk 4 c + part: the four lanes of a row move 64 contiguous bytes per instruction
+        uint8_t* const row = a.tiles + ((size_t)h * a.nKT + j) * G::TILE_BYTES + r * G::KROW + part * 16;
+        u32x4 v[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(row + c * 64);
-        float x[8];
-        if (a.qk_f16) {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        for (int c = 0; c < 4; ++c) v[c] = *reinterpret_cast<const u32x4*>(row + c * 64);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const f16x2 p = __builtin_bit_cast(f16x2, w[e]);
-                x[2 * e] = (float)p.x;
-                x[2 * e + 1] = (float)p.y;
+        for (int c = 0; c < 4; ++c) {
+            float x[8];
+            if (a.qk_f16) {
+                const uint32_t w[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f16x2 p = __builtin_bit_cast(f16x2, w[e]);
+                    x[2 * e] = (float)p.x;
+                    x[2 * e + 1] = (float)p.y;
+                }
+            } else {
+                widen8(v[c], x);
             }
-        } else {
-            widen8(v, x);
-        }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= rs;
-        *reinterpret_cast<u32x4*>(row + c * 64) = a.qk_f16 ? pack8<OP_F16>(x) : pack8<OP_BF16>(x);
+            for (int e = 0; e < 8; ++e) x[e] *= rs;
+            *reinterpret_cast<u32x4*>(row + c * 64) = a.qk_f16 ? pack8<OP_F16>(x) : pack8<OP_BF16>(x);
+        }
+        // the pad behind the row too, so that the pass leaves no sector partly written (see pack_tile)
+        if (part == 3) *reinterpret_cast<u32x4*>(row + 256 - 48) = mk4(0u, 0u, 0u, 0u);
     }
-    // the pad behind the row too, so that the pass leaves no sector partly written (see pack_tile)
-    if (part == 3) *reinterpret_cast<u32x4*>(row + 256 - 48) = mk4(0u, 0u, 0u, 0u);
 }
 
 hipError_t launch_k_rescale(const KRescaleArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL(k_rescale_kernel, dim3((unsigned)(a.H * a.nKT)), dim3(256), 0, s, a);
+    const int groups = (a.H + kRescaleHeads - 1) / kRescaleHeads;
+    hipLaunchKernelGGL(k_rescale_kernel, dim3((unsigned)(groups * a.nKT)), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
