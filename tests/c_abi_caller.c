@@ -1,5 +1,6 @@
 /* A C99 caller of the library's C ABI, with no Python and no C++ in between: device buffers from the
- * HIP runtime's C API, one self-attention and one masked cross-attention through include/dit_attn.h,
+ * HIP runtime's C API, one self-attention, one masked cross-attention, one projection and the fused q/k/v projection
+ * route through include/dit_attn.h,
  * results compared with the CPU oracle (oracle/dit_oracle.c, linked in) to the parity bar.
  * Built by paper_2601_20655_amd/build.py (build_c_caller), run by tests/test_gpu_c_caller.py. */
 #define __HIP_PLATFORM_AMD__ 1
@@ -214,6 +215,76 @@ int main(void)
         if (dit_linear_forward(dx, dw, db, dy, &p, NULL) != DIT_ERR_UNSUPPORTED) return 1;
         hipFree(dx); hipFree(dw); hipFree(db); hipFree(dy);
         free(x); free(w); free(b); free(y); free(ref);
+    }
+    /* ---- q/k/v projection that writes the attention's tile images, then attention on them: bit for bit the
+     * result of the separate calls (projection with bf16 output, attention on the q, k, v columns of that output) ---- */
+    {
+        const int32_t H = 2, D = 128, K = 128, grid[3] = {3, 7, 11}, split[3] = {44, 42, 42};
+        const int64_t L = 3 * 7 * 11, HD = (int64_t)H * D, N = 3 * HD;
+        uint16_t *x = make_bf16((size_t)L * K), *w = make_bf16((size_t)N * K), *b = make_bf16((size_t)N);
+        /* weights of the size a projection has, so that q and k stay of order one */
+        for (size_t i = 0; i < (size_t)N * K; ++i) {
+            uint32_t u = (uint32_t)w[i] << 16;
+            float f;
+            memcpy(&f, &u, 4);
+            f *= 0.09f;
+            memcpy(&u, &f, 4);
+            w[i] = (uint16_t)(u >> 16);
+        }
+        void *dx = to_device(x, (size_t)L * K * 2), *dw = to_device(w, (size_t)N * K * 2), *db = to_device(b, (size_t)N * 2);
+        void *dy = to_device(NULL, (size_t)L * N * 2), *dqo = to_device(NULL, (size_t)L * HD * 2);
+        void *o1 = to_device(NULL, (size_t)L * HD * 4), *o2 = to_device(NULL, (size_t)L * HD * 4);
+        if (!dx || !dw || !db || !dy || !dqo || !o1 || !o2) return 2;
+        dit_self_attn_params ap;
+        memset(&ap, 0, sizeof(ap));
+        ap.B = 1; ap.H = H; ap.D = D;
+        ap.T = grid[0]; ap.Hg = grid[1]; ap.Wg = grid[2];
+        ap.d_t = split[0]; ap.d_h = split[1]; ap.d_w = split[2];
+        ap.rope_base = 10000.0f;
+        ap.in_dtype = DIT_BF16; ap.out_dtype = DIT_F32;
+        dit_strides dense = {L * HD, HD, D};
+        ap.sq = ap.sk = ap.sv = ap.so = dense;
+        size_t ws_bytes = dit_attn_workspace_bytes(&ap);
+        void *ws = to_device(NULL, ws_bytes), *ws2 = to_device(NULL, ws_bytes);
+        if (!ws || !ws2) return 2;
+        dit_linear_params lp;
+        memset(&lp, 0, sizeof(lp));
+        lp.M = (int32_t)L; lp.N = (int32_t)N; lp.K = K; lp.ldx = K; lp.ldw = K; lp.ldy = N; lp.out_dtype = DIT_BF16;
+        dit_status st = dit_qkv_proj_forward(dx, dw, db, dqo, &lp, &ap, ws, ws_bytes, NULL);
+        if (st != DIT_OK) {
+            fprintf(stderr, "dit_qkv_proj_forward: %s %s\n", dit_strerror(st), dit_last_hip_error());
+            return 1;
+        }
+        dit_self_attn_params ar = ap;
+        ar.flags |= DIT_FLAG_KV_RESIDENT;
+        st = dit_attn_forward(dqo, NULL, NULL, o1, NULL, &ar, ws, ws_bytes, NULL);
+        if (st != DIT_OK) {
+            fprintf(stderr, "dit_attn_forward on resident tiles: %s %s\n", dit_strerror(st), dit_last_hip_error());
+            return 1;
+        }
+        /* the separate route: rows of [q | k | v] with a token stride of 3 H D */
+        st = dit_linear_forward(dx, dw, db, dy, &lp, NULL);
+        if (st != DIT_OK) return 1;
+        dit_self_attn_params as = ap;
+        dit_strides cols = {L * N, N, D};
+        as.sq = as.sk = as.sv = cols;
+        st = dit_attn_forward(dy, (uint16_t *)dy + HD, (uint16_t *)dy + 2 * HD, o2, NULL, &as, ws2, ws_bytes, NULL);
+        if (st != DIT_OK) {
+            fprintf(stderr, "dit_attn_forward on projected rows: %s %s\n", dit_strerror(st), dit_last_hip_error());
+            return 1;
+        }
+        CHECK_HIP(hipDeviceSynchronize());
+        float *h1 = (float *)malloc((size_t)L * HD * 4), *h2 = (float *)malloc((size_t)L * HD * 4);
+        CHECK_HIP(hipMemcpy(h1, o1, (size_t)L * HD * 4, hipMemcpyDeviceToHost));
+        CHECK_HIP(hipMemcpy(h2, o2, (size_t)L * HD * 4, hipMemcpyDeviceToHost));
+        double sq = 0.0;
+        for (size_t i = 0; i < (size_t)L * HD; ++i) sq += (double)h1[i] * h1[i];
+        const int same = memcmp(h1, h2, (size_t)L * HD * 4) == 0;
+        printf("fused q/k/v projection + attention: %s the separate calls (output RMS %.3e)\n",
+               same ? "bit for bit" : "DIFFERS from", sqrt(sq / (double)(L * HD)));
+        if (!same || !(sq > 0.0)) return 1;
+        hipFree(dx); hipFree(dw); hipFree(db); hipFree(dy); hipFree(dqo); hipFree(o1); hipFree(o2); hipFree(ws); hipFree(ws2);
+        free(x); free(w); free(b); free(h1); free(h2);
     }
     printf("c caller ok\n");
     return 0;
