@@ -257,6 +257,8 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
         uint8_t* const region = smem + stage_buf * kLinTileBytes + wave * 4096;
         const int rrow = lane / PR, rp = lane % PR;
         const int n = tn * kLinBN + wf * BR * FB + rp * (16 / ES);
+        // (16-bit output only: with fp32 output the extra path costs the step loop a register)
+        const bool full = !OUT_F32 && (tm + 1) * kLinBM <= a.M && (tn + 1) * kLinBN <= a.N;  // uniform
 #pragma unroll
         for (int pass = 0; pass < TB / TBP; ++pass) {
 #pragma unroll
@@ -285,16 +287,33 @@ __global__ void __launch_bounds__(64 * kLinWaves, 1) linear_kernel(const LinearA
                 if (m < a.M && n < a.N)
                     *reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.y) + ((int64_t)m * a.ldy + n) * ES) = v;
             };
-            // (two at a time: the loop around this leaves few registers free)
-            {
-                const uint4 v0 = staged(0), v1 = staged(1);
-                put(0, v0);
-                put(1, v1);
-            }
-            {
-                const uint4 v2 = staged(2), v3 = staged(3);
-                put(2, v2);
-                put(3, v3);
+            if (full) {
+                // a tile inside y stores without tests, and all four pieces of the pass are read back before the
+                // first is stored (behind a test each read sits in a branch of its own and is waited for there)
+                u32x4 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int row = k * (64 / PR) + rrow;
+                    v[k] = *reinterpret_cast<const u32x4*>(region + row * RB + ((rp ^ (row & (PR - 1))) << 4));
+                }
+                asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3])::"memory");
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int m = tm * kLinBM + wt * BR * TB + pass * RP + k * (64 / PR) + rrow;
+                    *reinterpret_cast<u32x4*>(static_cast<uint8_t*>(a.y) + ((int64_t)m * a.ldy + n) * ES) = v[k];
+                }
+            } else {
+                // (two at a time: the loop around this leaves few registers free)
+                {
+                    const uint4 v0 = staged(0), v1 = staged(1);
+                    put(0, v0);
+                    put(1, v1);
+                }
+                {
+                    const uint4 v2 = staged(2), v3 = staged(3);
+                    put(2, v2);
+                    put(3, v3);
+                }
             }
         }
         // (zeroed here, not as they are staged: the registers of staged accumulators serve as temporaries)
