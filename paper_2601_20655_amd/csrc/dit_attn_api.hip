@@ -378,9 +378,9 @@ dit_status plan_cross(const dit_cross_attn_params* p, CrossPlan* pl) {
     // Default for one joint softmax: the pipelined 16x16x32 kernel, each workgroup chaining several query tiles.
     // The plain kernel serves the decoupled form and DIT_FLAG_SIMPLE_SCHEDULE (also with DIT_FLAG_MFMA_32X32
     // or 64 rows per wavefront); DIT_FLAG_PIPELINED_SCHEDULE asks for the listed 32x32x16 pipelined kernel.
-    // (the chained kernel takes 16-bit query rows as they are: fp32 rows or a normalisation go to the plain kernel)
+    // (the chained kernel takes 16-bit query rows, normalised or not: fp32 rows go to the plain kernel)
     pl->chain16 = pl->split == 0 && !pl->fl.simple && !pl->fl.pipelined && !pl->fl.mfma32 && pl->fl.qb == 1 &&
-                  p->in_dtype == DIT_BF16 && p->norm.mode == DIT_NORM_NONE;
+                  p->in_dtype == DIT_BF16;
     if (!pl->fl.pipelined && !pl->chain16) pl->fl.simple = true;
     if (pl->chain16) {
         if (pl->fl.nw == 0) pl->fl.nw = (int64_t)((p->Lq + 255) / 256) * p->B * p->H >= 512 ? 8 : 4;

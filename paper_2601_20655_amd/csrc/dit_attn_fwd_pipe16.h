@@ -509,19 +509,45 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
 
     int vs_run = 0;  // chained: the V^T buffer of the stream's current step
     const int n_qt = CHAIN ? pv.qt_count : 1;
-    // chained form: the rows in this wavefront's area -> operand registers.  It takes 16-bit query rows as they
-    // are (the host sends anything else -- fp32 rows, a normalisation, a rotation -- to the other kernels):
-    // nothing here but widen, scale, round.
-    auto convert_q_area = [&]() {
+    // chained form: the rows of query tile `qtile` in this wavefront's area -> operand registers.  It takes 16-bit
+    // query rows (the host sends fp32 rows and rotations to the other kernels): widen, normalise if asked to, scale,
+    // round.  A row's four lanes (i, 0..3) hold its channels; the per-head statistic is their sum, the per-token one
+    // comes from the table.
+    auto convert_q_area = [&](int qtile) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the copy into the area (long done, except at the start)
         const int ln = opaque_lane();
+        auto chunk = [&](int qb, int ks, float x[8]) {
+            const int r = 16 * qb + (ln & 15);
+            widen8(*reinterpret_cast<const u32x4*>(qarea + r * (D * 2) + (((4 * ks + (ln >> 4)) ^ (r & (QPR - 1))) << 4)), x);
+        };
+        float rs[2] = {1.f, 1.f};
+        if (a.qn.mode == 2) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const int row = qtile * BQ + wave * 32 + 16 * qb + (ln & 15);
+                rs[qb] = a.qn.rstd[pv.stat_off + (row < pv.Lq ? row : pv.Lq - 1)];
+            }
+        } else if (a.qn.mode == 1) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                float ss = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    float x[8];
+                    chunk(qb, ks, x);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+                }
+                rs[qb] = 1.0f / sqrtf(sum_across_rows16(ss) * (1.0f / D) + a.qn.eps);
+            }
+        }
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
                 float x[8];
-                const int r = 16 * qb + (ln & 15);
-                widen8(*reinterpret_cast<const u32x4*>(qarea + r * (D * 2) + (((4 * ks + (ln >> 4)) ^ (r & (QPR - 1))) << 4)), x);
+                chunk(qb, ks, x);
+                if (a.qn.mode) norm8(x, a.qn, rs[qb], pv.h, D, 4 * ks + (ln >> 4));
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[e] *= a.qscale;
                 Qf[qb][ks] = pack8<QK_OP>(x);
@@ -531,7 +557,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
     if constexpr (CHAIN) {
         // the operands of this query tile were converted at the end of the one before; its area is free for
         // the rows of the next one, which arrive while this one is in its loop
-        if (it == 0) convert_q_area();
+        if (it == 0) convert_q_area(qt);
         else reset_state();
         if (it + 1 < n_qt) request_q(qt + 1);
     }
@@ -696,7 +722,7 @@ __device__ __forceinline__ void attn_pipe16_body(const AttnArgs& a, const PipeVi
             }
         };
         // the next query tile's operands out of the area, then the area is the staging area
-        if (it + 1 < n_qt) convert_q_area();
+        if (it + 1 < n_qt) convert_q_area(qt + 1);
         if (a.out_f32) stage_and_store(std::integral_constant<int, 4>());
         else stage_and_store(std::integral_constant<int, 2>());
     } else {

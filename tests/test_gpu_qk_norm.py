@@ -72,6 +72,31 @@ def test_cross_attention_normed(mode, split):
 
 
 @pytest.mark.parametrize("mode", ["head", "token"])
+@pytest.mark.parametrize("big", [False, True])
+def test_cross_attention_normed_chained_query_tiles(mode, big):
+    """Normalised q and k on the chained kernel with enough query tiles that a workgroup takes two or three in a row
+    (the operands of the NEXT query tile are normalised at the boundary, with the next tile's row factors) and a ragged
+    last query tile; four- and eight-wavefront forms; sampled rows of every request against the oracle."""
+    import torch
+
+    Lq = 256 * 150 + 37 if big else 128 * 201 + 37
+    cfg = dict(wl.CONFIGS["cross_14b"], B=4, Lq=Lq, H=6, n_text=150, n_image=42, min_text=5, seed=91)
+    q, k, v, valid, _ = wl.cross_attn_inputs(cfg)
+    gq, gk = wl.norm_weights(cfg)
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(Lq - 300, Lq),
+                                     np.random.default_rng(5).integers(0, Lq, 400)]))
+    qn = oracle.qk_rmsnorm(np.ascontiguousarray(q[:, rows]), gq, EPS, mode)
+    kn = oracle.qk_rmsnorm(k, gk, EPS, mode)
+    ref = oracle.cross_attn(qn, kn, oracle.as_f64(v), valid)
+    flags = B.DIT_FLAG_BIG_WORKGROUP if big else B.DIT_FLAG_SMALL_WORKGROUP
+    out = B.dit_cross_attn_forward(to_dev(q), to_dev(k), to_dev(v), to_dev(valid), out_dtype=torch.float32,
+                                   flags=flags, norm=dev_norm(mode, gq, gk))
+    torch.cuda.synchronize()
+    got = to_f64(out[:, torch.from_numpy(rows).cuda()])
+    compare(got, ref, what="chained cross normed %s, %d wavefronts" % (mode, 8 if big else 4))
+
+
+@pytest.mark.parametrize("mode", ["head", "token"])
 def test_packed_requests_normed(mode):
     import torch
 
