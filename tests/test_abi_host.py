@@ -452,3 +452,19 @@ def test_static_workspace_rejects_what_does_not_fit():
     p.D = 96
     st = B.lib().dit_cross_attn_forward_static(fake, fake, fake, None, fake, None, ctypes.byref(p), None)
     assert st == B.DIT_ERR_UNSUPPORTED
+
+
+def test_counter_summary_is_of_this_library_version():
+    """bench.py reports the measured HBM traffic of the headline kernel only when the counter summary under
+    profiles/ names the version of the library that runs: a summary left behind by an older version would turn the
+    figure into null without anybody noticing."""
+    import importlib.util
+    import os
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    traffic = bench.traffic_bytes_for(B.dit_attn_version())
+    assert traffic is not None and 1e9 < traffic < 1e10
+    assert bench.traffic_bytes_for(B.dit_attn_version() + 1) is None
