@@ -168,6 +168,10 @@ def other_workload(args):
         return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
 
     H, D = cfg.get("H"), cfg.get("D")
+    norm = None
+    if args.norm and cfg["kind"] in ("self", "cross"):
+        gq, gk = wl.norm_weights(cfg)
+        norm = (args.norm, 1e-6, torch.from_numpy(gq.reshape(-1)).cuda(), torch.from_numpy(gk.reshape(-1)).cuda())
     if cfg["kind"] == "linear":
         x, w, b = (dev(a) for a in wl.linear_inputs(cfg))
         out = torch.empty((cfg["M"], cfg["N"]), dtype=torch.bfloat16, device="cuda")
@@ -217,16 +221,18 @@ def other_workload(args):
         q, k, v = (dev(a) for a in wl.self_attn_inputs(cfg))
         out = torch.empty_like(q)
         ws = torch.empty(B.dit_attn_workspace_bytes(B.self_attn_params(q, k, v, out, cfg["grid"], cfg["split"],
-                                                                        flags=args.flags)),
+                                                                        flags=args.flags, norm=norm)),
                          dtype=torch.uint8, device="cuda")
         L = q.shape[1]
         flops = 4.0 * cfg["B"] * H * L * L * D
         what = "self-attention, grid %dx%dx%d = %d tokens, %d heads, d%d" % (cfg["grid"] + (L, H, D))
+        if norm:
+            what += ", q and k RMS-normalised per %s" % args.norm
         kernel = "attn_fwd_pipe16_kernel"
 
         def call():
             B.dit_attn_forward(q, k, v, cfg["grid"], cfg["split"], out=out, flags=args.flags, workspace=ws,
-                               stream=stream)
+                               stream=stream, norm=norm)
     elif cfg["kind"] == "varlen":
         q, k, v = (dev(a) for a in wl.varlen_attn_inputs(cfg))
         out = torch.empty_like(q)
@@ -248,7 +254,7 @@ def other_workload(args):
         out = torch.empty_like(q)
         split = cfg["n_text"] if args.decoupled else 0
         ws = torch.empty(B.dit_cross_attn_workspace_bytes(B.cross_attn_params(q, k, v, out, flags=args.flags,
-                                                                               split=split)),
+                                                                               split=split, norm=norm)),
                          dtype=torch.uint8, device="cuda")
         Lq = q.shape[1]
         flops = 4.0 * H * Lq * D * float(valid.sum())  # keys that attend; padded keys are skipped, not computed
@@ -264,14 +270,16 @@ def other_workload(args):
         kv_len = torch.tensor([[int(t), cfg["n_image"]] for t in text_len], dtype=torch.int32, device="cuda")
         if args.key_counts:
             what += ", keys given as counts"
+        if norm:
+            what += ", q and k RMS-normalised per %s" % args.norm
 
         def call():
             if args.key_counts:
                 B.dit_cross_attn_forward_lengths(q, k, v, kv_len, cfg["n_text"], out=out, flags=args.flags,
-                                                 workspace=ws, stream=stream, split=split)
+                                                 workspace=ws, stream=stream, split=split, norm=norm)
             else:
                 B.dit_cross_attn_forward(q, k, v, vd, out=out, flags=args.flags, workspace=ws, stream=stream,
-                                         split=split)
+                                         split=split, norm=norm)
 
     if args.flags & B.DIT_FLAG_KV_RESIDENT:  # the timed calls reuse what one ordinary call packs first
         resident = args.flags
@@ -354,6 +362,8 @@ def main():
     ap.add_argument("--fused-qkv", action="store_true",
                     help="qkv_attn_14b: dit_qkv_proj_forward (the projection writes the attention's tile images) and "
                          "the attention call on them, instead of two separate calls")
+    ap.add_argument("--norm", choices=["head", "token"], default=None,
+                    help="self- and cross-attention workloads: fused RMS normalisation of q and k (weights 1 + 0.25 N(0,1))")
     ap.add_argument("--key-counts", action="store_true",
                     help="cross_14b: dit_cross_attn_forward_lengths (two key counts per request) instead of the byte mask")
     args = ap.parse_args()
